@@ -1,0 +1,405 @@
+"""CPU oracle for the geometry-aware cached token merge around global attention.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the HIP
+path is checked against.  Only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import it; the product path never does.
+It shares no code with the HIP path and imports nothing from it.
+
+Everything is numpy in float64 (inputs are the stored values, widened).  Each
+function follows one passage of the paper (LiteVGGT, arXiv 2512.04939), cited in
+its docstring; where the paper is silent the chosen reading is stated in the
+docstring.  No blocking, fusion or re-ordering beyond what the definition says.
+
+Pins (tests/test_oracle_*.py, all CPU): closed forms for the Sobel/variance maps,
+scipy.ndimage routines for the filters, a sparse averaging matrix for the merge,
+torch's scaled_dot_product_attention for the attention core, pure-Python brute
+force for selection and matching, the paper's recompute-count table for the
+cache schedule.  The ratio -> (cell size, number of GA tokens) rule is a
+definition of this build, not of the paper: **parity unpinned** for that rule
+beyond its own closed-form counts.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+ROLE_PROTECTED = 0   # camera/register tokens and GA tokens: kept, never merged into
+ROLE_DST = 1         # merge anchors
+ROLE_SRC = 2         # merged into their most similar anchor
+
+
+@dataclass(frozen=True)
+class Params:
+    frames: int
+    grid_h: int
+    grid_w: int
+    n_special: int = 5          # Sec. 3.1: 1 camera + 4 register tokens per frame
+    dim: int = 1024
+    heads: int = 16
+    head_dim: int = 64
+    patch: int = 14
+    merge_ratio: float = 0.9    # < 0 selects the paper's fixed rule (Sec. 3.4)
+    ga_frac: float = 0.10       # Sec. 3.4 "GA Tokens": top 10 % per frame
+    alpha: float = 0.5          # Sec. 3.4 fusion weights (paper gives no values)
+    beta: float = 0.5
+    var_pool: int = 3           # window of the local average pooling (paper silent)
+    refresh_interval: int = 6   # Sec. 3.4 "Cached Token Merging"
+
+    @property
+    def patches(self) -> int:
+        return self.grid_h * self.grid_w
+
+    @property
+    def tokens_per_frame(self) -> int:
+        return self.patches + self.n_special
+
+    @property
+    def n_tokens(self) -> int:
+        return self.frames * self.tokens_per_frame
+
+
+# ---------------------------------------------------------------------------
+# size planning (closed form)
+# ---------------------------------------------------------------------------
+def plan(p: Params) -> Dict[str, int]:
+    """Token counts implied by the partition rule of Sec. 3.4 "GA Token Partitioning".
+
+    Paper rule (merge_ratio < 0): cell = 2, n_ga = floor(ga_frac * P).
+    Ratio rule (this build's extension): per non-first frame n_src = floor(r*P),
+    K = P - n_src tokens are kept; the cell side is the smallest s >= 2 whose
+    ceil(H/s)*ceil(W/s) cells fit into K; the K - n_dst remaining kept tokens are
+    GA tokens.  r = 0 keeps everything.
+    """
+    P = p.patches
+    if p.merge_ratio < 0:
+        cell = 2
+        n_dst = -(-p.grid_h // cell) * -(-p.grid_w // cell)
+        n_ga = int(np.floor(p.ga_frac * P + 1e-9))
+        n_ga = min(n_ga, P - n_dst)
+        n_src = P - n_dst - n_ga
+    else:
+        n_src = int(np.floor(p.merge_ratio * P + 1e-9))
+        K = P - n_src
+        if n_src == 0:
+            cell, n_dst, n_ga = 1, P, 0
+        else:
+            if K < 1:
+                raise ValueError("merge ratio leaves no anchor per frame")
+            cell = 2
+            while -(-p.grid_h // cell) * -(-p.grid_w // cell) > K:
+                cell += 1
+            n_dst = -(-p.grid_h // cell) * -(-p.grid_w // cell)
+            n_ga = K - n_dst
+    K = n_dst + n_ga
+    F, S = p.frames, p.n_special
+    return dict(N=p.n_tokens, M=S * F + P + (F - 1) * K, cell=cell,
+                n_dst_per_frame=n_dst, n_ga_per_frame=n_ga, n_src_per_frame=n_src,
+                n_dst=P + (F - 1) * n_dst, n_src=(F - 1) * n_src)
+
+
+# ---------------------------------------------------------------------------
+# step 1: geometry-aware map  (Sec. 3.4 "Geometry-aware Feature Map")
+# ---------------------------------------------------------------------------
+def luma(images: np.ndarray) -> np.ndarray:
+    """[F,3,Hi,Wi] RGB in [0,1] -> [F,Hi,Wi] intensity (Rec.601 weights; paper silent)."""
+    im = np.asarray(images, dtype=np.float64)
+    return 0.299 * im[:, 0] + 0.587 * im[:, 1] + 0.114 * im[:, 2]
+
+
+def sobel_magnitude(gray: np.ndarray) -> np.ndarray:
+    """Sobel gradient magnitude (horizontal and vertical intensity change) of
+    [F,Hi,Wi] images, 3x3 un-normalised kernels, border pixels replicated."""
+    g = np.pad(np.asarray(gray, dtype=np.float64), ((0, 0), (1, 1), (1, 1)), mode="edge")
+    Hi, Wi = gray.shape[1], gray.shape[2]
+    gx = np.zeros_like(gray, dtype=np.float64)
+    gy = np.zeros_like(gray, dtype=np.float64)
+    kx = [[-1.0, 0.0, 1.0], [-2.0, 0.0, 2.0], [-1.0, 0.0, 1.0]]
+    for a in range(3):
+        for b in range(3):
+            win = g[:, a:a + Hi, b:b + Wi]
+            gx += kx[a][b] * win
+            gy += kx[b][a] * win          # vertical kernel = transpose
+    return np.sqrt(gx * gx + gy * gy)
+
+
+def grad_map(images: np.ndarray, patch: int) -> np.ndarray:
+    """Psi_g: Sobel magnitude "downsampled to token granularity" = mean over each
+    patch x patch pixel block.  [F,3,Hi,Wi] -> [F,H,W]."""
+    mag = sobel_magnitude(luma(images))
+    F, Hi, Wi = mag.shape
+    if Hi % patch or Wi % patch:
+        raise ValueError("image size must be a multiple of the patch size")
+    return mag.reshape(F, Hi // patch, patch, Wi // patch, patch).mean(axis=(2, 4))
+
+
+def var_map(x: np.ndarray, p: Params) -> np.ndarray:
+    """Psi_v: tokens rearranged into their 2-D grid, "local average-pooled variance":
+    per channel, var = avgpool(x^2) - avgpool(x)^2 over a centred var_pool x var_pool
+    window (stride 1, windows clipped at the border average over in-grid cells only),
+    clamped at 0, then averaged over channels.  x [N,C] -> [F,H,W].  Patch tokens only."""
+    F, H, W, S, C = p.frames, p.grid_h, p.grid_w, p.n_special, x.shape[1]
+    g = np.asarray(x, dtype=np.float64).reshape(F, p.tokens_per_frame, C)[:, S:, :]
+    g = g.reshape(F, H, W, C)
+    r = p.var_pool // 2
+    out = np.zeros((F, H, W), dtype=np.float64)
+    for i in range(H):
+        i0, i1 = max(0, i - r), min(H, i + r + 1)
+        for j in range(W):
+            j0, j1 = max(0, j - r), min(W, j + r + 1)
+            win = g[:, i0:i1, j0:j1, :].reshape(F, -1, C)
+            mu = win.mean(axis=1)
+            nu = (win * win).mean(axis=1)
+            out[:, i, j] = np.maximum(nu - mu * mu, 0.0).mean(axis=1)
+    return out
+
+
+def minmax_norm(m: np.ndarray) -> np.ndarray:
+    """norm(.) of the fusion formula: per-frame min-max to [0,1]; a flat frame -> 0."""
+    F = m.shape[0]
+    flat = m.reshape(F, -1)
+    lo = flat.min(axis=1, keepdims=True)
+    hi = flat.max(axis=1, keepdims=True)
+    rng = hi - lo
+    out = np.where(rng > 0, (flat - lo) / np.where(rng > 0, rng, 1.0), 0.0)
+    return out.reshape(m.shape)
+
+
+def ga_map(psi_g: np.ndarray, psi_v: np.ndarray, p: Params) -> np.ndarray:
+    """Psi_GA = alpha * norm(Psi_g) + beta * norm(Psi_v)  (Sec. 3.4, fusion formula)."""
+    return p.alpha * minmax_norm(psi_g) + p.beta * minmax_norm(psi_v)
+
+
+def importance(images: np.ndarray, x: np.ndarray, p: Params,
+               psi_g: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Score [F,P] (float64) and the gradient map it used (cacheable: images only)."""
+    if psi_g is None:
+        psi_g = grad_map(images, p.patch)
+    score = ga_map(psi_g, var_map(x, p), p)
+    return score.reshape(p.frames, p.patches), psi_g
+
+
+# ---------------------------------------------------------------------------
+# step 2: partition into GA / dst / src  (Sec. 3.4 "GA Token Partitioning")
+# ---------------------------------------------------------------------------
+def select_anchors(score: np.ndarray, p: Params) -> Dict[str, np.ndarray]:
+    """Roles per token.  score [F,P]; comparisons are made on the values given
+    (callers pass float32-representable scores so both sides decide on equal keys).
+
+    * special tokens of every frame: PROTECTED;
+    * frame 0: every patch token is DST;
+    * other frames: the grid is tiled from (0,0) by cell x cell blocks (edge blocks
+      clipped); in each block the lowest-scoring token becomes DST (ties: lowest
+      token index); then the n_ga highest-scoring of the remaining patch tokens are
+      GA tokens = PROTECTED (ties: lowest index); the rest are SRC.
+    """
+    pl = plan(p)
+    F, H, W, S, P, T = p.frames, p.grid_h, p.grid_w, p.n_special, p.patches, p.tokens_per_frame
+    cell, n_ga = pl["cell"], pl["n_ga_per_frame"]
+    sc = np.asarray(score).reshape(F, H, W)
+    role = np.zeros(F * T, dtype=np.uint8)
+    for f in range(F):
+        base = f * T + S
+        if f == 0 or pl["n_src_per_frame"] == 0:
+            role[base:base + P] = ROLE_DST
+            continue
+        fr = np.full(P, ROLE_SRC, dtype=np.uint8)
+        for ci in range(0, H, cell):
+            for cj in range(0, W, cell):
+                best, best_t = None, -1
+                for i in range(ci, min(H, ci + cell)):
+                    for j in range(cj, min(W, cj + cell)):
+                        v = sc[f, i, j]
+                        if best is None or v < best:
+                            best, best_t = v, i * W + j
+                fr[best_t] = ROLE_DST
+        rest = [t for t in range(P) if fr[t] != ROLE_DST]
+        flat = sc[f].reshape(P)
+        rest.sort(key=lambda t: (-flat[t], t))
+        for t in rest[:n_ga]:
+            fr[t] = ROLE_PROTECTED
+        role[base:base + P] = fr
+    idx = np.arange(F * T, dtype=np.int64)
+    return dict(role=role,
+                kept_idx=idx[role != ROLE_SRC].astype(np.int32),
+                dst_idx=idx[role == ROLE_DST].astype(np.int32),
+                src_idx=idx[role == ROLE_SRC].astype(np.int32))
+
+
+# ---------------------------------------------------------------------------
+# step 3: cosine matching  (Sec. 3.4 "Cached Token Merging", first sentence)
+# ---------------------------------------------------------------------------
+def inv_norms(x: np.ndarray) -> np.ndarray:
+    n = np.sqrt((np.asarray(x, dtype=np.float64) ** 2).sum(axis=1))
+    return 1.0 / np.maximum(n, 1e-12)
+
+
+def match(x: np.ndarray, dst_idx: np.ndarray, src_idx: np.ndarray,
+          rows: Optional[np.ndarray] = None, block: int = 2048,
+          ) -> Dict[str, np.ndarray]:
+    """For every src token the most cosine-similar dst token among ALL frames' dst.
+
+    cos = <x_s, x_d> / (|x_s| |x_d|) in float64, then rounded to float32; the
+    decision is taken on the float32 values, ties -> the lowest dst token index.
+    ``rows`` optionally restricts the computation to positions in src_idx.
+    Returns anchor (original token index per src), best/second float64 similarity
+    (second = best over the other candidates, for near-tie accounting).
+    """
+    xd = np.asarray(x[dst_idx], dtype=np.float64)
+    invd = inv_norms(xd)
+    sel = np.arange(len(src_idx)) if rows is None else np.asarray(rows)
+    anchor = np.empty(len(sel), dtype=np.int32)
+    best = np.empty(len(sel), dtype=np.float64)
+    second = np.full(len(sel), -np.inf, dtype=np.float64)
+    for b0 in range(0, len(sel), block):
+        s = src_idx[sel[b0:b0 + block]]
+        xs = np.asarray(x[s], dtype=np.float64)
+        sim = (xs @ xd.T) * inv_norms(xs)[:, None] * invd[None, :]
+        sim32 = sim.astype(np.float32)
+        j = np.argmax(sim32, axis=1)                    # first maximum = lowest dst index
+        r = np.arange(len(s))
+        anchor[b0:b0 + len(s)] = dst_idx[j]
+        best[b0:b0 + len(s)] = sim[r, j]
+        if sim.shape[1] > 1:
+            sim[r, j] = -np.inf
+            second[b0:b0 + len(s)] = sim.max(axis=1)
+    return dict(anchor=anchor, best=best, second=second)
+
+
+def build_index(role: np.ndarray, src_idx: np.ndarray, src_anchor: np.ndarray,
+                ) -> Dict[str, np.ndarray]:
+    """Merge index: anchor_of[N] (self for kept tokens), slot_of[N] (position of the
+    anchor among kept tokens in ascending original order), CSR groups with members
+    in ascending original order."""
+    N = len(role)
+    anchor_of = np.arange(N, dtype=np.int32)
+    anchor_of[src_idx] = src_anchor
+    kept = np.flatnonzero(role != ROLE_SRC).astype(np.int32)
+    slot_of_kept = np.full(N, -1, dtype=np.int64)
+    slot_of_kept[kept] = np.arange(len(kept))
+    slot_of = slot_of_kept[anchor_of].astype(np.int32)
+    order = np.argsort(slot_of, kind="stable").astype(np.int32)
+    counts = np.bincount(slot_of, minlength=len(kept))
+    group_off = np.zeros(len(kept) + 1, dtype=np.int32)
+    group_off[1:] = np.cumsum(counts)
+    return dict(anchor_of=anchor_of, slot_of=slot_of, kept_idx=kept,
+                group_off=group_off, group_mem=order)
+
+
+# ---------------------------------------------------------------------------
+# steps 4-6: merge, attention, unmerge
+# ---------------------------------------------------------------------------
+def merge(x: np.ndarray, group_off: np.ndarray, group_mem: np.ndarray) -> np.ndarray:
+    """x_d' = (x_d + sum_{s in S_d} x_s) / (1 + |S_d|)  (Sec. 3.4 merge equation);
+    kept tokens without sources pass through.  Returns float64 [M,C]."""
+    M = len(group_off) - 1
+    xf = np.asarray(x, dtype=np.float64)
+    z = np.empty((M, x.shape[1]), dtype=np.float64)
+    for m in range(M):
+        mem = group_mem[group_off[m]:group_off[m + 1]]
+        z[m] = xf[mem].sum(axis=0) / len(mem)
+    return z
+
+
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: Optional[float] = None,
+              rows: Optional[np.ndarray] = None, block: int = 1024) -> np.ndarray:
+    """Full (unmasked) self-attention per head over the whole sequence (Sec. 3.1
+    "Bottleneck Analysis"): O = softmax(Q K^T * scale) V, scale = 1/sqrt(head_dim).
+    q,k,v [M,h,d]; returns float64 [M,h,d] (or [len(rows),h,d])."""
+    qf, kf, vf = (np.asarray(a, dtype=np.float64) for a in (q, k, v))
+    M, h, d = kf.shape
+    sc = 1.0 / np.sqrt(d) if scale is None else float(scale)
+    sel = np.arange(qf.shape[0]) if rows is None else np.asarray(rows)
+    out = np.empty((len(sel), h, d), dtype=np.float64)
+    for hh in range(h):
+        kh, vh = kf[:, hh, :], vf[:, hh, :]
+        for b0 in range(0, len(sel), block):
+            r = sel[b0:b0 + block]
+            s = (qf[r, hh, :] @ kh.T) * sc
+            s -= s.max(axis=1, keepdims=True)
+            e = np.exp(s)
+            out[b0:b0 + len(r), hh, :] = (e @ vh) / e.sum(axis=1, keepdims=True)
+    return out
+
+
+def unmerge(y: np.ndarray, slot_of: np.ndarray, residual: Optional[np.ndarray] = None,
+            ) -> np.ndarray:
+    """Every token of a group receives its anchor's merged row (Sec. 3.4 "Token
+    Unmerging"); optionally adds a per-token residual stream."""
+    out = np.asarray(y, dtype=np.float64)[slot_of]
+    if residual is not None:
+        out = out + np.asarray(residual, dtype=np.float64)
+    return out
+
+
+# ---------------------------------------------------------------------------
+# storage rounding used by the layer chain
+# ---------------------------------------------------------------------------
+def round_bf16(a: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding of float64/float32 values to bfloat16, as float64."""
+    f = np.asarray(a, dtype=np.float32)
+    u = f.view(np.uint32)
+    r = ((u >> 16) & 1) + np.uint32(0x7FFF)
+    return (((u + r) >> 16) << 16).astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def round_e4m3(a: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding to FP8 E4M3 (OCP "FN": bias 7, max 448, no inf),
+    saturating; subnormals with step 2^-9.  Returns float64."""
+    v = np.asarray(a, dtype=np.float64)
+    s = np.sign(v)
+    m = np.minimum(np.abs(v), 448.0)
+    e = np.floor(np.log2(np.where(m > 0, m, 1.0)))
+    e = np.maximum(e, -6.0)
+    step = np.exp2(e - 3.0)
+    q = np.rint(m / step) * step          # rint = ties to even
+    return s * np.minimum(q, 448.0)
+
+
+# ---------------------------------------------------------------------------
+# cached-index layer driver  (Sec. 3.4: indices recomputed every refresh_interval layers)
+# ---------------------------------------------------------------------------
+def refresh_schedule(n_layers: int, interval: int) -> List[int]:
+    return [1 if (l % interval) == 0 else 0 for l in range(n_layers)]
+
+
+def compute_index(images, x, p: Params, psi_g=None, score_dtype=np.float32):
+    """importance -> select -> match -> CSR; returns (index dict, psi_g, score, match)."""
+    score, psi_g = importance(images, x, p, psi_g)
+    score = score.astype(score_dtype)
+    sel = select_anchors(score, p)
+    if len(sel["src_idx"]):
+        mt = match(x, sel["dst_idx"], sel["src_idx"])
+    else:
+        mt = dict(anchor=np.empty(0, np.int32), best=np.empty(0), second=np.empty(0))
+    idx = build_index(sel["role"], sel["src_idx"], mt["anchor"])
+    idx.update(role=sel["role"], dst_idx=sel["dst_idx"], src_idx=sel["src_idx"])
+    return idx, psi_g, score, mt
+
+
+def global_layer(x: np.ndarray, idx: Dict[str, np.ndarray], p: Params,
+                 store=lambda a: a) -> np.ndarray:
+    """One merged global layer: x + U(Attn(M(x))) with Q = K = V = merged tokens viewed
+    as [M, heads, head_dim] (no projections: the paper does not describe them).
+    ``store`` models the storage rounding applied to z, y and the output."""
+    z = store(merge(x, idx["group_off"], idx["group_mem"]))
+    zz = z.reshape(z.shape[0], p.heads, p.head_dim)
+    y = store(attention(zz, zz, zz).reshape(z.shape))
+    return store(unmerge(y, idx["slot_of"], residual=x))
+
+
+def layers_run(images: np.ndarray, x: np.ndarray, p: Params, n_layers: int,
+               store=lambda a: a, trace: Optional[list] = None):
+    """Run n_layers merged global layers, recomputing the merge index when
+    layer % refresh_interval == 0 (the gradient map only once)."""
+    x = np.asarray(x, dtype=np.float64)
+    psi_g, idx = None, None
+    log = refresh_schedule(n_layers, p.refresh_interval)
+    for l in range(n_layers):
+        if log[l]:
+            idx, psi_g, _, _ = compute_index(images, x, p, psi_g)
+        if trace is not None:
+            trace.append(dict(layer=l, x_in=x, index=idx))
+        x = global_layer(x, idx, p, store)
+    return x, log
