@@ -1,0 +1,178 @@
+/*
+ * litevggt.h -- C ABI of the MI355X (gfx950) implementation of LiteVGGT's hot path:
+ * geometry-aware cached token merging wrapped around VGGT's frame-global
+ * self-attention (LiteVGGT, arXiv 2512.04939, Sec. 3.4).
+ *
+ * Conventions (every entry point):
+ *   - returns 0 (LV_OK) or a negative LV_ERR_* code; litevggt_strerror() names it.
+ *     Arguments are validated on the host before anything is launched; on an error
+ *     nothing has been enqueued.
+ *   - pointers marked [device] are device memory owned by the caller; the library
+ *     never allocates, frees or keeps them.  Pointers marked [host] are host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only
+ *     enqueue work; they never synchronise.  Kernel faults surface at the caller's
+ *     next synchronisation.
+ *   - token order: frame-major; inside a frame the n_special camera/register tokens
+ *     come first, then the grid_h*grid_w patch tokens row-major.  N = frames*(P+S).
+ *   - features are bf16 (raw 16-bit patterns), row-major [tokens, dim], rows 16-byte
+ *     aligned; indices are int32; scores are fp32.
+ *   - inputs are never written; outputs must not overlap inputs unless stated.
+ *   - `ws` is scratch device memory of at least the size the matching *_ws_bytes /
+ *     litevggt_plan reports, 256-byte aligned; its contents are undefined afterwards.
+ */
+#ifndef LITEVGGT_H
+#define LITEVGGT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  LV_OK = 0,
+  LV_ERR_NULL = -1,       /* a required pointer is NULL                          */
+  LV_ERR_SHAPE = -2,      /* sizes inconsistent or unsupported                    */
+  LV_ERR_PARAM = -3,      /* hyper-parameter out of range                         */
+  LV_ERR_WORKSPACE = -4,  /* ws too small or misaligned                           */
+  LV_ERR_DTYPE = -5,      /* unsupported dtype selector                           */
+  LV_ERR_HIP = -6         /* a HIP runtime call failed (launch error)             */
+};
+
+enum { LV_IMG_F32 = 0, LV_IMG_U8 = 1 };        /* image element type              */
+enum { LV_ATTN_BF16 = 0, LV_ATTN_FP8_E4M3 = 1 }; /* attention MFMA operand type   */
+enum { LV_ROLE_PROTECTED = 0, LV_ROLE_DST = 1, LV_ROLE_SRC = 2 };
+
+/* Shape and hyper-parameters (host memory). */
+typedef struct {
+  int32_t frames;          /* F                                                    */
+  int32_t grid_h, grid_w;  /* patch grid; P = grid_h*grid_w                        */
+  int32_t n_special;       /* camera + register tokens per frame (Sec. 3.1: 5)     */
+  int32_t dim;             /* C = heads*head_dim, multiple of 64                   */
+  int32_t heads;
+  int32_t head_dim;        /* must be 64                                           */
+  int32_t patch;           /* pixels per patch side (14); image = grid*patch       */
+  int32_t img_dtype;       /* LV_IMG_F32 ([0,1]) or LV_IMG_U8 ([0,255])            */
+  int32_t var_pool;        /* window of the local variance pooling (3), odd        */
+  int32_t refresh_interval;/* layers between merge-index recomputations (6)        */
+  int32_t attn_dtype;      /* LV_ATTN_BF16 or LV_ATTN_FP8_E4M3                     */
+  float   alpha, beta;     /* weights of the gradient and variance maps            */
+  float   softmax_scale;   /* <= 0 selects 1/sqrt(head_dim)                        */
+  double  merge_ratio;     /* r in [0,1): fraction of patch tokens per non-first
+                              frame that become src; < 0 selects the paper's fixed
+                              rule (top ga_frac GA tokens, one dst per 2x2 cell)   */
+  double  ga_frac;         /* 0.10; used only when merge_ratio < 0                 */
+} litevggt_params;
+
+/* Token counts that follow from the parameters (closed form, Sec. 3.4 partition). */
+typedef struct {
+  int64_t N;               /* tokens in the sequence                               */
+  int64_t M;               /* tokens after merging                                 */
+  int64_t n_dst, n_src;    /* totals over all frames                               */
+  int32_t cell;            /* side of the grid cell that yields one dst token      */
+  int32_t n_dst_per_frame, n_ga_per_frame, n_src_per_frame; /* frames 1..F-1       */
+  size_t  ws_bytes;        /* scratch that covers every call below at these sizes
+                              with n_tokens <= M for litevggt_global_attn          */
+} litevggt_plan_t;
+
+/* The cached merge index: caller-owned device buffers, filled by
+ * litevggt_select_anchors (role, kept_idx, dst_idx, src_idx, and the entries of
+ * anchor_of/slot_of that belong to kept tokens) and litevggt_match (the rest). */
+typedef struct {
+  uint8_t *role;           /* [N]   LV_ROLE_*                                      */
+  int32_t *kept_idx;       /* [M]   token index of merged slot m, ascending        */
+  int32_t *dst_idx;        /* [n_dst] ascending                                    */
+  int32_t *src_idx;        /* [n_src] ascending                                    */
+  int32_t *anchor_of;      /* [N]   token index of the token's anchor (self if kept)*/
+  int32_t *slot_of;        /* [N]   merged slot of the token's anchor              */
+  int32_t *group_off;      /* [M+1] CSR offsets into group_mem                     */
+  int32_t *group_mem;      /* [N]   members of each slot, ascending inside a slot  */
+} litevggt_index;
+
+const char *litevggt_strerror(int code);
+
+/* Host only.  Validates the parameters and fills the closed-form counts. */
+int litevggt_plan(const litevggt_params *p, litevggt_plan_t *out /*[host]*/);
+
+/* Scratch needed by litevggt_global_attn for a sequence of n_tokens (host only). */
+size_t litevggt_attn_ws_bytes(const litevggt_params *p, int64_t n_tokens);
+
+/* Step 1, Sec. 3.4 "Geometry-aware Feature Map": score = alpha*norm(Psi_g) +
+ * beta*norm(Psi_v).  Psi_g = Sobel gradient magnitude of the luma image (3x3
+ * kernels, replicated border) averaged over each patch; Psi_v = variance of the
+ * patch tokens over a var_pool x var_pool grid neighbourhood (clipped at the grid
+ * border), averaged over channels; norm = per-frame min-max (a flat map -> 0).
+ *   images     [device] [F,3,grid_h*patch,grid_w*patch] img_dtype; may be NULL when
+ *              recompute_grad == 0
+ *   x          [device] [N,dim] bf16 tokens entering the layer
+ *   grad_cache [device] [F,P] fp32, written when recompute_grad != 0, else read
+ *   score      [device] [F,P] fp32 out
+ */
+int litevggt_importance(const litevggt_params *p, const void *images, const void *x,
+                        float *grad_cache, int recompute_grad, float *score,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/* Step 2, Sec. 3.4 "GA Token Partitioning".  Special tokens: PROTECTED.  Frame 0:
+ * every patch token DST.  Other frames: in every cell x cell block of the grid the
+ * lowest-scoring token is DST (ties: lowest index); of the remaining patch tokens
+ * the n_ga_per_frame highest-scoring are PROTECTED GA tokens (ties: lowest index);
+ * the rest are SRC.  Scores are compared as fp32 (-0 == +0); NaN scores give an
+ * unspecified but valid partition.  Writes role, kept_idx, dst_idx, src_idx and,
+ * for kept tokens, anchor_of[i] = i and slot_of[i] = position in kept_idx.
+ *   score [device] [F,P] fp32
+ */
+int litevggt_select_anchors(const litevggt_params *p, const float *score,
+                            litevggt_index *index, void *stream);
+
+/* Step 3, Sec. 3.4 "Cached Token Merging": every SRC token is assigned the DST token
+ * (of any frame) with the largest cosine similarity of the full dim-vectors; the
+ * decision is taken on fp32 similarities, ties go to the lowest token index.
+ * Fills anchor_of/slot_of for SRC tokens and builds group_off/group_mem.
+ * Requires the outputs of litevggt_select_anchors in `index`.
+ *   best_sim [device] [n_src] fp32 similarity of each src (order of src_idx), or NULL
+ */
+int litevggt_match(const litevggt_params *p, const void *x, litevggt_index *index,
+                   float *best_sim, void *ws, size_t ws_bytes, void *stream);
+
+/* Step 4, Sec. 3.4 merge equation: z[m] = mean of x over the members of slot m
+ * (fp32 sum in ascending token order, one rounding to bf16).
+ *   x [device] [N,dim] bf16;  z [device] [M,dim] bf16 out
+ */
+int litevggt_merge(const litevggt_params *p, const void *x, const litevggt_index *index,
+                   void *z, void *stream);
+
+/* Step 5, Sec. 3.1 "Bottleneck Analysis": unmasked self-attention over the whole
+ * sequence, per head: O = softmax(Q K^T * softmax_scale) V.
+ *   q,k,v [device] [n_tokens, heads, 64] bf16 (row stride dim); o likewise, out.
+ *   n_tokens = M for the merged path, N for the unmerged baseline.
+ * attn_dtype LV_ATTN_FP8_E4M3 quantises q,k,v per tensor (scale = amax/448) and the
+ * softmax weights to e4m3 for the MFMAs; accumulation and softmax stay fp32.
+ */
+int litevggt_global_attn(const litevggt_params *p, int64_t n_tokens, const void *q,
+                         const void *k, const void *v, void *o,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/* Step 6, Sec. 3.4 "Token Unmerging": out[i] = y[slot_of[i]] (+ residual[i]).
+ *   y [device] [M,dim] bf16; residual [device] [N,dim] bf16 or NULL;
+ *   out [device] [N,dim] bf16, may be the same buffer as residual.
+ */
+int litevggt_unmerge(const litevggt_params *p, const void *y, const litevggt_index *index,
+                     const void *residual, void *out, void *stream);
+
+/* Cached-index layer driver, Sec. 3.4: for layer l = 0..n_layers-1, recompute the
+ * merge index (steps 1-3; the gradient map only at l = 0) when
+ * l % refresh_interval == 0, then x <- x + unmerge(attn(merge(x))) with
+ * Q = K = V = the merged tokens viewed as [M, heads, 64].
+ *   x           [device] [N,dim] bf16, in/out
+ *   grad_cache, score [device] [F,P] fp32 scratch/outputs of the last refresh
+ *   refresh_log [host] [n_layers] set to 1 where the index was recomputed, or NULL
+ */
+int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *images,
+                        void *x, litevggt_index *index, float *grad_cache, float *score,
+                        int32_t *refresh_log, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LITEVGGT_H */

@@ -1,0 +1,214 @@
+"""ctypes binding of liblitevggt.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/litevggt.h) and passes
+torch tensors' device pointers and the current HIP stream.  There is no CPU fallback: a
+missing library raises at import of the symbols, a failing call raises ``LiteVGGTError``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "liblitevggt.so")
+
+IMG_F32, IMG_U8 = 0, 1
+ATTN_BF16, ATTN_FP8_E4M3 = 0, 1
+ROLE_PROTECTED, ROLE_DST, ROLE_SRC = 0, 1, 2
+
+EXPORTS = ["litevggt_strerror", "litevggt_plan", "litevggt_attn_ws_bytes", "litevggt_importance",
+           "litevggt_select_anchors", "litevggt_match", "litevggt_merge", "litevggt_global_attn",
+           "litevggt_unmerge", "litevggt_layers_run"]
+
+
+class LiteVGGTError(RuntimeError):
+    pass
+
+
+class Params(C.Structure):
+    """Mirror of ``litevggt_params``."""
+    _fields_ = [("frames", C.c_int32), ("grid_h", C.c_int32), ("grid_w", C.c_int32),
+                ("n_special", C.c_int32), ("dim", C.c_int32), ("heads", C.c_int32),
+                ("head_dim", C.c_int32), ("patch", C.c_int32), ("img_dtype", C.c_int32),
+                ("var_pool", C.c_int32), ("refresh_interval", C.c_int32),
+                ("attn_dtype", C.c_int32), ("alpha", C.c_float), ("beta", C.c_float),
+                ("softmax_scale", C.c_float), ("merge_ratio", C.c_double),
+                ("ga_frac", C.c_double)]
+
+
+class Plan(C.Structure):
+    """Mirror of ``litevggt_plan_t``."""
+    _fields_ = [("N", C.c_int64), ("M", C.c_int64), ("n_dst", C.c_int64), ("n_src", C.c_int64),
+                ("cell", C.c_int32), ("n_dst_per_frame", C.c_int32),
+                ("n_ga_per_frame", C.c_int32), ("n_src_per_frame", C.c_int32),
+                ("ws_bytes", C.c_size_t)]
+
+
+class Index(C.Structure):
+    """Mirror of ``litevggt_index`` (device pointers)."""
+    _fields_ = [("role", C.c_void_p), ("kept_idx", C.c_void_p), ("dst_idx", C.c_void_p),
+                ("src_idx", C.c_void_p), ("anchor_of", C.c_void_p), ("slot_of", C.c_void_p),
+                ("group_off", C.c_void_p), ("group_mem", C.c_void_p)]
+
+
+def make_params(frames, grid_h, grid_w, dim, heads, *, head_dim=64, n_special=5, patch=14,
+                img_dtype=IMG_F32, var_pool=3, refresh_interval=6, attn_dtype=ATTN_BF16,
+                alpha=0.5, beta=0.5, softmax_scale=0.0, merge_ratio=0.9, ga_frac=0.10) -> Params:
+    return Params(frames, grid_h, grid_w, n_special, dim, heads, head_dim, patch, img_dtype,
+                  var_pool, refresh_interval, attn_dtype, alpha, beta, softmax_scale,
+                  merge_ratio, ga_frac)
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise LiteVGGTError(f"{LIB_PATH} not found: run paper_2512_04939_amd/build.py "
+                                "(or __graft_entry__.build()) first; there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        vp, sz, i32, i64 = C.c_void_p, C.c_size_t, C.c_int, C.c_int64
+        PP = C.POINTER(Params)
+        L.litevggt_strerror.restype = C.c_char_p
+        L.litevggt_strerror.argtypes = [i32]
+        L.litevggt_plan.argtypes = [PP, C.POINTER(Plan)]
+        L.litevggt_attn_ws_bytes.restype = sz
+        L.litevggt_attn_ws_bytes.argtypes = [PP, i64]
+        L.litevggt_importance.argtypes = [PP, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.litevggt_select_anchors.argtypes = [PP, vp, C.POINTER(Index), vp]
+        L.litevggt_match.argtypes = [PP, vp, C.POINTER(Index), vp, vp, sz, vp]
+        L.litevggt_merge.argtypes = [PP, vp, C.POINTER(Index), vp, vp]
+        L.litevggt_global_attn.argtypes = [PP, i64, vp, vp, vp, vp, vp, sz, vp]
+        L.litevggt_unmerge.argtypes = [PP, vp, C.POINTER(Index), vp, vp, vp]
+        L.litevggt_layers_run.argtypes = [PP, i32, vp, vp, C.POINTER(Index), vp, vp,
+                                          C.POINTER(C.c_int32), vp, sz, vp]
+        for name in EXPORTS[1:]:
+            if name != "litevggt_attn_ws_bytes":
+                getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise LiteVGGTError(f"{what} failed: {lib().litevggt_strerror(rc).decode()} ({rc})")
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def litevggt_strerror(code: int) -> str:
+    return lib().litevggt_strerror(code).decode()
+
+
+def litevggt_plan(p: Params) -> Plan:
+    out = Plan()
+    _check(lib().litevggt_plan(C.byref(p), C.byref(out)), "litevggt_plan")
+    return out
+
+
+def litevggt_attn_ws_bytes(p: Params, n_tokens: int) -> int:
+    return int(lib().litevggt_attn_ws_bytes(C.byref(p), n_tokens))
+
+
+@dataclass
+class IndexBuffers:
+    """Device tensors backing a ``litevggt_index`` (allocated by torch, owned by the caller)."""
+    role: "object"
+    kept_idx: "object"
+    dst_idx: "object"
+    src_idx: "object"
+    anchor_of: "object"
+    slot_of: "object"
+    group_off: "object"
+    group_mem: "object"
+
+    def struct(self) -> Index:
+        return Index(*(t.data_ptr() for t in (self.role, self.kept_idx, self.dst_idx, self.src_idx,
+                                              self.anchor_of, self.slot_of, self.group_off,
+                                              self.group_mem)))
+
+
+def alloc_index(pl: Plan, device="cuda") -> IndexBuffers:
+    import torch
+    i32 = dict(dtype=torch.int32, device=device)
+    return IndexBuffers(
+        role=torch.empty(pl.N, dtype=torch.uint8, device=device),
+        kept_idx=torch.empty(pl.M, **i32), dst_idx=torch.empty(max(pl.n_dst, 1), **i32),
+        src_idx=torch.empty(max(pl.n_src, 1), **i32), anchor_of=torch.empty(pl.N, **i32),
+        slot_of=torch.empty(pl.N, **i32), group_off=torch.empty(pl.M + 1, **i32),
+        group_mem=torch.empty(pl.N, **i32))
+
+
+def alloc_ws(nbytes: int, device="cuda"):
+    import torch
+    return torch.empty(max(int(nbytes), 256) + 256, dtype=torch.uint8, device=device)
+
+
+def _ws_args(ws):
+    """256-byte aligned pointer and usable size of a uint8 workspace tensor."""
+    if ws is None:
+        return None, 0
+    base = ws.data_ptr()
+    aligned = (base + 255) // 256 * 256
+    return aligned, ws.numel() - (aligned - base)
+
+
+def litevggt_importance(p: Params, images, x, grad_cache, recompute_grad: bool, score, ws) -> None:
+    wp, wn = _ws_args(ws)
+    _check(lib().litevggt_importance(C.byref(p), _ptr(images), _ptr(x), _ptr(grad_cache),
+                                     1 if recompute_grad else 0, _ptr(score), wp, wn, _stream()),
+           "litevggt_importance")
+
+
+def litevggt_select_anchors(p: Params, score, index: IndexBuffers) -> None:
+    ix = index.struct()
+    _check(lib().litevggt_select_anchors(C.byref(p), _ptr(score), C.byref(ix), _stream()),
+           "litevggt_select_anchors")
+
+
+def litevggt_match(p: Params, x, index: IndexBuffers, best_sim, ws) -> None:
+    ix = index.struct()
+    wp, wn = _ws_args(ws)
+    _check(lib().litevggt_match(C.byref(p), _ptr(x), C.byref(ix), _ptr(best_sim), wp, wn, _stream()),
+           "litevggt_match")
+
+
+def litevggt_merge(p: Params, x, index: IndexBuffers, z) -> None:
+    ix = index.struct()
+    _check(lib().litevggt_merge(C.byref(p), _ptr(x), C.byref(ix), _ptr(z), _stream()),
+           "litevggt_merge")
+
+
+def litevggt_global_attn(p: Params, n_tokens: int, q, k, v, o, ws) -> None:
+    wp, wn = _ws_args(ws)
+    _check(lib().litevggt_global_attn(C.byref(p), n_tokens, _ptr(q), _ptr(k), _ptr(v), _ptr(o),
+                                      wp, wn, _stream()), "litevggt_global_attn")
+
+
+def litevggt_unmerge(p: Params, y, index: IndexBuffers, residual, out) -> None:
+    ix = index.struct()
+    _check(lib().litevggt_unmerge(C.byref(p), _ptr(y), C.byref(ix), _ptr(residual), _ptr(out),
+                                  _stream()), "litevggt_unmerge")
+
+
+def litevggt_layers_run(p: Params, n_layers: int, images, x, index: IndexBuffers, grad_cache,
+                        score, ws):
+    ix = index.struct()
+    wp, wn = _ws_args(ws)
+    log = (C.c_int32 * max(n_layers, 1))()
+    _check(lib().litevggt_layers_run(C.byref(p), n_layers, _ptr(images), _ptr(x), C.byref(ix),
+                                     _ptr(grad_cache), _ptr(score), log, wp, wn, _stream()),
+           "litevggt_layers_run")
+    return list(log)[:n_layers]

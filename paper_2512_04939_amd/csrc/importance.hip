@@ -1,0 +1,208 @@
+// Geometry-aware map (Sec. 3.4 "Geometry-aware Feature Map"): Sobel gradient map,
+// local token-variance map, per-frame min-max normalisation and fusion.
+// All three kernels are HBM-bound streaming passes; arithmetic is fp32.
+#include "common.h"
+#include "internal.h"
+
+namespace lv {
+
+// ---------------------------------------------------------------------------------
+// Psi_g.  One workgroup per (frame, patch row): the patch+2 luma rows it needs are
+// built once in LDS (border pixels replicated), then each wave reduces whole patches.
+// ---------------------------------------------------------------------------------
+template <typename PixT>
+__global__ __launch_bounds__(256) void k_grad_map(const PixT *__restrict__ img, int H, int W,
+                                                  int patch, float *__restrict__ psi_g) {
+  extern __shared__ float luma[];            // [(patch+2)][Wi+2]
+  const int Hi = H * patch, Wi = W * patch, LW = Wi + 2;
+  const int f = blockIdx.x / H, ph = blockIdx.x % H;
+  const size_t plane = (size_t)Hi * Wi;
+  const PixT *base = img + (size_t)f * 3 * plane;
+  const float unit = sizeof(PixT) == 1 ? (1.0f / 255.0f) : 1.0f;
+  for (int i = threadIdx.x; i < (patch + 2) * LW; i += blockDim.x) {
+    int rr = i / LW, cc = i - rr * LW;
+    int y = min(max(ph * patch + rr - 1, 0), Hi - 1);
+    int x = min(max(cc - 1, 0), Wi - 1);
+    size_t o = (size_t)y * Wi + x;
+    float r = (float)base[o] * unit, g = (float)base[plane + o] * unit,
+          b = (float)base[2 * plane + o] * unit;
+    luma[i] = 0.299f * r + 0.587f * g + 0.114f * b;
+  }
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+  const int pp = patch * patch;
+  for (int pw = wave; pw < W; pw += nw) {
+    float acc = 0.f;
+    for (int i = lane; i < pp; i += 64) {
+      int py = i / patch, px = i - py * patch;
+      const float *c = luma + (py + 1) * LW + pw * patch + px + 1;
+      float tl = c[-LW - 1], tc = c[-LW], tr = c[-LW + 1];
+      float ml = c[-1], mr = c[1];
+      float bl = c[LW - 1], bc = c[LW], br = c[LW + 1];
+      float gx = (tr + 2.f * mr + br) - (tl + 2.f * ml + bl);
+      float gy = (bl + 2.f * bc + br) - (tl + 2.f * tc + tr);
+      acc += sqrtf(gx * gx + gy * gy);
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) psi_g[((size_t)f * H + ph) * W + pw] = acc / (float)pp;
+  }
+}
+
+int launch_grad_map(const void *images, int img_dtype, const Dims &d, int patch, float *psi_g,
+                    hipStream_t st) {
+  size_t lds = (size_t)(patch + 2) * (d.W * patch + 2) * sizeof(float);
+  if (lds > 64 * 1024) return LV_ERR_SHAPE;
+  dim3 grid((unsigned)(d.F * d.H));
+  if (img_dtype == LV_IMG_F32)
+    hipLaunchKernelGGL(k_grad_map<float>, grid, dim3(256), lds, st, (const float *)images, d.H,
+                       d.W, patch, psi_g);
+  else
+    hipLaunchKernelGGL(k_grad_map<uint8_t>, grid, dim3(256), lds, st, (const uint8_t *)images,
+                       d.H, d.W, patch, psi_g);
+  LV_HIP_CHECK_LAUNCH();
+  return LV_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// Psi_v.  One workgroup per (frame, grid row); thread t owns channels 4t..4t+3 (+1024k).
+// For every grid column the K x K neighbourhood (clipped) is loaded into registers,
+// mean and mean squared deviation are taken per channel, summed over channels.
+// Workgroups of consecutive grid rows are placed on the same XCD so the two
+// neighbouring rows they share are found in that XCD's L2.
+// ---------------------------------------------------------------------------------
+template <int K>
+__global__ __launch_bounds__(256) void k_var_map(const uint16_t *__restrict__ x, int F, int H,
+                                                 int W, int S, int C, float *__restrict__ psi_v) {
+  extern __shared__ float part[];            // [W][4 waves]
+  const uint32_t nblk = (uint32_t)F * H;
+  const uint32_t lb = xcd_contiguous(blockIdx.x, nblk);
+  if (lb >= nblk) return;
+  const int f = lb / H, i = lb % H;
+  constexpr int R = K / 2;
+  const int T = H * W + S;
+  const uint16_t *frame = x + ((size_t)f * T + S) * C;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i0 = max(i - R, 0), i1 = min(i + R, H - 1);
+  for (int j = 0; j < W; ++j) {
+    const int j0 = max(j - R, 0), j1 = min(j + R, W - 1);
+    const float inv_cnt = 1.0f / (float)((i1 - i0 + 1) * (j1 - j0 + 1));
+    float tot = 0.f;
+    for (int c0 = threadIdx.x * 4; c0 < C; c0 += 1024) {
+      float v[K * K][4];
+      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+      for (int a = 0; a < K; ++a) {
+#pragma unroll
+        for (int b = 0; b < K; ++b) {
+          int ii = i - R + a, jj = j - R + b;
+          bool ok = ii >= i0 && ii <= i1 && jj >= j0 && jj <= j1;
+          u32x2 w = {0u, 0u};
+          if (ok) w = *(const u32x2 *)(frame + ((size_t)ii * W + jj) * C + c0);
+          // cells outside the grid hold 0 and are excluded from the deviation pass below
+          v[a * K + b][0] = bf16_lo(w.x);
+          v[a * K + b][1] = bf16_hi(w.x);
+          v[a * K + b][2] = bf16_lo(w.y);
+          v[a * K + b][3] = bf16_hi(w.y);
+          s0 += v[a * K + b][0];
+          s1 += v[a * K + b][1];
+          s2 += v[a * K + b][2];
+          s3 += v[a * K + b][3];
+        }
+      }
+      const float m0 = s0 * inv_cnt, m1 = s1 * inv_cnt, m2 = s2 * inv_cnt, m3 = s3 * inv_cnt;
+      float q = 0.f;
+#pragma unroll
+      for (int a = 0; a < K; ++a) {
+#pragma unroll
+        for (int b = 0; b < K; ++b) {
+          int ii = i - R + a, jj = j - R + b;
+          bool ok = ii >= i0 && ii <= i1 && jj >= j0 && jj <= j1;
+          float d0 = v[a * K + b][0] - m0, d1 = v[a * K + b][1] - m1;
+          float d2 = v[a * K + b][2] - m2, d3 = v[a * K + b][3] - m3;
+          float e = d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
+          q += ok ? e : 0.f;
+        }
+      }
+      tot += q * inv_cnt;
+    }
+    tot = wave_sum(tot);
+    if (lane == 0) part[j * 4 + wave] = tot;
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < W; j += blockDim.x) {
+    float t = ((part[j * 4] + part[j * 4 + 1]) + part[j * 4 + 2]) + part[j * 4 + 3];
+    psi_v[((size_t)f * H + i) * W + j] = t / (float)C;
+  }
+}
+
+int launch_var_map(const uint16_t *x, const Dims &d, int pool, float *psi_v, hipStream_t st) {
+  dim3 grid((unsigned)(align_up((size_t)d.F * d.H, kXcd)));
+  size_t lds = (size_t)d.W * 4 * sizeof(float);
+  switch (pool) {
+    case 1:
+      hipLaunchKernelGGL(k_var_map<1>, grid, dim3(256), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
+      break;
+    case 3:
+      hipLaunchKernelGGL(k_var_map<3>, grid, dim3(256), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
+      break;
+    case 5:
+      hipLaunchKernelGGL(k_var_map<5>, grid, dim3(256), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
+      break;
+    default:
+      return LV_ERR_PARAM;
+  }
+  LV_HIP_CHECK_LAUNCH();
+  return LV_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// Fusion: one workgroup per frame finds min/max of both maps, then writes
+// alpha*norm(Psi_g) + beta*norm(Psi_v).
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_ga_fuse(const float *__restrict__ psi_g,
+                                                 const float *__restrict__ psi_v, int P,
+                                                 float alpha, float beta,
+                                                 float *__restrict__ score) {
+  __shared__ float red[4][4];
+  const float *g = psi_g + (size_t)blockIdx.x * P, *v = psi_v + (size_t)blockIdx.x * P;
+  float glo = INFINITY, ghi = -INFINITY, vlo = INFINITY, vhi = -INFINITY;
+  for (int t = threadIdx.x; t < P; t += blockDim.x) {
+    float a = g[t], b = v[t];
+    glo = fminf(glo, a);
+    ghi = fmaxf(ghi, a);
+    vlo = fminf(vlo, b);
+    vhi = fmaxf(vhi, b);
+  }
+  glo = wave_min(glo);
+  ghi = wave_max(ghi);
+  vlo = wave_min(vlo);
+  vhi = wave_max(vhi);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (lane == 0) {
+    red[wave][0] = glo;
+    red[wave][1] = ghi;
+    red[wave][2] = vlo;
+    red[wave][3] = vhi;
+  }
+  __syncthreads();
+  glo = fminf(fminf(red[0][0], red[1][0]), fminf(red[2][0], red[3][0]));
+  ghi = fmaxf(fmaxf(red[0][1], red[1][1]), fmaxf(red[2][1], red[3][1]));
+  vlo = fminf(fminf(red[0][2], red[1][2]), fminf(red[2][2], red[3][2]));
+  vhi = fmaxf(fmaxf(red[0][3], red[1][3]), fmaxf(red[2][3], red[3][3]));
+  const float gr = ghi - glo, vr = vhi - vlo;
+  for (int t = threadIdx.x; t < P; t += blockDim.x) {
+    float ng = gr > 0.f ? (g[t] - glo) / gr : 0.f;
+    float nv = vr > 0.f ? (v[t] - vlo) / vr : 0.f;
+    score[(size_t)blockIdx.x * P + t] = alpha * ng + beta * nv;
+  }
+}
+
+int launch_ga_fuse(const float *psi_g, const float *psi_v, const Dims &d, float alpha, float beta,
+                   float *score, hipStream_t st) {
+  hipLaunchKernelGGL(k_ga_fuse, dim3((unsigned)d.F), dim3(256), 0, st, psi_g, psi_v, d.P, alpha,
+                     beta, score);
+  LV_HIP_CHECK_LAUNCH();
+  return LV_OK;
+}
+
+}  // namespace lv

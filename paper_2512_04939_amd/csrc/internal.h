@@ -1,0 +1,47 @@
+// Host-side launch functions of the kernel files; the C ABI in api.hip calls these
+// after validating arguments.  All pointers are device pointers unless noted.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/litevggt.h"
+
+namespace lv {
+
+struct Dims {
+  int F, H, W, S, C, heads, P, T;
+  int64_t N;
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// importance.hip
+int launch_grad_map(const void *images, int img_dtype, const Dims &d, int patch, float *psi_g,
+                    hipStream_t st);
+int launch_var_map(const uint16_t *x, const Dims &d, int pool, float *psi_v, hipStream_t st);
+int launch_ga_fuse(const float *psi_g, const float *psi_v, const Dims &d, float alpha, float beta,
+                   float *score, hipStream_t st);
+
+// select.hip
+int launch_select(const float *score, const Dims &d, const litevggt_plan_t &pl,
+                  const litevggt_index &ix, hipStream_t st);
+
+// match.hip
+size_t match_ws_bytes(const Dims &d, const litevggt_plan_t &pl);
+int launch_match(const uint16_t *x, const Dims &d, const litevggt_plan_t &pl,
+                 const litevggt_index &ix, float *best_sim, void *ws, hipStream_t st);
+
+// merge.hip
+int launch_merge(const uint16_t *x, const Dims &d, int64_t M, const litevggt_index &ix,
+                 uint16_t *z, hipStream_t st);
+int launch_unmerge(const uint16_t *y, const Dims &d, const litevggt_index &ix,
+                   const uint16_t *residual, uint16_t *out, hipStream_t st);
+
+// attn.hip
+size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype);
+int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_t *o,
+                int64_t n_tokens, int heads, float scale, int attn_dtype, void *ws,
+                hipStream_t st);
+
+}  // namespace lv
