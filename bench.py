@@ -1,0 +1,275 @@
+#!/usr/bin/env python3
+"""Benchmark of the merged global-attention layer stack on one MI355X.
+
+A *step* is one pass of the whole hot path over one synthetic sequence: the cached-index
+layer driver (`litevggt_layers_run`) running all global layers of the workload, including
+the merge-index refreshes.  `value` = tokens of the sequence / seconds per step, with all
+inputs resident in HBM before the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload f1000]
+
+Prints one JSON line.  `roofline` describes the dominant kernel (the attention kernel):
+its duration is measured with HIP events that the driver records on the launch stream
+inside the timed steps.  `cpu_baseline` is the CPU oracle timed on a bounded sub-sequence
+of the same workload and scaled by each step's operation count.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16
+PEAK_FP8_MFMA_TFLOPS = 5000.0      # MI355X dense fp8
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="f1000", help="f32 | f100 | f500 | f1000 | tiny2")
+    ap.add_argument("--merge-ratio", type=float, default=None)
+    ap.add_argument("--attn-dtype", default="bf16", choices=["bf16", "fp8"])
+    ap.add_argument("--no-unmerged", action="store_true",
+                    help="skip the one-launch unmerged attention baseline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-frames", type=int, default=24,
+                    help="frames of the sub-sequence the CPU oracle is timed on")
+    return ap.parse_args()
+
+
+class HipEvents:
+    """hipEvent_t handles created through the HIP runtime the library itself is linked to."""
+
+    def __init__(self, lib, n):
+        self.lib = lib
+        lib.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        lib.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        lib.hipEventDestroy.argtypes = [C.c_void_p]
+        self.arr = (C.c_void_p * n)()
+        for i in range(n):
+            ev = C.c_void_p()
+            assert lib.hipEventCreate(C.byref(ev)) == 0
+            self.arr[i] = ev
+
+    def ms(self, a, b):
+        out = C.c_float()
+        rc = self.lib.hipEventElapsedTime(C.byref(out), self.arr[a], self.arr[b])
+        assert rc == 0, f"hipEventElapsedTime rc={rc}"
+        return out.value
+
+    def close(self):
+        for ev in self.arr:
+            self.lib.hipEventDestroy(ev)
+
+
+def cpu_baseline(wl, pl_full, n_frames):
+    """Time the oracle on the first n_frames of the workload, one layer with a refresh, and
+    scale each step to the full sequence by its operation count."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from helpers import oracle_params
+    from oracle import litevggt_oracle as O
+    from paper_2512_04939_amd import synth
+
+    sub = synth.Workload(**{**wl.__dict__, "frames": n_frames})
+    gen = synth.Generator(wl)                     # same canvases/offsets as the full workload
+    x = synth.stored_to_f32(gen.tokens(range(n_frames)))
+    im = gen.images(range(n_frames))
+    po = oracle_params(sub)
+    pls = O.plan(po)
+    t = {}
+    t0 = time.perf_counter()
+    score, psi_g = O.importance(im, x, po)
+    t["importance"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    sel = O.select_anchors(score.astype(np.float32), po)
+    t["select"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    mt = O.match(x, sel["dst_idx"], sel["src_idx"])
+    idx = O.build_index(sel["role"], sel["src_idx"], mt["anchor"])
+    t["match"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    z = O.merge(x, idx["group_off"], idx["group_mem"])
+    t["merge"] = time.perf_counter() - t0
+    zz = z.reshape(z.shape[0], po.heads, po.head_dim)
+    t0 = time.perf_counter()
+    y = O.attention(zz, zz, zz).reshape(z.shape)
+    t["attn"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    O.unmerge(y, idx["slot_of"], residual=x)
+    t["unmerge"] = time.perf_counter() - t0
+    fr = wl.frames / n_frames
+    scale = dict(importance=fr, select=fr,
+                 match=(pl_full.n_src * pl_full.n_dst) / max(pls["n_src"] * pls["n_dst"], 1),
+                 merge=pl_full.N / pls["N"], unmerge=pl_full.N / pls["N"],
+                 attn=(pl_full.M / pls["M"]) ** 2)
+    refreshes = sum(O.refresh_schedule(wl.layers, wl.refresh_interval))
+    full = (refreshes * sum(t[k] * scale[k] for k in ("importance", "select", "match"))
+            + wl.layers * sum(t[k] * scale[k] for k in ("merge", "attn", "unmerge")))
+    threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    return dict(value=pl_full.N / full, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=(f"oracle timed on the first {n_frames} of {wl.frames} frames "
+                        f"(N={pls['N']}, M={pls['M']}), one refresh + one layer, "
+                        f"{sum(t.values()):.1f} s measured; each step scaled to the full "
+                        f"sequence by its operation count (extrapolated step: {full:.0f} s)"),
+                measured_s={k: round(v, 3) for k, v in t.items()})
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not "
+              "supported (no collectives are part of it).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from helpers import hip_params
+    from paper_2512_04939_amd import binding as B
+    from paper_2512_04939_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    lib = B.lib()
+
+    over = {} if args.merge_ratio is None else dict(merge_ratio=args.merge_ratio)
+    wl = synth.workload(args.workload, **over)
+    attn_dtype = B.ATTN_BF16 if args.attn_dtype == "bf16" else B.ATTN_FP8_E4M3
+    ph = hip_params(wl, attn_dtype=attn_dtype)
+    pl = B.litevggt_plan(ph)
+    L, C_ = wl.layers, wl.dim
+
+    t0 = time.perf_counter()
+    gen = synth.Generator(wl)
+    bits = gen.tokens(threads=min(16, os.cpu_count() or 1))
+    if bits.dtype != np.uint16:
+        bits = synth.f32_to_bf16_bits(bits)
+    x0 = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    del bits
+    im = torch.empty(wl.frames, 3, wl.img_h, wl.img_w, dtype=torch.float32, device="cuda")
+    for f0 in range(0, wl.frames, 50):
+        fr = range(f0, min(wl.frames, f0 + 50))
+        im[f0:f0 + len(fr)].copy_(torch.from_numpy(gen.images(fr)))
+    gen_s = time.perf_counter() - t0
+
+    x = torch.empty_like(x0)
+    ib = B.alloc_index(pl)
+    grad = torch.zeros(wl.frames, wl.patches, device="cuda")
+    score = torch.zeros(wl.frames, wl.patches, device="cuda")
+    ws = B.alloc_ws(pl.ws_bytes)
+    n_ev = B.EVENTS_PER_LAYER * L
+    evs = [HipEvents(lib, n_ev) for _ in range(args.steps)]
+
+    for _ in range(args.warmup):
+        x.copy_(x0)
+        B.litevggt_layers_run(ph, L, im, x, ib, grad, score, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        x.copy_(x0)                      # restore the input (0.03 % of a step at 1000 frames)
+        log = B.litevggt_layers_run(ph, L, im, x, ib, grad, score, ws, events=evs[k].arr)
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    ms_step = 1e3 * total_s / args.steps
+    finite = bool(torch.isfinite(x.float()).all().item())
+
+    # per-step durations from the driver's events
+    E = B.EVENTS_PER_LAYER
+    names = {"importance": (B.EV_LAYER_BEGIN, B.EV_IMPORTANCE_END),
+             "select": (B.EV_IMPORTANCE_END, B.EV_SELECT_END),
+             "match": (B.EV_SELECT_END, B.EV_MATCH_END),
+             "merge": (B.EV_MATCH_END, B.EV_MERGE_END),
+             "attn_pack": (B.EV_MERGE_END, B.EV_ATTN_PACK_END),
+             "attn": (B.EV_ATTN_PACK_END, B.EV_ATTN_END),
+             "unmerge": (B.EV_ATTN_END, B.EV_UNMERGE_END)}
+    dur = {k: [] for k in names}
+    for ev in evs:
+        for l in range(L):
+            for k, (a, b) in names.items():
+                if k in ("importance", "select", "match") and not log[l]:
+                    continue
+                dur[k].append(ev.ms(l * E + a, l * E + b))
+    avg = {k: (sum(v) / len(v) if v else 0.0) for k, v in dur.items()}
+    for ev in evs:
+        ev.close()
+
+    N, M = pl.N, pl.M
+    peak_tf = PEAK_BF16_MFMA_TFLOPS if args.attn_dtype == "bf16" else PEAK_FP8_MFMA_TFLOPS
+    attn_flop = 4.0 * M * M * C_
+    attn_tf = attn_flop / (avg["attn"] * 1e-3) / 1e12
+    match_flop = 2.0 * pl.n_src * pl.n_dst * C_
+    merge_bytes = (N + M) * C_ * 2 + 4 * (N + M)
+    unmerge_bytes = (M + 2 * N) * C_ * 2 + 4 * N
+    ops = {
+        "attn": dict(ms=avg["attn"], tflops=attn_tf, frac_mfma=attn_tf / peak_tf),
+        "attn_pack": dict(ms=avg["attn_pack"]),
+        "match": dict(ms=avg["match"],
+                      tflops=(match_flop / (avg["match"] * 1e-3) / 1e12) if avg["match"] else 0.0),
+        "merge": dict(ms=avg["merge"], gbs=merge_bytes / (avg["merge"] * 1e-3) / 1e9),
+        "unmerge": dict(ms=avg["unmerge"], gbs=unmerge_bytes / (avg["unmerge"] * 1e-3) / 1e9),
+        "importance": dict(ms=avg["importance"]),
+        "select": dict(ms=avg["select"]),
+    }
+    ops["match"]["frac_mfma"] = ops["match"]["tflops"] / PEAK_BF16_MFMA_TFLOPS
+    ops["merge"]["frac_hbm"] = ops["merge"]["gbs"] / PEAK_HBM_GBS
+    ops["unmerge"]["frac_hbm"] = ops["unmerge"]["gbs"] / PEAK_HBM_GBS
+
+    unmerged = None
+    if not args.no_unmerged:
+        need = B.litevggt_attn_ws_bytes(ph, N)
+        ws_u = B.alloc_ws(need)
+        o = torch.empty_like(x0)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        B.litevggt_global_attn(ph, N, x0, x0, x0, o, ws_u)
+        b.record()
+        torch.cuda.synchronize()
+        u_ms = a.elapsed_time(b)
+        unmerged = dict(ms_per_layer=u_ms, tflops=4.0 * N * N * C_ / (u_ms * 1e-3) / 1e12,
+                        ms_stack_extrapolated=u_ms * L,
+                        note="one launch of the same attention entry point on the unmerged "
+                             "sequence (n_tokens = N, q = k = v = x), times the layer count")
+        del ws_u, o
+
+    out = {
+        "metric": "merged global-attn tokens/s @%d frames" % wl.frames,
+        "value": N / (ms_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.attn_dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.frames} frames x {wl.tokens_per_frame} tokens "
+                               f"(N={N}), dim {C_}, {wl.heads} heads x 64, merge ratio "
+                               f"{wl.merge_ratio} (M={M}), {L} global layers, index refreshed "
+                               f"every {wl.refresh_interval}",
+                   "token_layers_per_s": L * N / (ms_step * 1e-3),
+                   "refresh_log": log, "output_finite": finite,
+                   "peak_hbm_alloc_gib": torch.cuda.max_memory_allocated() / 2 ** 30,
+                   "input_generation_s": gen_s},
+        "roofline": {"kernel": "k_attn_bf16", "bound": "mfma", "achieved": attn_tf, "peak": peak_tf,
+                     "unit": "TFLOP/s", "frac": attn_tf / peak_tf, "traffic": None,
+                     "flop_per_launch": attn_flop, "avg_launch_ms": avg["attn"],
+                     "launches_timed": len(dur["attn"])},
+        "ops": ops,
+        "unmerged_attention": unmerged,
+    }
+    if unmerged:
+        out["speedup_vs_unmerged_stack"] = unmerged["ms_stack_extrapolated"] / ms_step
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, pl, min(args.cpu_frames, wl.frames))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

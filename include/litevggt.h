@@ -57,6 +57,8 @@ typedef struct {
   int32_t var_pool;        /* window of the local variance pooling (3), odd        */
   int32_t refresh_interval;/* layers between merge-index recomputations (6)        */
   int32_t attn_dtype;      /* LV_ATTN_BF16 or LV_ATTN_FP8_E4M3                     */
+  int32_t qk_norm;         /* != 0: attention RMS-normalises q and k per head first:
+                              q <- bf16(q / sqrt(mean(q^2) + 1e-6)), same for k      */
   float   alpha, beta;     /* weights of the gradient and variance maps            */
   float   softmax_scale;   /* <= 0 selects 1/sqrt(head_dim)                        */
   double  merge_ratio;     /* r in [0,1): fraction of patch tokens per non-first
@@ -146,6 +148,9 @@ int litevggt_merge(const litevggt_params *p, const void *x, const litevggt_index
  * sequence, per head: O = softmax(Q K^T * softmax_scale) V.
  *   q,k,v [device] [n_tokens, heads, 64] bf16 (row stride dim); o likewise, out.
  *   n_tokens = M for the merged path, N for the unmerged baseline.
+ * With qk_norm the scores use the per-head RMS-normalised q and k (see litevggt_params);
+ * v is used as given.  Scores are exponentiated as exp2(s*c - max*c) with one fused
+ * multiply-add: accurate while |score * softmax_scale| stays below about 2^16.
  * attn_dtype LV_ATTN_FP8_E4M3 quantises q,k,v per tensor (scale = amax/448) and the
  * softmax weights to e4m3 for the MFMAs; accumulation and softmax stay fp32.
  */
@@ -163,14 +168,31 @@ int litevggt_unmerge(const litevggt_params *p, const void *y, const litevggt_ind
 /* Cached-index layer driver, Sec. 3.4: for layer l = 0..n_layers-1, recompute the
  * merge index (steps 1-3; the gradient map only at l = 0) when
  * l % refresh_interval == 0, then x <- x + unmerge(attn(merge(x))) with
- * Q = K = V = the merged tokens viewed as [M, heads, 64].
+ * Q = K = V = the merged tokens viewed as [M, heads, 64] (q, k normalised when qk_norm).
  *   x           [device] [N,dim] bf16, in/out
  *   grad_cache, score [device] [F,P] fp32 scratch/outputs of the last refresh
  *   refresh_log [host] [n_layers] set to 1 where the index was recomputed, or NULL
+ *   events      [host] NULL, or LV_EVENTS_PER_LAYER*n_layers hipEvent_t handles (as
+ *               void*) created by the caller; the driver records them on `stream` at the
+ *               step boundaries of every layer (LV_EV_* below) so the caller can time each
+ *               step inside a run.  On layers without a refresh the first four boundaries
+ *               are recorded back to back.
  */
+enum {
+  LV_EV_LAYER_BEGIN = 0,   /* before importance                                    */
+  LV_EV_IMPORTANCE_END,    /* after the GA map, before the partition               */
+  LV_EV_SELECT_END,        /* after the partition, before matching                 */
+  LV_EV_MATCH_END,         /* after matching + CSR, before merge                   */
+  LV_EV_MERGE_END,         /* after merge, before the K/V re-layout of attention   */
+  LV_EV_ATTN_PACK_END,     /* after the re-layout, before the attention kernel     */
+  LV_EV_ATTN_END,          /* after the attention kernel, before unmerge           */
+  LV_EV_UNMERGE_END,       /* after unmerge                                        */
+  LV_EVENTS_PER_LAYER
+};
 int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *images,
                         void *x, litevggt_index *index, float *grad_cache, float *score,
-                        int32_t *refresh_log, void *ws, size_t ws_bytes, void *stream);
+                        int32_t *refresh_log, void **events, void *ws, size_t ws_bytes,
+                        void *stream);
 
 #ifdef __cplusplus
 }

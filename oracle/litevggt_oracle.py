@@ -46,6 +46,7 @@ class Params:
     beta: float = 0.5
     var_pool: int = 3           # window of the local average pooling (paper silent)
     refresh_interval: int = 6   # Sec. 3.4 "Cached Token Merging"
+    qk_norm: bool = False       # layer loop: RMS-normalise q and k per head (see global_layer)
 
     @property
     def patches(self) -> int:
@@ -323,6 +324,15 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: Optional[float
     return out
 
 
+def qk_normalize(a: np.ndarray, eps: float = 1e-6) -> np.ndarray:
+    """Per-head RMS normalisation a / sqrt(mean(a^2) + eps) over the last axis of
+    [M,h,d].  Not part of the paper (it does not describe VGGT's attention block, which
+    normalises queries and keys); used by the layer loop to keep the projection-free
+    stand-in attention in a sane numeric range at every depth."""
+    af = np.asarray(a, dtype=np.float64)
+    return af / np.sqrt((af * af).mean(axis=-1, keepdims=True) + eps)
+
+
 def unmerge(y: np.ndarray, slot_of: np.ndarray, residual: Optional[np.ndarray] = None,
             ) -> np.ndarray:
     """Every token of a group receives its anchor's merged row (Sec. 3.4 "Token
@@ -381,11 +391,13 @@ def compute_index(images, x, p: Params, psi_g=None, score_dtype=np.float32):
 def global_layer(x: np.ndarray, idx: Dict[str, np.ndarray], p: Params,
                  store=lambda a: a) -> np.ndarray:
     """One merged global layer: x + U(Attn(M(x))) with Q = K = V = merged tokens viewed
-    as [M, heads, head_dim] (no projections: the paper does not describe them).
-    ``store`` models the storage rounding applied to z, y and the output."""
+    as [M, heads, head_dim] (no projections: the paper does not describe them); with
+    p.qk_norm, Q = K = the per-head RMS-normalised merged tokens (stored, i.e. rounded).
+    ``store`` models the storage rounding applied to z, the normalised q/k, y and the output."""
     z = store(merge(x, idx["group_off"], idx["group_mem"]))
     zz = z.reshape(z.shape[0], p.heads, p.head_dim)
-    y = store(attention(zz, zz, zz).reshape(z.shape))
+    qk = store(qk_normalize(zz)) if p.qk_norm else zz
+    y = store(attention(qk, qk, zz).reshape(z.shape))
     return store(unmerge(y, idx["slot_of"], residual=x))
 
 

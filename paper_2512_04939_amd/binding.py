@@ -33,7 +33,7 @@ class Params(C.Structure):
                 ("n_special", C.c_int32), ("dim", C.c_int32), ("heads", C.c_int32),
                 ("head_dim", C.c_int32), ("patch", C.c_int32), ("img_dtype", C.c_int32),
                 ("var_pool", C.c_int32), ("refresh_interval", C.c_int32),
-                ("attn_dtype", C.c_int32), ("alpha", C.c_float), ("beta", C.c_float),
+                ("attn_dtype", C.c_int32), ("qk_norm", C.c_int32), ("alpha", C.c_float), ("beta", C.c_float),
                 ("softmax_scale", C.c_float), ("merge_ratio", C.c_double),
                 ("ga_frac", C.c_double)]
 
@@ -55,9 +55,9 @@ class Index(C.Structure):
 
 def make_params(frames, grid_h, grid_w, dim, heads, *, head_dim=64, n_special=5, patch=14,
                 img_dtype=IMG_F32, var_pool=3, refresh_interval=6, attn_dtype=ATTN_BF16,
-                alpha=0.5, beta=0.5, softmax_scale=0.0, merge_ratio=0.9, ga_frac=0.10) -> Params:
+                qk_norm=0, alpha=0.5, beta=0.5, softmax_scale=0.0, merge_ratio=0.9, ga_frac=0.10) -> Params:
     return Params(frames, grid_h, grid_w, n_special, dim, heads, head_dim, patch, img_dtype,
-                  var_pool, refresh_interval, attn_dtype, alpha, beta, softmax_scale,
+                  var_pool, refresh_interval, attn_dtype, qk_norm, alpha, beta, softmax_scale,
                   merge_ratio, ga_frac)
 
 
@@ -86,7 +86,7 @@ def lib() -> C.CDLL:
         L.litevggt_global_attn.argtypes = [PP, i64, vp, vp, vp, vp, vp, sz, vp]
         L.litevggt_unmerge.argtypes = [PP, vp, C.POINTER(Index), vp, vp, vp]
         L.litevggt_layers_run.argtypes = [PP, i32, vp, vp, C.POINTER(Index), vp, vp,
-                                          C.POINTER(C.c_int32), vp, sz, vp]
+                                          C.POINTER(C.c_int32), C.POINTER(C.c_void_p), vp, sz, vp]
         for name in EXPORTS[1:]:
             if name != "litevggt_attn_ws_bytes":
                 getattr(L, name).restype = i32
@@ -203,12 +203,19 @@ def litevggt_unmerge(p: Params, y, index: IndexBuffers, residual, out) -> None:
                                   _stream()), "litevggt_unmerge")
 
 
+EVENTS_PER_LAYER = 8
+(EV_LAYER_BEGIN, EV_IMPORTANCE_END, EV_SELECT_END, EV_MATCH_END, EV_MERGE_END, EV_ATTN_PACK_END,
+ EV_ATTN_END, EV_UNMERGE_END) = range(EVENTS_PER_LAYER)
+
+
 def litevggt_layers_run(p: Params, n_layers: int, images, x, index: IndexBuffers, grad_cache,
-                        score, ws):
+                        score, ws, events=None):
+    """``events``: optional ctypes array of EVENTS_PER_LAYER*n_layers hipEvent_t handles."""
     ix = index.struct()
     wp, wn = _ws_args(ws)
     log = (C.c_int32 * max(n_layers, 1))()
     _check(lib().litevggt_layers_run(C.byref(p), n_layers, _ptr(images), _ptr(x), C.byref(ix),
-                                     _ptr(grad_cache), _ptr(score), log, wp, wn, _stream()),
+                                     _ptr(grad_cache), _ptr(score), log, events, wp, wn,
+                                     _stream()),
            "litevggt_layers_run")
     return list(log)[:n_layers]

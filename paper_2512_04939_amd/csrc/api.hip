@@ -203,7 +203,7 @@ int litevggt_global_attn(const litevggt_params *p, int64_t n_tokens, const void 
   if (n_tokens < 1 || n_tokens >= ((int64_t)1 << 31)) return LV_ERR_SHAPE;
   if (!ws_ok(ws, ws_bytes, attn_ws_bytes(d.heads, n_tokens, p->attn_dtype))) return LV_ERR_WORKSPACE;
   return launch_attn((const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)o,
-                     n_tokens, d.heads, scale_of(p), p->attn_dtype, ws, (hipStream_t)stream);
+                     n_tokens, d.heads, scale_of(p), p->attn_dtype, p->qk_norm, ws, (hipStream_t)stream);
 }
 
 int litevggt_unmerge(const litevggt_params *p, const void *y, const litevggt_index *index,
@@ -218,7 +218,8 @@ int litevggt_unmerge(const litevggt_params *p, const void *y, const litevggt_ind
 
 int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *images, void *x,
                         litevggt_index *index, float *grad_cache, float *score,
-                        int32_t *refresh_log, void *ws, size_t ws_bytes, void *stream) {
+                        int32_t *refresh_log, void **events, void *ws, size_t ws_bytes,
+                        void *stream) {
   Dims d;
   litevggt_plan_t pl;
   int rc = check_params(p, &d);
@@ -238,6 +239,12 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
   for (int l = 0; l < n_layers; ++l) {
     const bool refresh = (l % p->refresh_interval) == 0;
     if (refresh_log) refresh_log[l] = refresh ? 1 : 0;
+    hipEvent_t *ev = events ? (hipEvent_t *)events + (size_t)l * LV_EVENTS_PER_LAYER : nullptr;
+    auto mark = [&](int which) -> int {
+      if (ev && hipEventRecord(ev[which], st) != hipSuccess) return LV_ERR_HIP;
+      return LV_OK;
+    };
+    if ((rc = mark(LV_EV_LAYER_BEGIN))) return rc;
     if (refresh) {
       if (l == 0) {
         rc = launch_grad_map(images, p->img_dtype, d, p->patch, grad_cache, st);
@@ -247,17 +254,28 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
       if (rc) return rc;
       rc = launch_ga_fuse(grad_cache, (const float *)op_ws, d, p->alpha, p->beta, score, st);
       if (rc) return rc;
+    }
+    if ((rc = mark(LV_EV_IMPORTANCE_END))) return rc;
+    if (refresh) {
       rc = launch_select(score, d, pl, *index, st);
       if (rc) return rc;
+    }
+    if ((rc = mark(LV_EV_SELECT_END))) return rc;
+    if (refresh) {
       rc = launch_match(xx, d, pl, *index, nullptr, op_ws, st);
       if (rc) return rc;
     }
+    if ((rc = mark(LV_EV_MATCH_END))) return rc;
     rc = launch_merge(xx, d, pl.M, *index, z, st);
     if (rc) return rc;
-    rc = launch_attn(z, z, z, y, pl.M, d.heads, scale_of(p), p->attn_dtype, op_ws, st);
+    if ((rc = mark(LV_EV_MERGE_END))) return rc;
+    rc = launch_attn(z, z, z, y, pl.M, d.heads, scale_of(p), p->attn_dtype, p->qk_norm, op_ws, st,
+                     ev ? ev[LV_EV_ATTN_PACK_END] : nullptr);
     if (rc) return rc;
+    if ((rc = mark(LV_EV_ATTN_END))) return rc;
     rc = launch_unmerge(y, d, *index, xx, xx, st);
     if (rc) return rc;
+    if ((rc = mark(LV_EV_UNMERGE_END))) return rc;
   }
   return LV_OK;
 }

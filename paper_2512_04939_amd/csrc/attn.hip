@@ -27,13 +27,34 @@ constexpr int kQW = 64;              // queries per wave
 constexpr int kQB = 256;             // queries per workgroup
 constexpr int kFragU4 = 64;          // one fragment = 64 lanes x 16 B
 
+constexpr float kQkEps = 1e-6f;
+
+// RMS-normalise a 64-value head row that is spread over 2^log2_lanes neighbouring lanes (8
+// bf16 values each, or several such chunks per lane): returns this lane's chunk scaled by
+// 1/sqrt(mean(x^2) + eps), rounded to bf16.
+__device__ __forceinline__ float sumsq8(const u32x4 w) {
+  const float a0 = bf16_lo(w.x), a1 = bf16_hi(w.x), a2 = bf16_lo(w.y), a3 = bf16_hi(w.y);
+  const float a4 = bf16_lo(w.z), a5 = bf16_hi(w.z), a6 = bf16_lo(w.w), a7 = bf16_hi(w.w);
+  return ((a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3)) + ((a4 * a4 + a5 * a5) + (a6 * a6 + a7 * a7));
+}
+__device__ __forceinline__ u32x4 scale8(const u32x4 w, float r) {
+  return u32x4{pack_bf16(bf16_lo(w.x) * r, bf16_hi(w.x) * r), pack_bf16(bf16_lo(w.y) * r, bf16_hi(w.y) * r),
+               pack_bf16(bf16_lo(w.z) * r, bf16_hi(w.z) * r), pack_bf16(bf16_lo(w.w) * r, bf16_hi(w.w) * r)};
+}
+__device__ __forceinline__ u32x4 rms_scale8(const u32x4 w, int log2_lanes) {
+  float ss = sumsq8(w);
+  for (int o = 1; o < (1 << log2_lanes); o <<= 1) ss += __shfl_xor(ss, o, 64);
+  return scale8(w, 1.0f / sqrtf(ss * (1.0f / 64.0f) + kQkEps));
+}
+
 // K -> [head][key tile][k-step s][lane] : lane (h*32+r) holds K[tile*32+r][16s+8h .. +8]
 // V -> [head][key tile][u][dt][lane]    : lane (h*32+dr) holds, for e = 0..7,
 //      V[tile*32 + 16u + 8(e/4) + 4h + e%4][32dt + dr]   (the key order in which a lane of
 //      the S^T accumulator holds its rows, so P needs no shuffle before the second MFMA)
 __global__ __launch_bounds__(256) void k_attn_pack(const uint16_t *__restrict__ k,
                                                    const uint16_t *__restrict__ v, int64_t n,
-                                                   int heads, int n_kt, u32x4 *__restrict__ kp,
+                                                   int heads, int n_kt, int qk_norm,
+                                                   u32x4 *__restrict__ kp,
                                                    u32x4 *__restrict__ vp) {
   __shared__ __attribute__((aligned(16))) uint16_t vt[kKT][72];
   const int kt = blockIdx.x, head = blockIdx.y, t = threadIdx.x;
@@ -45,6 +66,7 @@ __global__ __launch_bounds__(256) void k_attn_pack(const uint16_t *__restrict__ 
     wk = *(const u32x4 *)(k + (size_t)row * C + head * 64 + chunk * 8);
     wv = *(const u32x4 *)(v + (size_t)row * C + head * 64 + chunk * 8);
   }
+  if (qk_norm) wk = rms_scale8(wk, 3);   // the 8 lanes that share a key hold its 64 values
   const size_t tile = ((size_t)head * n_kt + kt) * 4 * kFragU4;
   kp[tile + (chunk >> 1) * kFragU4 + (chunk & 1) * 32 + key] = wk;
   *(u32x4 *)&vt[key][chunk * 8] = wv;
@@ -64,7 +86,7 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(
 template <bool RAGGED_UNUSED = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_bf16(
     const uint16_t *__restrict__ q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp,
-    uint16_t *__restrict__ o, int64_t n, int heads, int n_kt, int nqb, float c) {
+    uint16_t *__restrict__ o, int64_t n, int heads, int n_kt, int nqb, float c, int qk_norm) {
   __shared__ u32x4 ks[2][8 * kFragU4];
   __shared__ u32x4 vs[2][8 * kFragU4];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, h = lane >> 5, ql = lane & 31;
@@ -86,8 +108,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   for (int sub = 0; sub < 2; ++sub) {
     const int64_t row = min(q0 + sub * 32 + ql, n - 1);
     const uint16_t *qp = q + (size_t)row * C + head * 64 + 8 * h;
+    u32x4 w[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) qf[sub][s] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(qp + 16 * s));
+    for (int s = 0; s < 4; ++s) w[s] = *(const u32x4 *)(qp + 16 * s);
+    if (qk_norm) {   // this lane holds 32 of the row's 64 values, lane^32 the other 32
+      float ss = (sumsq8(w[0]) + sumsq8(w[1])) + (sumsq8(w[2]) + sumsq8(w[3]));
+      ss += __shfl_xor(ss, 32, 64);
+      const float r = 1.0f / sqrtf(ss * (1.0f / 64.0f) + kQkEps);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) w[s] = scale8(w[s], r);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) qf[sub][s] = __builtin_bit_cast(bf16x8, w[s]);
   }
 
   f32x16 oacc[2][2];
@@ -238,18 +270,20 @@ size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype) {
 }
 
 int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_t *o,
-                int64_t n, int heads, float scale, int attn_dtype, void *ws, hipStream_t st) {
+                int64_t n, int heads, float scale, int attn_dtype, int qk_norm, void *ws,
+                hipStream_t st, hipEvent_t after_pack) {
   if (attn_dtype != LV_ATTN_BF16) return LV_ERR_DTYPE;
   const int n_kt = n_key_tiles(n);
   const size_t per = align_up((size_t)heads * n_kt * 4 * kFragU4 * sizeof(u32x4), 256);
   u32x4 *kp = (u32x4 *)ws;
   u32x4 *vp = (u32x4 *)((char *)ws + per);
   hipLaunchKernelGGL(k_attn_pack, dim3((unsigned)n_kt, (unsigned)heads), dim3(256), 0, st, k, v, n,
-                     heads, n_kt, kp, vp);
+                     heads, n_kt, qk_norm, kp, vp);
+  if (after_pack && hipEventRecord(after_pack, st) != hipSuccess) return LV_ERR_HIP;
   const int nqb = (int)((n + kQB - 1) / kQB);
   const float c = scale * 1.4426950408889634f;
   hipLaunchKernelGGL(k_attn_bf16<false>, dim3((unsigned)(nqb * heads)), dim3(256), 0, st, q, kp, vp,
-                     o, n, heads, n_kt, nqb, c);
+                     o, n, heads, n_kt, nqb, c, qk_norm);
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;
 }

@@ -40,8 +40,9 @@ int launch_unmerge(const uint16_t *y, const Dims &d, const litevggt_index &ix,
 
 // attn.hip
 size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype);
+// `after_pack`, when not NULL, is recorded between the K/V re-layout and the main kernel
 int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_t *o,
-                int64_t n_tokens, int heads, float scale, int attn_dtype, void *ws,
-                hipStream_t st);
+                int64_t n_tokens, int heads, float scale, int attn_dtype, int qk_norm, void *ws,
+                hipStream_t st, hipEvent_t after_pack = nullptr);
 
 }  // namespace lv

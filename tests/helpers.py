@@ -10,7 +10,7 @@ from paper_2512_04939_amd import synth
 def oracle_params(wl: synth.Workload, **kw) -> O.Params:
     base = dict(frames=wl.frames, grid_h=wl.grid_h, grid_w=wl.grid_w, n_special=wl.n_special,
                 dim=wl.dim, heads=wl.heads, head_dim=wl.head_dim, patch=wl.patch,
-                merge_ratio=wl.merge_ratio, refresh_interval=wl.refresh_interval)
+                merge_ratio=wl.merge_ratio, refresh_interval=wl.refresh_interval, qk_norm=True)
     base.update(kw)
     return O.Params(**base)
 
@@ -18,7 +18,7 @@ def oracle_params(wl: synth.Workload, **kw) -> O.Params:
 def hip_params(wl: synth.Workload, **kw):
     from paper_2512_04939_amd import binding as B
     base = dict(n_special=wl.n_special, patch=wl.patch, merge_ratio=wl.merge_ratio,
-                refresh_interval=wl.refresh_interval)
+                refresh_interval=wl.refresh_interval, qk_norm=1)
     base.update(kw)
     return B.make_params(wl.frames, wl.grid_h, wl.grid_w, wl.dim, wl.heads, **base)
 

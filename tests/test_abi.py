@@ -89,6 +89,6 @@ def test_entry_points_validate_before_launch():
     assert lib.litevggt_global_attn(C.byref(p), 0, fake, fake, fake, fake, fake, 1 << 30, None) == -2
     assert lib.litevggt_global_attn(C.byref(p), 100, fake, fake, fake, fake, fake, 16, None) == -4
     assert lib.litevggt_unmerge(C.byref(p), None, C.byref(ix), None, fake, None) == -1
-    assert lib.litevggt_layers_run(C.byref(p), 2, fake, fake, C.byref(ix), fake, fake, None, fake,
-                                   1 << 30, None) == -1
+    assert lib.litevggt_layers_run(C.byref(p), 2, fake, fake, C.byref(ix), fake, fake, None, None,
+                                   fake, 1 << 30, None) == -1
     assert B.litevggt_attn_ws_bytes(p, 1000) > 0

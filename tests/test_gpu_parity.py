@@ -321,13 +321,33 @@ def test_global_attn_softmax_scale_parameter(B):
     assert max_rel_err(dev_bf16_to_f64(o).reshape(n, 1, 64), ref) <= BF16_TOL
 
 
+def test_global_attn_qk_norm(B):
+    """With qk_norm the kernel normalises q and k per head itself (fp32), rounding them to
+    bf16 before the MFMAs; the oracle normalises in float64 and rounds at the same point."""
+    import torch
+    n, heads = 333, 4
+    q, k, v = synth.random_qkv(n, heads, 64, seed=79, scale=5.0)
+    bits = [synth.f32_to_bf16_bits(a.reshape(n, heads * 64)) for a in (q, k, v)]
+    ph = B.make_params(1, 1, 1, heads * 64, heads, n_special=0, qk_norm=1)
+    ws = B.alloc_ws(B.litevggt_attn_ws_bytes(ph, n))
+    o = torch.zeros(n, heads * 64, dtype=torch.bfloat16, device="cuda")
+    B.litevggt_global_attn(ph, n, *(to_dev_bf16(b) for b in bits), o, ws)
+    torch.cuda.synchronize()
+    qs, ks, vs = (synth.bf16_bits_to_f32(b).reshape(n, heads, 64) for b in bits)
+    ref = O.attention(O.round_bf16(O.qk_normalize(qs)), O.round_bf16(O.qk_normalize(ks)), vs)
+    assert max_rel_err(dev_bf16_to_f64(o).reshape(n, heads, 64), ref) <= BF16_TOL
+    # and it differs from the un-normalised result, i.e. the flag does something
+    ref_plain = O.attention(qs, ks, vs)
+    assert max_rel_err(ref_plain, ref) > 0.1
+
+
 # ------------------------------------------------------------------------- the layer driver
 def _store_bf16(a):
     return O.round_bf16(a)
 
 
 @pytest.mark.parametrize("name,layers,interval", [("tiny2", 2, 6), ("tiny2", 4, 2),
-                                                   ("small_r09", 3, 2)])
+                                                   ("small_r09", 3, 2), ("tiny2", 24, 6)])
 def test_layers_run_teacher_forced_and_end_to_end(B, name, layers, interval):
     """Each GPU layer is fed the oracle's input of that layer (teacher forcing); the chained
     GPU run is compared too.  The oracle rounds z, y and the layer output to bf16 where the

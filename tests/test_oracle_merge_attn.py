@@ -110,6 +110,25 @@ def test_attention_special_cases():
     assert np.all(np.isfinite(O.attention(300 * q, k, v)))
 
 
+def test_qk_normalize_against_torch_rms_norm():
+    q, _, _ = synth.random_qkv(50, 3, 64, seed=44, scale=3.0)
+    n = O.qk_normalize(q)
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(q.astype(np.float64)), (64,), eps=1e-6).numpy()
+    assert np.allclose(n, ref, atol=1e-13)
+    assert np.allclose((n * n).mean(axis=-1), 1.0, atol=1e-5)          # unit RMS per head
+    assert np.allclose(O.qk_normalize(1000.0 * q), n, atol=1e-6)       # scale invariant
+    assert np.all(O.qk_normalize(np.zeros((2, 1, 64))) == 0.0)
+
+
+def test_layer_with_qk_norm_stays_bounded_over_depth():
+    p, x, im = _tiny_problem(0.5, interval=6, layers=12)
+    pq = p.__class__(**{**p.__dict__, "qk_norm": True})
+    out, _ = O.layers_run(im, x, pq, 12, store=O.round_bf16)
+    assert np.all(np.isfinite(out))
+    # every layer adds a convex combination of merged rows: at most a doubling per layer
+    assert np.abs(out).max() <= 2.0 ** 12 * np.abs(x).max()
+
+
 # -------------------------------------------------------------------------------- rounding
 def test_round_bf16_matches_torch():
     rng = np.random.default_rng(51)
