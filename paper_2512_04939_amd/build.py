@@ -14,7 +14,7 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build(verbose: bool = True, extra: list[str] | None = None) -> str:
+def build(verbose: bool = True, extra: list[str] | None = None, lib: str = LIB) -> str:
     objs = []
     procs = []
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
@@ -38,11 +38,11 @@ def build(verbose: bool = True, extra: list[str] | None = None) -> str:
             print(f"hipcc failed on {s}", file=sys.stderr)
     if failed:
         raise RuntimeError("HIP build failed")
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

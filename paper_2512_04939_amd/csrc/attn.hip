@@ -28,6 +28,7 @@ constexpr int kQB = 256;             // queries per workgroup
 constexpr int kFragU4 = 64;          // one fragment = 64 lanes x 16 B
 
 constexpr float kQkEps = 1e-6f;
+constexpr float kRaise = 8.0f;       // log2 headroom before the softmax reference is raised
 
 // RMS-normalise a 64-value head row that is spread over 2^log2_lanes neighbouring lanes (8
 // bf16 values each, or several such chunks per lane): returns this lane's chunk scaled by
@@ -129,7 +130,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[sub][dt][r] = 0.f;
-  float mrow[2] = {-INFINITY, -INFINITY}, lrow[2] = {0.f, 0.f};
+  float mref[2] = {-INFINITY, -INFINITY}, mc[2] = {0.f, 0.f}, lrow[2] = {0.f, 0.f};
+  const bf16x2 kOnes = {(__bf16)1.0f, (__bf16)1.0f};
 
   const int nkv = n_kt >> 1;
   const u32x4 *kh = kp + (size_t)head * n_kt * 4 * kFragU4;
@@ -185,7 +187,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           }
       }
     }
-    // ---- online softmax, one query column per lane
+    // ---- online softmax, one query column per lane.  The running reference mref is only
+    // raised (and O, l rescaled) when some lane's tile maximum exceeds it by more than
+    // kRaise in log2 units, so weights stay below 2^kRaise and rescaling is rare.
     u32x4 pb[2][2][2];   // [query block][key tile][u]
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
@@ -195,29 +199,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int r = 0; r < 16; r += 2) mx = max3(mx, sacc[kt2][sub][r], sacc[kt2][sub][r + 1]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mnew = fmaxf(mrow[sub], mx);
-      const float alpha = __builtin_amdgcn_exp2f((mrow[sub] - mnew) * c);
-      const float mc = mnew * c;
-      mrow[sub] = mnew;
-      float ls = 0.f;
+      if (__builtin_amdgcn_ballot_w64((mx - mref[sub]) * c > kRaise) != 0) {
+        const float mnew = fmaxf(mref[sub], mx);
+        const float alpha = __builtin_amdgcn_exp2f((mref[sub] - mnew) * c);
+        mref[sub] = mnew;
+        mc[sub] = mnew * c;
+        lrow[sub] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[sub][dt][r] *= alpha;
+      }
+      float ls = lrow[sub];
 #pragma unroll
       for (int kt2 = 0; kt2 < 2; ++kt2) {
         float p[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt2][sub][r], c, -mc));
-          ls += p[r];
+        for (int r = 0; r < 16; ++r)
+          p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt2][sub][r], c, -mc[sub]));
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          uint32_t w[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            w[e] = pack_bf16(p[8 * u + 2 * e], p[8 * u + 2 * e + 1]);
+            // row sum of the bf16-rounded weights (what the second MFMA really multiplies)
+            ls = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e]), kOnes, ls, false);
+          }
+          pb[sub][kt2][u] = u32x4{w[0], w[1], w[2], w[3]};
         }
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-          pb[sub][kt2][u] = u32x4{pack_bf16(p[8 * u], p[8 * u + 1]), pack_bf16(p[8 * u + 2], p[8 * u + 3]),
-                                  pack_bf16(p[8 * u + 4], p[8 * u + 5]), pack_bf16(p[8 * u + 6], p[8 * u + 7])};
       }
-      lrow[sub] = lrow[sub] * alpha + ls;
-#pragma unroll
-      for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[sub][dt][r] *= alpha;
+      lrow[sub] = ls;
     }
     // ---- O^T += V^T P^T
 #pragma unroll

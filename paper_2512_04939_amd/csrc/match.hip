@@ -17,7 +17,14 @@
 namespace lv {
 
 constexpr int kSrcTile = 64;         // src rows resident per workgroup
-constexpr int kMatchWaves = 8;       // 2 waves per SIMD
+#ifndef LV_MATCH_WAVES
+#define LV_MATCH_WAVES 8
+#endif
+#ifndef LV_MATCH_DEPTH
+#define LV_MATCH_DEPTH 3
+#endif
+constexpr int kMatchWaves = LV_MATCH_WAVES;   // 8 = 2 waves per SIMD
+constexpr int kDepth = LV_MATCH_DEPTH;        // register ring: chunks of dst fragments in flight per wave
 constexpr float kRescoreGap = 2e-4f; // similarity gap below which float64 decides
 
 struct Top2 {
@@ -52,9 +59,11 @@ __global__ __launch_bounds__(256) void k_pack_dst(const uint16_t *__restrict__ x
                                                   const int32_t *__restrict__ dst_idx,
                                                   const float *__restrict__ inv, int n_dst,
                                                   int n_dst_pad, int C, u32x4 *__restrict__ packed,
-                                                  float *__restrict__ invd) {
+                                                  float *__restrict__ invd,
+                                                  int32_t *__restrict__ belt) {
   const int nch = C >> 3, KS = C >> 4;
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < kXcd) belt[idx] = 0;   // sweep positions of the matching kernel start at 0
   if (idx >= (int64_t)n_dst_pad * nch) return;
   const int j = (int)(idx / nch), c = (int)(idx % nch);
   u32x4 w = {0u, 0u, 0u, 0u};
@@ -95,11 +104,22 @@ __device__ __forceinline__ void top2_insert_any(Top2 &t, float v, int i) {
 
 __global__ __launch_bounds__(kMatchWaves * 64) void k_match(
     const uint16_t *__restrict__ x, const int32_t *__restrict__ src_idx, int n_src,
-    const u32x4 *__restrict__ dstp, const float *__restrict__ invd, int n_dst, int n_tilepairs,
-    int C, Top2 *__restrict__ top2) {
+    const u32x4 *__restrict__ dstp, const float *__restrict__ invd, int n_dst, int n_groups,
+    int C, Top2 *__restrict__ top2, int32_t *belt) {
   extern __shared__ u32x4 frag[];   // [2 src tiles][KS][64 lanes]
+  __shared__ int g_start;
   const int KS = C >> 4, nch = C >> 3, NCHUNK = KS >> 2;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, h = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // keeps address math scalar
+  // All workgroups of an XCD share one L2.  They sweep the dst matrix circularly and a new
+  // workgroup joins the sweep where its XCD's others currently are (belt[xcd], a hint that
+  // wave 0 keeps publishing), so the same dst rows are requested by many CUs while they
+  // are still resident in that L2 instead of each CU streaming them from memory.
+  const int xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kXcd - 1);   // XCC_ID[3:0]
+  if (tid == 0) {
+    int g = __atomic_load_n(&belt[xcd], __ATOMIC_RELAXED);
+    g_start = (g >= 0 && g < n_groups) ? g : 0;
+  }
   const int src0 = blockIdx.x * kSrcTile;
 
   for (int idx = tid; idx < kSrcTile * nch; idx += blockDim.x) {
@@ -114,70 +134,92 @@ __global__ __launch_bounds__(kMatchWaves * 64) void k_match(
 #pragma unroll
   for (int b = 0; b < 2; ++b) best[b] = Top2{-INFINITY, -1, -INFINITY, -1};
 
-  for (int tp = wave; tp < n_tilepairs; tp += kMatchWaves) {
-    f32x16 acc[2][2];
+  // A group is kMatchWaves consecutive tile pairs (64 dst rows each), one per wave.  This
+  // wave's K-chunks (4 k-steps = 8 fragments) over all groups form one flat stream that is
+  // prefetched kDepth-1 chunks ahead through a register ring, across tile-pair boundaries,
+  // so that enough bytes are in flight to cover L2 latency.
+  const int g0 = g_start;
+  const int total = n_groups * NCHUNK;
+  const size_t a1off = (size_t)KS * 64;
+  u32x4 ring[kDepth][8];
+  int pgrp = g0, psb = 0, pg = 0;            // next chunk to fetch: group, chunk, flat index
+  auto fetch = [&](u32x4(&buf)[8]) {
+    const int ptp = pgrp * kMatchWaves + wave;
+    const u32x4 *ap = dstp + ((size_t)(2 * ptp) * KS + (size_t)psb * 4) * 64 + lane;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      buf[ks] = ap[(size_t)ks * 64];
+      buf[4 + ks] = ap[a1off + (size_t)ks * 64];
+    }
+    ++pg;
+    if (++psb == NCHUNK) {
+      psb = 0;
+      if (++pgrp == n_groups) pgrp = 0;
+    }
+  };
+  f32x16 acc[2][2];
+  auto clear_acc = [&]() {
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-
-    const u32x4 *ap = dstp + (size_t)(2 * tp) * KS * 64 + lane;
-    const size_t a1off = (size_t)KS * 64;
-    u32x4 abuf[2][8];
-    auto load_chunk = [&](u32x4(&buf)[8], int chunk) {
+  };
+  clear_acc();
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        buf[ks] = ap[(size_t)(chunk * 4 + ks) * 64];
-        buf[4 + ks] = ap[a1off + (size_t)(chunk * 4 + ks) * 64];
-      }
-    };
-    auto compute_chunk = [&](const u32x4(&buf)[8], int chunk) {
+  for (int j = 0; j < kDepth - 1; ++j)
+    if (pg < total) fetch(ring[j]);
+  int grp = g0, sb = 0;                      // chunk being computed
+  for (int f0 = 0; f0 < total; f0 += kDepth) {
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const int s = chunk * 4 + ks;
-        const bf16x8 b0 = __builtin_bit_cast(bf16x8, frag[(size_t)s * 64 + lane]);
-        const bf16x8 b1 = __builtin_bit_cast(bf16x8, frag[(size_t)(KS + s) * 64 + lane]);
-        const bf16x8 a0 = __builtin_bit_cast(bf16x8, buf[ks]);
-        const bf16x8 a1 = __builtin_bit_cast(bf16x8, buf[4 + ks]);
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
-      }
-    };
-    load_chunk(abuf[0], 0);
-    for (int sb = 0; sb < NCHUNK; sb += 2) {
-      if (sb + 1 < NCHUNK) load_chunk(abuf[1], sb + 1);
-      compute_chunk(abuf[0], sb);
-      if (sb + 2 < NCHUNK) load_chunk(abuf[0], sb + 2);
-      if (sb + 1 < NCHUNK) compute_chunk(abuf[1], sb + 1);
-    }
-
-    // fold the four finished 32x32 tiles into the running top-2 of this lane's src columns
+    for (int j = 0; j < kDepth; ++j) {
+      if (f0 + j < total) {
+        if (pg < total) fetch(ring[(j + kDepth - 1) % kDepth]);
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
-      const int row0 = (2 * tp + a) * 32 + h * 4;
-      const f32x4 *ip = (const f32x4 *)(invd + row0);
-      f32x4 iv[4];
-#pragma unroll
-      for (int g = 0; g < 4; ++g) iv[g] = ip[2 * g];
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        float v[16];
-        float m = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          v[r] = acc[a][b][r] * iv[r >> 2][r & 3];
-          m = fmaxf(m, v[r]);
+        for (int ks = 0; ks < 4; ++ks) {
+          const int s = sb * 4 + ks;
+          const bf16x8 b0 = __builtin_bit_cast(bf16x8, frag[(size_t)s * 64 + lane]);
+          const bf16x8 b1 = __builtin_bit_cast(bf16x8, frag[(size_t)(KS + s) * 64 + lane]);
+          const bf16x8 a0 = __builtin_bit_cast(bf16x8, ring[j][ks]);
+          const bf16x8 a1 = __builtin_bit_cast(bf16x8, ring[j][4 + ks]);
+          acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
+          acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
+          acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
+          acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
         }
-        if (__builtin_amdgcn_ballot_w64(m > best[b].v2) != 0) {
+        if (++sb == NCHUNK) {
+          // fold the four finished 32x32 tiles into the running top-2 of this lane's columns
+          const int tp = grp * kMatchWaves + wave;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int j = row0 + (r >> 2) * 8 + (r & 3);
-            if (j < n_dst) top2_insert_ordered(best[b], v[r], j);
+          for (int a = 0; a < 2; ++a) {
+            const int row0 = (2 * tp + a) * 32 + h * 4;
+            const f32x4 *ip = (const f32x4 *)(invd + row0);
+            f32x4 iv[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) iv[g] = ip[2 * g];
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+              float v[16];
+              float m = -INFINITY;
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                v[r] = acc[a][b][r] * iv[r >> 2][r & 3];
+                m = fmaxf(m, v[r]);
+              }
+              if (__builtin_amdgcn_ballot_w64(m > best[b].v2) != 0) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                  const int j2 = row0 + (r >> 2) * 8 + (r & 3);
+                  if (j2 < n_dst) top2_insert_any(best[b], v[r], j2);   // sweep order is circular
+                }
+              }
+            }
           }
+          clear_acc();
+          sb = 0;
+          if (++grp == n_groups) grp = 0;
+          if (wave == 0 && lane == 0) __atomic_store_n(&belt[xcd], grp, __ATOMIC_RELAXED);
         }
       }
     }
@@ -366,6 +408,7 @@ struct MatchWs {
   uint32_t *keys[2];
   int32_t *vals[2];
   uint32_t *hist;
+  int32_t *belt;
   size_t bytes;
   int n_dst_pad, nchunks;
 };
@@ -378,7 +421,7 @@ static MatchWs carve(const Dims &d, const litevggt_plan_t &pl, char *base) {
     off += align_up(bytes, 256);
     return p;
   };
-  w.n_dst_pad = (int)align_up((size_t)pl.n_dst, 64);
+  w.n_dst_pad = (int)align_up((size_t)pl.n_dst, 64 * kMatchWaves);   // whole groups
   w.nchunks = (int)((d.N + kSortChunk - 1) / kSortChunk);
   w.inv = (float *)take((size_t)d.N * 4);
   w.dstp = (u32x4 *)take((size_t)w.n_dst_pad * d.C * 2);
@@ -389,6 +432,7 @@ static MatchWs carve(const Dims &d, const litevggt_plan_t &pl, char *base) {
     w.vals[i] = (int32_t *)take((size_t)d.N * 4);
   }
   w.hist = (uint32_t *)take((size_t)256 * w.nchunks * 4);
+  w.belt = (int32_t *)take(kXcd * sizeof(int32_t));
   w.bytes = off;
   return w;
 }
@@ -415,10 +459,10 @@ int launch_match(const uint16_t *x, const Dims &d, const litevggt_plan_t &pl,
     hipLaunchKernelGGL(k_inv_norm, dim3(rows_grid), dim3(256), 0, st, x, d.N, d.C, w.inv);
     const int64_t pk = (int64_t)w.n_dst_pad * (d.C / 8);
     hipLaunchKernelGGL(k_pack_dst, dim3((unsigned)((pk + 255) / 256)), dim3(256), 0, st, x,
-                       ix.dst_idx, w.inv, n_dst, w.n_dst_pad, d.C, w.dstp, w.invd);
+                       ix.dst_idx, w.inv, n_dst, w.n_dst_pad, d.C, w.dstp, w.invd, w.belt);
     hipLaunchKernelGGL(k_match, dim3((unsigned)((n_src + kSrcTile - 1) / kSrcTile)),
                        dim3(kMatchWaves * 64), lds, st, x, ix.src_idx, n_src, w.dstp, w.invd,
-                       n_dst, w.n_dst_pad / 64, d.C, w.top2);
+                       n_dst, w.n_dst_pad / (64 * kMatchWaves), d.C, w.top2, w.belt);
     const unsigned fin = (unsigned)(((n_src + 3) / 4) < 16384 ? ((n_src + 3) / 4) : 16384);
     hipLaunchKernelGGL(k_match_finish, dim3(fin), dim3(256), 0, st, x, ix.src_idx, ix.dst_idx,
                        w.inv, w.top2, n_src, d.C, ix.anchor_of, ix.slot_of, best_sim);
