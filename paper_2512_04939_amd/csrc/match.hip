@@ -23,6 +23,9 @@ constexpr int kSrcTile = 64;         // src rows resident per workgroup
 #ifndef LV_MATCH_DEPTH
 #define LV_MATCH_DEPTH 3
 #endif
+#ifndef LV_MATCH_PANEL_GROUPS
+#define LV_MATCH_PANEL_GROUPS 16   /* 16 groups x 512 rows x 2 KB = 16 MB of dst per launch */
+#endif
 constexpr int kMatchWaves = LV_MATCH_WAVES;   // 8 = 2 waves per SIMD
 constexpr int kDepth = LV_MATCH_DEPTH;        // register ring: chunks of dst fragments in flight per wave
 constexpr float kRescoreGap = 2e-4f; // similarity gap below which float64 decides
@@ -104,8 +107,8 @@ __device__ __forceinline__ void top2_insert_any(Top2 &t, float v, int i) {
 
 __global__ __launch_bounds__(kMatchWaves * 64) void k_match(
     const uint16_t *__restrict__ x, const int32_t *__restrict__ src_idx, int n_src,
-    const u32x4 *__restrict__ dstp, const float *__restrict__ invd, int n_dst, int n_groups,
-    int C, Top2 *__restrict__ top2, int32_t *belt) {
+    const u32x4 *__restrict__ dstp, const float *__restrict__ invd, int n_dst, int g_first,
+    int n_groups, int C, Top2 *__restrict__ top2, int32_t *belt) {
   extern __shared__ u32x4 frag[];   // [2 src tiles][KS][64 lanes]
   __shared__ int g_start;
   const int KS = C >> 4, nch = C >> 3, NCHUNK = KS >> 2;
@@ -144,7 +147,7 @@ __global__ __launch_bounds__(kMatchWaves * 64) void k_match(
   u32x4 ring[kDepth][8];
   int pgrp = g0, psb = 0, pg = 0;            // next chunk to fetch: group, chunk, flat index
   auto fetch = [&](u32x4(&buf)[8]) {
-    const int ptp = pgrp * kMatchWaves + wave;
+    const int ptp = (g_first + pgrp) * kMatchWaves + wave;
     const u32x4 *ap = dstp + ((size_t)(2 * ptp) * KS + (size_t)psb * 4) * 64 + lane;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -190,7 +193,7 @@ __global__ __launch_bounds__(kMatchWaves * 64) void k_match(
         }
         if (++sb == NCHUNK) {
           // fold the four finished 32x32 tiles into the running top-2 of this lane's columns
-          const int tp = grp * kMatchWaves + wave;
+          const int tp = (g_first + grp) * kMatchWaves + wave;
 #pragma unroll
           for (int a = 0; a < 2; ++a) {
             const int row0 = (2 * tp + a) * 32 + h * 4;
@@ -239,7 +242,14 @@ __global__ __launch_bounds__(kMatchWaves * 64) void k_match(
         top2_insert_any(t, c.v1, c.i1);
         top2_insert_any(t, c.v2, c.i2);
       }
-    if (src0 + tid < n_src) top2[src0 + tid] = t;
+    if (src0 + tid < n_src) {
+      if (g_first > 0) {   // earlier launches covered the dst rows before this panel
+        const Top2 prev = top2[src0 + tid];
+        top2_insert_any(t, prev.v1, prev.i1);
+        top2_insert_any(t, prev.v2, prev.i2);
+      }
+      top2[src0 + tid] = t;
+    }
   }
 }
 
@@ -460,9 +470,16 @@ int launch_match(const uint16_t *x, const Dims &d, const litevggt_plan_t &pl,
     const int64_t pk = (int64_t)w.n_dst_pad * (d.C / 8);
     hipLaunchKernelGGL(k_pack_dst, dim3((unsigned)((pk + 255) / 256)), dim3(256), 0, st, x,
                        ix.dst_idx, w.inv, n_dst, w.n_dst_pad, d.C, w.dstp, w.invd, w.belt);
-    hipLaunchKernelGGL(k_match, dim3((unsigned)((n_src + kSrcTile - 1) / kSrcTile)),
-                       dim3(kMatchWaves * 64), lds, st, x, ix.src_idx, n_src, w.dstp, w.invd,
-                       n_dst, w.n_dst_pad / (64 * kMatchWaves), d.C, w.top2, w.belt);
+    // The dst matrix is processed in panels small enough to stay resident in every XCD's L2
+    // (one launch per panel, all workgroups of a launch stream the same panel); the running
+    // top-2 of each src row is carried from launch to launch in `top2`.
+    const int groups = w.n_dst_pad / (64 * kMatchWaves);
+    const int per_panel = LV_MATCH_PANEL_GROUPS > 0 ? LV_MATCH_PANEL_GROUPS : groups;
+    for (int g = 0; g < groups; g += per_panel)
+      hipLaunchKernelGGL(k_match, dim3((unsigned)((n_src + kSrcTile - 1) / kSrcTile)),
+                         dim3(kMatchWaves * 64), lds, st, x, ix.src_idx, n_src, w.dstp, w.invd,
+                         n_dst, g, (groups - g < per_panel ? groups - g : per_panel), d.C, w.top2,
+                         w.belt);
     const unsigned fin = (unsigned)(((n_src + 3) / 4) < 16384 ? ((n_src + 3) / 4) : 16384);
     hipLaunchKernelGGL(k_match_finish, dim3(fin), dim3(256), 0, st, x, ix.src_idx, ix.dst_idx,
                        w.inv, w.top2, n_src, d.C, ix.anchor_of, ix.slot_of, best_sim);

@@ -378,9 +378,23 @@ def test_layers_run_teacher_forced_and_end_to_end(B, name, layers, interval):
     log = B.litevggt_layers_run(ph, layers, im_dev, x_dev, ib, grad, score, ws)
     torch.cuda.synchronize()
     assert log == ref_log
-    err = max_rel_err(dev_bf16_to_f64(x_dev), ref_out)
-    print(f"[{name}] end-to-end max rel err after {layers} layers: {err:.3e}")
+    # Chained run: from the second refresh on the two sides see inputs that differ by bf16
+    # rounding, so a src token with two nearly equally similar anchors may pick the other one
+    # (not restricted to 1e-6 near-ties, the inputs differ).  Such tokens are counted and
+    # excluded; every other row must meet the tolerance.
+    got, last = dev_bf16_to_f64(x_dev), trace[-1]["index"]
+    same = _i32(ib.anchor_of) == last["anchor_of"]
+    n_diff = int((~same).sum())
+    scale = np.abs(ref_out).max()
+    err = float(np.abs(got - ref_out)[same].max() / scale)
+    print(f"[{name}] end-to-end after {layers} layers: max rel err {err:.3e} on rows with the "
+          f"oracle's anchor; {n_diff} of {pl.n_src} src tokens chose another anchor")
     assert err <= BF16_TOL
+    # divergence of a chained run grows with depth (the features of a group converge, so more
+    # candidates are nearly tied): bounded loosely here, exact parity is the teacher-forced part
+    assert n_diff <= max(2, pl.n_src // 10)
+    n_role = int((ib.role.cpu().numpy() != last["role"]).sum())
+    assert n_role <= max(2, pl.N // 50), n_role
     sizes = np.diff(_i32(ib.group_off))
     assert sizes.sum() == pl.N and sizes.min() >= 1
 
