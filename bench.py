@@ -146,6 +146,7 @@ def main():
     wl = synth.workload(args.workload, **over)
     attn_dtype = B.ATTN_BF16 if args.attn_dtype == "bf16" else B.ATTN_FP8_E4M3
     ph = hip_params(wl, attn_dtype=attn_dtype)
+    wl_qk_norm = bool(ph.qk_norm)
     pl = B.litevggt_plan(ph)
     L, C_ = wl.layers, wl.dim
 
@@ -257,7 +258,7 @@ def main():
                    "refresh_log": log, "output_finite": finite,
                    "peak_hbm_alloc_gib": torch.cuda.max_memory_allocated() / 2 ** 30,
                    "input_generation_s": gen_s},
-        "roofline": {"kernel": "k_attn_bf16", "bound": "mfma", "achieved": attn_tf, "peak": peak_tf,
+        "roofline": {"kernel": "k_attn_bf16_bounded" if wl_qk_norm else "k_attn_bf16", "bound": "mfma", "achieved": attn_tf, "peak": peak_tf,
                      "unit": "TFLOP/s", "frac": attn_tf / peak_tf, "traffic": None,
                      "flop_per_launch": attn_flop, "avg_launch_ms": avg["attn"],
                      "launches_timed": len(dur["attn"])},

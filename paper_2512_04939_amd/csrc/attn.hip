@@ -446,34 +446,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   f32x16 sacc[2];      // [query block]: scores of its current 32-key tile
   u32x4 pb[2][2];      // [query block][u]: bf16 weights of its current 32-key tile
+  // Fragments held in registers: fv = V fragments of tile t, fk = K fragments of tile t+1.
+  // They are read from LDS once, during phase A(t) -- each right after the MFMAs that used
+  // the previous contents have been issued -- and feed both query blocks: phases B(t), A(t+1).
+  u32x4 fv[4], fk[4];
 
-  auto mma_s = [&](int t, int sub) {
+  auto load_v = [&](int t, u32x4(&dst)[4]) {
+    const u32x4 *vt = &vs[(t >> 1) & (kBStages - 1)][(t & 1) * 4 * kFragU4 + lane];
+#pragma unroll
+    for (int f = 0; f < 4; ++f) dst[f] = vt[f * kFragU4];
+  };
+  auto load_k = [&](int t, u32x4(&dst)[4]) {
     const u32x4 *kt = &ks[(t >> 1) & (kBStages - 1)][(t & 1) * 4 * kFragU4 + lane];
+#pragma unroll
+    for (int f = 0; f < 4; ++f) dst[f] = kt[f * kFragU4];
+  };
+  auto mma_s = [&](int sub, const u32x4(&kf)[4]) {
     f32x16 acc = kZero;
 #pragma unroll
     for (int s = 0; s < 4; ++s)
-#ifdef LV_ATTN_NOLDS   /* timing experiment only: wrong results */
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[sub ^ 1][s], qf[sub][s], acc, 0, 0, 0);
-#else
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kt[s * kFragU4]),
-                                                    qf[sub][s], acc, 0, 0, 0);
-#endif
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[s]), qf[sub][s],
+                                                    acc, 0, 0, 0);
     sacc[sub] = acc;
   };
-  auto mma_pv = [&](int t, int sub) {
-    const u32x4 *vt = &vs[(t >> 1) & (kBStages - 1)][(t & 1) * 4 * kFragU4 + lane];
+  auto mma_pv = [&](int sub, const u32x4(&vf)[4]) {
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int dt = 0; dt < 2; ++dt)
-#ifdef LV_ATTN_NOLDS
         oacc[sub][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            qf[sub][u * 2 + dt], __builtin_bit_cast(bf16x8, pb[sub][u]), oacc[sub][dt], 0, 0, 0);
-#else
-        oacc[sub][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            __builtin_bit_cast(bf16x8, vt[(u * 2 + dt) * kFragU4]),
-            __builtin_bit_cast(bf16x8, pb[sub][u]), oacc[sub][dt], 0, 0, 0);
-#endif
+            __builtin_bit_cast(bf16x8, vf[u * 2 + dt]), __builtin_bit_cast(bf16x8, pb[sub][u]),
+            oacc[sub][dt], 0, 0, 0);
   };
   auto mask_tail = [&](int t, int sub) {   // keys beyond the sequence end
     if ((int64_t)(t + 1) * kKT > n) {
@@ -499,29 +502,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
     lrow[sub] = ls;
   };
-  // One phase = 8 MFMAs + the weights of 16 scores per lane (16 exp2, 8 pack, 8 dot2).
-  auto recipe = [&]() {
+  // One phase = 8 MFMAs + the weights of 16 scores per lane (16 exp2, 8 pack, 8 dot2).  The
+  // recipe asks the scheduler to spread the MFMAs over the VALU work; A phases re-fill fv
+  // after their 4 PV MFMAs and fk after their 4 score MFMAs.  (Forcing a strict
+  // exp2/exp2/MFMA/pack/dot2 order with opaque pins was measured slower than this.)
+  auto recipe = [&](bool with_loads) {
 #if LV_ATTN_RECIPE
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);     // fragment reads of the phase
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // 2 exp2
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // pack + dot2
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // 2 exp2
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // pack + dot2
+      }
+      if (with_loads) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);   // 4 LDS reads
     }
 #endif
   };
-  auto phase_a = [&](int t) {              // t >= 1
+  // A(t), t >= 1: weights of block 0 || PV(t-1) and scores(t) of block 1
+  auto phase_a = [&](int t) {
     weights(0);
-    mma_pv(t - 1, 1);
-    mma_s(t, 1);
-    recipe();
+    mma_pv(1, fv);
+    load_v(t, fv);
+    mma_s(1, fk);
+    if (t + 1 < nkt) load_k(t + 1, fk);
+    recipe(true);
   };
-  auto phase_b = [&](int t) {              // t <= nkt-2
+  // B(t), t <= nkt-2: weights of block 1 || PV(t) and scores(t+1) of block 0
+  auto phase_b = [&]() {
     weights(1);
-    mma_pv(t, 0);
-    mma_s(t + 1, 0);
-    recipe();
+    mma_pv(0, fv);
+    mma_s(0, fk);
+    recipe(false);
   };
 
   g2r(0);
@@ -531,35 +544,38 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     r2s(1);
   }
   __syncthreads();
-  // prologue
-  mma_s(0, 0);
+  // prologue: scores of tile 0 for both blocks, weights of block 0, then fv = V(0), fk = K(1)
+  load_k(0, fk);
+  mma_s(0, fk);
   mask_tail(0, 0);
   weights(0);
-  mma_s(0, 1);
+  mma_s(1, fk);
+  load_v(0, fv);
+  load_k(1, fk);
   if (nkv == 1) mask_tail(0, 1);
   // steady state: stage i holds tiles 2i, 2i+1; stage i+2 is fetched meanwhile
   for (int i = 0; i < nkv - 1; ++i) {
     if (i + 2 < nkv) g2r(i + 2);
-    phase_b(2 * i);
-    phase_a(2 * i + 1);
-    phase_b(2 * i + 1);
+    phase_b();                             // B(2i)
+    phase_a(2 * i + 1);                    // A(2i+1)
+    phase_b();                             // B(2i+1)
     if (i == nkv - 2) {                    // entering the last stage: its tiles may be ragged
       mask_tail(2 * i + 1, 1);             // (no-op unless n is tiny)
       mask_tail(2 * i + 2, 0);
     }
-    phase_a(2 * i + 2);
+    phase_a(2 * i + 2);                    // A(2i+2)
     if (i == nkv - 2) mask_tail(2 * i + 2, 1);
     if (i + 2 < nkv) r2s(i + 2);
     __syncthreads();
   }
   // last stage: tiles nkt-2, nkt-1
-  phase_b(nkt - 2);
+  phase_b();                               // B(nkt-2)
   mask_tail(nkt - 1, 0);
-  phase_a(nkt - 1);
+  phase_a(nkt - 1);                        // A(nkt-1): loads V(nkt-1) only
   mask_tail(nkt - 1, 1);
   weights(1);
-  mma_pv(nkt - 1, 0);
-  mma_pv(nkt - 1, 1);
+  mma_pv(0, fv);
+  mma_pv(1, fv);
 
 #pragma unroll
   for (int sub = 0; sub < 2; ++sub) {
