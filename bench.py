@@ -258,7 +258,7 @@ def main():
                    "refresh_log": log, "output_finite": finite,
                    "peak_hbm_alloc_gib": torch.cuda.max_memory_allocated() / 2 ** 30,
                    "input_generation_s": gen_s},
-        "roofline": {"kernel": "k_attn_bf16_bounded" if wl_qk_norm else "k_attn_bf16", "bound": "mfma", "achieved": attn_tf, "peak": peak_tf,
+        "roofline": {"kernel": ("k_attn_fp8" if args.attn_dtype == "fp8" else "k_attn_bf16_bounded" if wl_qk_norm else "k_attn_bf16"), "bound": "mfma", "achieved": attn_tf, "peak": peak_tf,
                      "unit": "TFLOP/s", "frac": attn_tf / peak_tf, "traffic": None,
                      "flop_per_launch": attn_flop, "avg_launch_ms": avg["attn"],
                      "launches_timed": len(dur["attn"])},

@@ -47,6 +47,7 @@ class Params:
     var_pool: int = 3           # window of the local average pooling (paper silent)
     refresh_interval: int = 6   # Sec. 3.4 "Cached Token Merging"
     qk_norm: bool = False       # layer loop: RMS-normalise q and k per head (see global_layer)
+    attn_fp8: bool = False      # layer loop: FP8 E4M3 attention emulation (see attention_fp8)
 
     @property
     def patches(self) -> int:
@@ -367,6 +368,39 @@ def round_e4m3(a: np.ndarray) -> np.ndarray:
     return s * np.minimum(q, 448.0)
 
 
+def quantize_e4m3(a: np.ndarray) -> Tuple[np.ndarray, float]:
+    """Per-tensor FP8 E4M3 quantisation with the scale taken from the tensor itself
+    (scale = amax / 448): returns (codes as float64 values, scale)."""
+    af = np.asarray(a, dtype=np.float64)
+    amax = float(np.abs(af).max()) if af.size else 0.0
+    scale = amax / 448.0 if amax > 0 else 1.0
+    return round_e4m3(af / scale), scale
+
+
+def attention_fp8(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: Optional[float] = None,
+                  quantize_p: bool = True, p_scale: float = 256.0, block: int = 1024) -> np.ndarray:
+    """Emulation of the FP8 attention variant (the paper's FP8 recipe, supplementary "FP8
+    Quantization Details", is E4M3 through Transformer Engine on the aggregator's linear
+    modules; applying E4M3 with per-tensor scales to the attention core is this benchmark's
+    choice): q, k, v quantised per tensor, scores and softmax in float64, the weights
+    exp(s - rowmax) quantised to E4M3 at scale 1/p_scale for the second product, the
+    normaliser taken from the unquantised weights."""
+    q8, sq = quantize_e4m3(q)
+    k8, sk = quantize_e4m3(k)
+    v8, sv = quantize_e4m3(v)
+    M, h, d = k8.shape
+    sc = (1.0 / np.sqrt(d) if scale is None else float(scale)) * sq * sk
+    out = np.empty((q8.shape[0], h, d), dtype=np.float64)
+    for hh in range(h):
+        for b0 in range(0, q8.shape[0], block):
+            s = (q8[b0:b0 + block, hh, :] @ k8[:, hh, :].T) * sc
+            s -= s.max(axis=1, keepdims=True)
+            e = np.exp(s)
+            e8 = round_e4m3(e * p_scale) / p_scale if quantize_p else e
+            out[b0:b0 + block, hh, :] = (e8 @ v8[:, hh, :]) * sv / e.sum(axis=1, keepdims=True)
+    return out
+
+
 # ---------------------------------------------------------------------------
 # cached-index layer driver  (Sec. 3.4: indices recomputed every refresh_interval layers)
 # ---------------------------------------------------------------------------
@@ -397,7 +431,8 @@ def global_layer(x: np.ndarray, idx: Dict[str, np.ndarray], p: Params,
     z = store(merge(x, idx["group_off"], idx["group_mem"]))
     zz = z.reshape(z.shape[0], p.heads, p.head_dim)
     qk = store(qk_normalize(zz)) if p.qk_norm else zz
-    y = store(attention(qk, qk, zz).reshape(z.shape))
+    attn = attention_fp8 if p.attn_fp8 else attention
+    y = store(attn(qk, qk, zz).reshape(z.shape))
     return store(unmerge(y, idx["slot_of"], residual=x))
 
 

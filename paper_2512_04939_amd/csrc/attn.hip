@@ -99,12 +99,6 @@ constexpr int kVSlots = 3;           // LDS ring slots of 64-key V tiles
 // row sums).  The two groups run exactly one phase apart, with a workgroup barrier at every
 // phase boundary, so on every SIMD one wave feeds the matrix pipe while the other feeds the
 // VALU -- deterministically, not by luck of the wave scheduler.
-//
-// BOUNDED (used with qk_norm when the scale allows): q and k have unit RMS per head, so
-// |q.k| <= 64 (Cauchy-Schwarz, plus bf16 rounding slack) and the scores need no running
-// maximum at all: softmax is invariant to the reference, so the weights are exp2(s') with the
-// scale folded into q before its bf16 rounding -- no max, no subtraction, no rescaling.
-template <bool BOUNDED>
 __global__ __launch_bounds__(512) void k_attn_bf16(
     const uint16_t *__restrict__ q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp,
     uint16_t *__restrict__ o, int64_t n, int heads, int n_kt, int nqb, float c, int qk_norm) {
@@ -137,8 +131,7 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
     if (qk_norm) {   // this lane holds 32 of the row's 64 values, lane^32 the other 32
       float ss = (sumsq8(w[0]) + sumsq8(w[1])) + (sumsq8(w[2]) + sumsq8(w[3]));
       ss += __shfl_xor(ss, 32, 64);
-      // BOUNDED: the softmax scale (in log2 units) rides along, one rounding for both
-      const float r = (BOUNDED ? c : 1.0f) / sqrtf(ss * (1.0f / 64.0f) + kQkEps);
+      const float r = 1.0f / sqrtf(ss * (1.0f / 64.0f) + kQkEps);
 #pragma unroll
       for (int s = 0; s < 4; ++s) w[s] = scale8(w[s], r);
     }
@@ -248,7 +241,7 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
     }
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
-      if (!BOUNDED) {
+      {
         float mx = -INFINITY;
 #pragma unroll
         for (int kt2 = 0; kt2 < 2; ++kt2)
@@ -276,8 +269,8 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float s0 = sacc[kt2][sub][8 * u + 2 * e], s1 = sacc[kt2][sub][8 * u + 2 * e + 1];
-            const float p0 = __builtin_amdgcn_exp2f(BOUNDED ? s0 : __builtin_fmaf(s0, c, -mc[sub]));
-            const float p1 = __builtin_amdgcn_exp2f(BOUNDED ? s1 : __builtin_fmaf(s1, c, -mc[sub]));
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0, c, -mc[sub]));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1, c, -mc[sub]));
             w[e] = pack_bf16(p0, p1);
             // row sum of the bf16-rounded weights (what the second MFMA really multiplies)
             ls = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e]), kOnes, ls, false);
@@ -596,6 +589,345 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// FP8 (E4M3, OCP "fn": bias 7, max 448) variant: q, k, v are quantised per tensor with
+// scale = amax/448 taken in the same call, the softmax weights with a fixed scale 2^8; the
+// MFMAs are v_mfma_f32_32x32x16_fp8_fp8, everything else (scores, max, sums, O) stays fp32.
+// ---------------------------------------------------------------------------------------
+constexpr float kFp8Max = 448.0f;
+constexpr float kFp8PShift = 8.0f;   // weights are stored as 2^8 * p, p <= 1 at the reference
+constexpr float kFp8Raise = 0.75f;   // 2^(8 + 0.75) < 448: the reference follows the maximum closely
+
+__device__ __forceinline__ uint32_t cvt4_fp8(float a, float b, float c, float d) {
+  uint32_t w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0u, false);
+  return __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
+}
+__device__ __forceinline__ float clamp448(float x) { return fminf(fmaxf(x, -kFp8Max), kFp8Max); }
+// 8 bf16 values scaled by r and quantised to 8 fp8 bytes
+__device__ __forceinline__ u32x2 quant8(const u32x4 w, float r) {
+  return u32x2{cvt4_fp8(clamp448(bf16_lo(w.x) * r), clamp448(bf16_hi(w.x) * r),
+                        clamp448(bf16_lo(w.y) * r), clamp448(bf16_hi(w.y) * r)),
+               cvt4_fp8(clamp448(bf16_lo(w.z) * r), clamp448(bf16_hi(w.z) * r),
+                        clamp448(bf16_lo(w.w) * r), clamp448(bf16_hi(w.w) * r))};
+}
+__device__ __forceinline__ float absmax8(const u32x4 w) {
+  const float a = fmaxf(fmaxf(fabsf(bf16_lo(w.x)), fabsf(bf16_hi(w.x))), fmaxf(fabsf(bf16_lo(w.y)), fabsf(bf16_hi(w.y))));
+  const float b = fmaxf(fmaxf(fabsf(bf16_lo(w.z)), fabsf(bf16_hi(w.z))), fmaxf(fabsf(bf16_lo(w.w)), fabsf(bf16_hi(w.w))));
+  return fmaxf(a, b);
+}
+// bf16 values of w scaled by r and rounded to bf16 (the normalised q/k as the bf16 path sees them)
+__device__ __forceinline__ u32x4 norm8(const u32x4 w, float ss_head, int qk_norm) {
+  return qk_norm ? scale8(w, 1.0f / sqrtf(ss_head * (1.0f / 64.0f) + kQkEps)) : w;
+}
+
+__global__ void k_attn_amax_zero(uint32_t *amax) {
+  if (threadIdx.x < 4) amax[threadIdx.x] = 0u;
+}
+
+// amax[0..2] = max |q^|, |k^|, |v| over the call's tensors (q^, k^ normalised when qk_norm).
+// One thread per 8-value chunk; the 8 lanes of a (row, head) combine their sums of squares.
+__global__ __launch_bounds__(256) void k_attn_amax(const uint16_t *__restrict__ q,
+                                                   const uint16_t *__restrict__ k,
+                                                   const uint16_t *__restrict__ v, int64_t n, int C,
+                                                   int qk_norm, uint32_t *__restrict__ amax) {
+  __shared__ float red[3][4];
+  const int64_t nchunks = n * (C >> 3);
+  float mq = 0.f, mk = 0.f, mv = 0.f;
+  // the 8 lanes that share a (row, head) hold consecutive chunk indices, so they enter and
+  // leave this loop together and the xor-shuffles below only read lanes that are active
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nchunks;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const u32x4 wq = ((const u32x4 *)q)[i], wk = ((const u32x4 *)k)[i], wv = ((const u32x4 *)v)[i];
+    float sq = sumsq8(wq), sk = sumsq8(wk);
+    for (int o = 1; o < 8; o <<= 1) {
+      sq += __shfl_xor(sq, o, 64);
+      sk += __shfl_xor(sk, o, 64);
+    }
+    mq = fmaxf(mq, absmax8(norm8(wq, sq, qk_norm)));
+    mk = fmaxf(mk, absmax8(norm8(wk, sk, qk_norm)));
+    mv = fmaxf(mv, absmax8(wv));
+  }
+  mq = wave_max(mq);
+  mk = wave_max(mk);
+  mv = wave_max(mv);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (lane == 0) {
+    red[0][wave] = mq;
+    red[1][wave] = mk;
+    red[2][wave] = mv;
+  }
+  __syncthreads();
+  if (threadIdx.x < 3) {
+    const float m = fmaxf(fmaxf(red[threadIdx.x][0], red[threadIdx.x][1]),
+                          fmaxf(red[threadIdx.x][2], red[threadIdx.x][3]));
+    atomicMax(&amax[threadIdx.x], __float_as_uint(m));   // non-negative floats order like uints
+  }
+}
+
+__device__ __forceinline__ float fp8_scale_inv(uint32_t amax_bits) {   // 448 / amax (1 if amax = 0)
+  const float a = __uint_as_float(amax_bits);
+  return a > 0.f ? kFp8Max / a : 1.0f;
+}
+
+// fp8 counterpart of k_attn_pack: same fragment-major orders with 8 bytes per lane.
+__global__ __launch_bounds__(256) void k_attn_pack_fp8(const uint16_t *__restrict__ k,
+                                                       const uint16_t *__restrict__ v, int64_t n,
+                                                       int heads, int n_kt, int qk_norm,
+                                                       const uint32_t *__restrict__ amax,
+                                                       u32x2 *__restrict__ kp, u32x2 *__restrict__ vp) {
+  __shared__ __attribute__((aligned(8))) uint8_t vt[kKT][72];
+  const int kt = blockIdx.x, head = blockIdx.y, t = threadIdx.x;
+  const int C = heads * 64;
+  const int key = t >> 3, chunk = t & 7;
+  const int64_t row = (int64_t)kt * kKT + key;
+  u32x4 wk = {0u, 0u, 0u, 0u}, wv = {0u, 0u, 0u, 0u};
+  if (row < n) {
+    wk = *(const u32x4 *)(k + (size_t)row * C + head * 64 + chunk * 8);
+    wv = *(const u32x4 *)(v + (size_t)row * C + head * 64 + chunk * 8);
+  }
+  float ss = sumsq8(wk);
+  for (int o = 1; o < 8; o <<= 1) ss += __shfl_xor(ss, o, 64);
+  wk = norm8(wk, ss, qk_norm);
+  const size_t tile = ((size_t)head * n_kt + kt) * 4 * kFragU4;
+  kp[tile + (chunk >> 1) * kFragU4 + (chunk & 1) * 32 + key] = quant8(wk, fp8_scale_inv(amax[1]));
+  *(u32x2 *)&vt[key][chunk * 8] = quant8(wv, fp8_scale_inv(amax[2]));
+  __syncthreads();
+  const int u = t >> 7, dt = (t >> 6) & 1, lane = t & 63, h = lane >> 5, dr = lane & 31;
+  uint32_t w[2] = {0u, 0u};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int k0 = 16 * u + 8 * (e >> 2) + 4 * h + (e & 3);
+    w[e >> 2] |= (uint32_t)vt[k0][32 * dt + dr] << (8 * (e & 3));
+  }
+  vp[tile + (u * 2 + dt) * kFragU4 + lane] = u32x2{w[0], w[1]};
+}
+
+// Same structure as k_attn_bf16 (two phase groups, lazily raised reference) on fp8 operands.
+__global__ __launch_bounds__(512) void k_attn_fp8(
+    const uint16_t *__restrict__ q, const u32x2 *__restrict__ kp, const u32x2 *__restrict__ vp,
+    uint16_t *__restrict__ o, int64_t n, int heads, int n_kt, int nqb, float c_in, int qk_norm,
+    const uint32_t *__restrict__ amax) {
+  __shared__ u32x2 ks[kKSlots][8 * kFragU4];
+  __shared__ u32x2 vs[kVSlots][8 * kFragU4];
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ql = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2;
+  const int C = heads * 64;
+  int head, qb;
+  if ((heads & 7) == 0) {
+    const int hp = heads >> 3, xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    head = xcd * hp + local / nqb;
+    qb = local % nqb;
+  } else {
+    head = blockIdx.x / nqb;
+    qb = blockIdx.x % nqb;
+  }
+  const int64_t q0 = (int64_t)qb * kQB + wave * kQW;
+  const float inv_sq = fp8_scale_inv(amax[0]);
+  // scores come out in units of scale_q*scale_k; fold both into the exponent scale
+  const float c = c_in * (1.0f / inv_sq) * (1.0f / fp8_scale_inv(amax[1]));
+  const float out_scale = 1.0f / fp8_scale_inv(amax[2]);
+
+  long qf[2][4];
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) {
+    const int64_t row = min(q0 + sub * 32 + ql, n - 1);
+    const uint16_t *qp = q + (size_t)row * C + head * 64 + 8 * h;
+    u32x4 w[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) w[s] = *(const u32x4 *)(qp + 16 * s);
+    float ss = (sumsq8(w[0]) + sumsq8(w[1])) + (sumsq8(w[2]) + sumsq8(w[3]));
+    ss += __shfl_xor(ss, 32, 64);
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      qf[sub][s] = __builtin_bit_cast(long, quant8(norm8(w[s], ss, qk_norm), inv_sq));
+  }
+
+  f32x16 oacc[2][2];
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[sub][dt][r] = 0.f;
+  float mref[2] = {-INFINITY, -INFINITY}, mc[2] = {0.f, 0.f}, lrow[2] = {0.f, 0.f};
+
+  const int nkv = n_kt >> 1;
+  const u32x2 *kh = kp + (size_t)head * n_kt * 4 * kFragU4;
+  const u32x2 *vh = vp + (size_t)head * n_kt * 4 * kFragU4;
+  u32x2 rk, rv;
+  auto g2r = [&](int j) {
+    const size_t off = (size_t)j * 8 * kFragU4;
+    rk = kh[off + tid];
+    rv = vh[off + tid];
+  };
+  auto r2s = [&](int j) {
+    ks[j % kKSlots][tid] = rk;
+    vs[j % kVSlots][tid] = rv;
+  };
+
+  f32x16 sacc[2][2];
+  u32x2 pb[2][2][2];
+
+  auto phase_m = [&](int j) {
+    __builtin_amdgcn_sched_barrier(0);
+    if (j > 0) {
+      const u32x2 *vt = &vs[(j - 1) % kVSlots][lane];
+      u32x2 vf[8];
+#pragma unroll
+      for (int f = 0; f < 8; ++f) vf[f] = vt[f * kFragU4];
+#pragma unroll
+      for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt) {
+            const long a = __builtin_bit_cast(long, vf[(kt2 * 2 + u) * 2 + dt]);
+            oacc[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(
+                a, __builtin_bit_cast(long, pb[0][kt2][u]), oacc[0][dt], 0, 0, 0);
+            oacc[1][dt] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(
+                a, __builtin_bit_cast(long, pb[1][kt2][u]), oacc[1][dt], 0, 0, 0);
+          }
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (j < nkv) {
+      const u32x2 *kt = &ks[j % kKSlots][lane];
+      u32x2 kf[8];
+#pragma unroll
+      for (int f = 0; f < 8; ++f) kf[f] = kt[f * kFragU4];
+#pragma unroll
+      for (int kt2 = 0; kt2 < 2; ++kt2) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sacc[kt2][sub][r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const long a = __builtin_bit_cast(long, kf[kt2 * 4 + s]);
+          sacc[kt2][0] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, qf[0][s], sacc[kt2][0], 0, 0, 0);
+          sacc[kt2][1] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, qf[1][s], sacc[kt2][1], 0, 0, 0);
+        }
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+    }
+    asm volatile("" : "+v"(sacc[0][0]), "+v"(sacc[0][1]), "+v"(sacc[1][0]), "+v"(sacc[1][1]),
+                 "+v"(oacc[0][0]), "+v"(oacc[0][1]), "+v"(oacc[1][0]), "+v"(oacc[1][1]));
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto phase_v = [&](int j) {
+    __builtin_amdgcn_sched_barrier(0);
+    if (j == nkv - 1) {
+      const int64_t kbase = (int64_t)j * kKV;
+      if (kbase + kKV > n) {
+#pragma unroll
+        for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int64_t key = kbase + kt2 * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+            if (key >= n) {
+              sacc[kt2][0][r] = -INFINITY;
+              sacc[kt2][1][r] = -INFINITY;
+            }
+          }
+      }
+    }
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) mx = max3(mx, sacc[kt2][sub][r], sacc[kt2][sub][r + 1]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      if (__builtin_amdgcn_ballot_w64((mx - mref[sub]) * c > kFp8Raise) != 0) {
+        const float mnew = fmaxf(mref[sub], mx);
+        const float alpha = __builtin_amdgcn_exp2f((mref[sub] - mnew) * c);
+        mref[sub] = mnew;
+        mc[sub] = mnew * c - kFp8PShift;
+        lrow[sub] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[sub][dt][r] *= alpha;
+      }
+      float ls = lrow[sub];
+#pragma unroll
+      for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          float pv[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt2][sub][8 * u + e], c, -mc[sub]));
+            ls += pv[e];   // row sum of the fp32 weights, before the cast
+          }
+          pb[sub][kt2][u] = u32x2{cvt4_fp8(pv[0], pv[1], pv[2], pv[3]), cvt4_fp8(pv[4], pv[5], pv[6], pv[7])};
+        }
+      lrow[sub] = ls;
+    }
+    asm volatile("" : "+v"(pb[0][0][0]), "+v"(pb[0][0][1]), "+v"(pb[0][1][0]), "+v"(pb[0][1][1]),
+                 "+v"(pb[1][0][0]), "+v"(pb[1][0][1]), "+v"(pb[1][1][0]), "+v"(pb[1][1][1]),
+                 "+v"(lrow[0]), "+v"(lrow[1]));
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  g2r(0);
+  r2s(0);
+  __syncthreads();
+  if (grp == 0) {
+    for (int j = 0; j < nkv; ++j) {
+      if (j + 1 < nkv) g2r(j + 1);
+      phase_m(j);
+      __syncthreads();
+      if (j + 1 < nkv) r2s(j + 1);
+      phase_v(j);
+      __syncthreads();
+    }
+    phase_m(nkv);
+    __syncthreads();
+    __syncthreads();
+  } else {
+    if (nkv > 1) g2r(1);
+    __syncthreads();
+    if (nkv > 1) r2s(1);
+    phase_m(0);
+    __syncthreads();
+    for (int j = 1; j < nkv; ++j) {
+      if (j + 1 < nkv) g2r(j + 1);
+      phase_v(j - 1);
+      __syncthreads();
+      if (j + 1 < nkv) r2s(j + 1);
+      phase_m(j);
+      __syncthreads();
+    }
+    phase_v(nkv - 1);
+    __syncthreads();
+    phase_m(nkv);
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) {
+    const float l = lrow[sub] + __shfl_xor(lrow[sub], 32, 64);
+    const float inv = out_scale / l;
+    const int64_t row = q0 + sub * 32 + ql;
+    if (row < n) {
+      uint16_t *op = o + (size_t)row * C + head * 64 + 4 * h;
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          u32x2 w = {pack_bf16(oacc[sub][dt][4 * g] * inv, oacc[sub][dt][4 * g + 1] * inv),
+                     pack_bf16(oacc[sub][dt][4 * g + 2] * inv, oacc[sub][dt][4 * g + 3] * inv)};
+          *(u32x2 *)(op + 32 * dt + 8 * g) = w;
+        }
+    }
+  }
+}
+
 #ifdef LV_ATTN_TRACE
 extern "C" int lv_debug_attn_trace(unsigned long long *host_out) {
   return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_attn_trace), sizeof(g_attn_trace));
@@ -605,24 +937,42 @@ extern "C" int lv_debug_attn_trace(unsigned long long *host_out) {
 static int n_key_tiles(int64_t n) { return (int)(2 * ((n + kKV - 1) / kKV)); }
 
 size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype) {
-  (void)attn_dtype;
-  const size_t per = (size_t)heads * n_key_tiles(n_tokens) * 4 * kFragU4 * sizeof(u32x4);
-  return 2 * align_up(per, 256);
+  const size_t elem = attn_dtype == LV_ATTN_FP8_E4M3 ? sizeof(u32x2) : sizeof(u32x4);
+  const size_t per = (size_t)heads * n_key_tiles(n_tokens) * 4 * kFragU4 * elem;
+  return 256 + 2 * align_up(per, 256);   // [amax block][K fragments][V fragments]
 }
 
 int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_t *o,
                 int64_t n, int heads, float scale, int attn_dtype, int qk_norm, void *ws,
                 hipStream_t st, hipEvent_t after_pack) {
-  if (attn_dtype != LV_ATTN_BF16) return LV_ERR_DTYPE;
   const int n_kt = n_key_tiles(n);
+  const float c = scale * 1.4426950408889634f;
+  const int nqb = (int)((n + kQB - 1) / kQB);
+  uint32_t *amax = (uint32_t *)ws;
+  char *frag = (char *)ws + 256;
+  if (attn_dtype == LV_ATTN_FP8_E4M3) {
+    const size_t per = align_up((size_t)heads * n_kt * 4 * kFragU4 * sizeof(u32x2), 256);
+    u32x2 *kp = (u32x2 *)frag, *vp = (u32x2 *)(frag + per);
+    const int C = heads * 64;
+    const int64_t nchunks = n * (C / 8);
+    const unsigned ag = (unsigned)(((nchunks + 255) / 256) < 4096 ? ((nchunks + 255) / 256) : 4096);
+    hipLaunchKernelGGL(k_attn_amax_zero, dim3(1), dim3(64), 0, st, amax);
+    hipLaunchKernelGGL(k_attn_amax, dim3(ag), dim3(256), 0, st, q, k, v, n, C, qk_norm, amax);
+    hipLaunchKernelGGL(k_attn_pack_fp8, dim3((unsigned)n_kt, (unsigned)heads), dim3(256), 0, st, k,
+                       v, n, heads, n_kt, qk_norm, amax, kp, vp);
+    if (after_pack && hipEventRecord(after_pack, st) != hipSuccess) return LV_ERR_HIP;
+    hipLaunchKernelGGL(k_attn_fp8, dim3((unsigned)(nqb * heads)), dim3(512), 0, st, q, kp, vp, o, n,
+                       heads, n_kt, nqb, c, qk_norm, amax);
+    LV_HIP_CHECK_LAUNCH();
+    return LV_OK;
+  }
+  if (attn_dtype != LV_ATTN_BF16) return LV_ERR_DTYPE;
   const size_t per = align_up((size_t)heads * n_kt * 4 * kFragU4 * sizeof(u32x4), 256);
-  u32x4 *kp = (u32x4 *)ws;
-  u32x4 *vp = (u32x4 *)((char *)ws + per);
+  u32x4 *kp = (u32x4 *)frag;
+  u32x4 *vp = (u32x4 *)(frag + per);
   hipLaunchKernelGGL(k_attn_pack, dim3((unsigned)n_kt, (unsigned)heads), dim3(256), 0, st, k, v, n,
                      heads, n_kt, qk_norm, kp, vp);
   if (after_pack && hipEventRecord(after_pack, st) != hipSuccess) return LV_ERR_HIP;
-  const int nqb = (int)((n + kQB - 1) / kQB);
-  const float c = scale * 1.4426950408889634f;
   // |q.k| <= 64 * (1 + 2^-8) for unit-RMS heads rounded to bf16; exp2 of the scaled score must
   // stay well inside fp32 range even summed over the sequence
   const bool bounded = qk_norm && 64.25f * c <= 64.0f;
@@ -630,9 +980,10 @@ int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_
     const int nqb2 = (int)((n + kBQB - 1) / kBQB);
     hipLaunchKernelGGL(k_attn_bf16_bounded, dim3((unsigned)(nqb2 * heads)), dim3(256), 0, st, q,
                        kp, vp, o, n, heads, n_kt, nqb2, c);
-  } else
-    hipLaunchKernelGGL(k_attn_bf16<false>, dim3((unsigned)(nqb * heads)), dim3(512), 0, st, q, kp,
-                       vp, o, n, heads, n_kt, nqb, c, qk_norm);
+  } else {
+    hipLaunchKernelGGL(k_attn_bf16, dim3((unsigned)(nqb * heads)), dim3(512), 0, st, q, kp, vp, o,
+                       n, heads, n_kt, nqb, c, qk_norm);
+  }
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;
 }

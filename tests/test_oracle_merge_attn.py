@@ -129,6 +129,28 @@ def test_layer_with_qk_norm_stays_bounded_over_depth():
     assert np.abs(out).max() <= 2.0 ** 12 * np.abs(x).max()
 
 
+def test_attention_fp8_emulation_properties():
+    # inputs that E4M3 holds exactly (small integers, amax 448 * 2^-5 = 14) and unquantised
+    # weights: the emulation must reproduce exact attention
+    rng = np.random.default_rng(45)
+    q = rng.integers(-3, 4, size=(40, 2, 16)).astype(np.float64)
+    k = rng.integers(-3, 4, size=(40, 2, 16)).astype(np.float64)
+    v = rng.integers(-7, 8, size=(40, 2, 16)).astype(np.float64)
+    for a in (q, k, v):
+        a[0, 0, 0] = 14.0
+    assert np.allclose(O.attention_fp8(q, k, v, quantize_p=False), O.attention(q, k, v), atol=1e-12)
+    codes, sc = O.quantize_e4m3(v)
+    assert sc == 14.0 / 448.0 and np.array_equal(codes * sc, v)
+    # with everything quantised the result stays within the FP8 budget of the exact one and
+    # the weights still form a convex combination (constant V is reproduced up to its own rounding)
+    q, k, v = synth.random_qkv(200, 2, 64, seed=46)
+    exact = O.attention(q, k, v)
+    emu = O.attention_fp8(q, k, v)
+    assert np.abs(emu - exact).max() / np.abs(exact).max() < 6e-2
+    const = np.full_like(v, 1.75)
+    assert np.abs(O.attention_fp8(q, k, const) - 1.75).max() < 0.05
+
+
 # -------------------------------------------------------------------------------- rounding
 def test_round_bf16_matches_torch():
     rng = np.random.default_rng(51)
