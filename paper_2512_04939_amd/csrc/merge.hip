@@ -17,67 +17,118 @@ __device__ __forceinline__ void acc8(float (&a)[8], const u32x4 w) {
   a[7] += bf16_hi(w.w);
 }
 
-// One wave per merged slot; lane l owns the 16-byte chunks l, l+64, ... of the row.
-// Members are summed in ascending token order (the CSR order), so the result does not
-// depend on scheduling.  Four member rows are in flight per lane.
+#ifndef LV_MERGE_COOP
+#define LV_MERGE_COOP 64
+#endif
+constexpr int kCoopSize = LV_MERGE_COOP;   // groups larger than this are summed by all 4 waves of a workgroup
+
+// acc += rows group_mem[lo..hi) of x, this lane's chunks; 8 member rows in flight per lane.
+template <int CPL>
+__device__ __forceinline__ void sum_rows(const uint16_t *__restrict__ x,
+                                         const int32_t *__restrict__ group_mem, int lo, int hi,
+                                         int C, int nch, int lane, float (&a)[CPL][8]) {
+  int j = lo;
+  for (; j + 8 <= hi; j += 8) {
+    u32x4 w[8][CPL];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int r = group_mem[j + u];
+#pragma unroll
+      for (int c = 0; c < CPL; ++c) {
+        const int ch = lane + 64 * c;
+        w[u][c] = ch < nch ? ((const u32x4 *)(x + (size_t)r * C))[ch] : u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int c = 0; c < CPL; ++c) acc8(a[c], w[u][c]);
+  }
+  for (; j < hi; ++j) {
+    const int r = group_mem[j];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+      const int ch = lane + 64 * c;
+      if (ch < nch) acc8(a[c], ((const u32x4 *)(x + (size_t)r * C))[ch]);
+    }
+  }
+}
+
+template <int CPL>
+__device__ __forceinline__ void store_mean(uint16_t *__restrict__ z, int m, int C, int nch, int lane,
+                                           const float (&a)[CPL][8], float inv) {
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane + 64 * c;
+    if (ch < nch) {
+      u32x4 o;
+      o.x = pack_bf16(a[c][0] * inv, a[c][1] * inv);
+      o.y = pack_bf16(a[c][2] * inv, a[c][3] * inv);
+      o.z = pack_bf16(a[c][4] * inv, a[c][5] * inv);
+      o.w = pack_bf16(a[c][6] * inv, a[c][7] * inv);
+      ((u32x4 *)(z + (size_t)m * C))[ch] = o;
+    }
+  }
+}
+
+// A workgroup (4 waves) owns 4 consecutive merged slots; lane l owns the 16-byte chunks l,
+// l+64, ... of a row.  A slot with at most kCoopSize members is summed by one wave in
+// ascending member order.  Larger groups (a heavy tail: 1 % of the slots hold a third of the
+// tokens) are summed by all 4 waves, each taking a contiguous quarter of the members, and the
+// four partial sums are added in wave order -- the order of additions depends only on the
+// group size, so results are reproducible.
 template <int CPL>
 __global__ __launch_bounds__(256) void k_merge(const uint16_t *__restrict__ x,
                                                const int32_t *__restrict__ group_off,
                                                const int32_t *__restrict__ group_mem, int M,
                                                int C, uint16_t *__restrict__ z) {
+  __shared__ float part[3][CPL * 64 * 8];
   const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nch = C >> 3;
-  const int wpb = blockDim.x >> 6;
-  for (int m = blockIdx.x * wpb + (threadIdx.x >> 6); m < M; m += gridDim.x * wpb) {
-    const int mu = __builtin_amdgcn_readfirstlane(m);
-    const int b = group_off[mu], e = group_off[mu + 1];
+  const int m0 = blockIdx.x * 4;
+  for (int s = 0; s < 4; ++s) {          // cooperative pass over the workgroup's large groups
+    const int m = m0 + s;
+    if (m >= M) break;
+    const int b = group_off[m], e = group_off[m + 1], n = e - b;
+    if (n <= kCoopSize) continue;
+    const int per = (n + 3) >> 2;
+    const int lo = min(b + wave * per, e), hi = min(lo + per, e);
     float a[CPL][8];
 #pragma unroll
     for (int c = 0; c < CPL; ++c)
 #pragma unroll
       for (int i = 0; i < 8; ++i) a[c][i] = 0.f;
-    int j = b;
-    for (; j + 4 <= e; j += 4) {
-      const int r0 = group_mem[j], r1 = group_mem[j + 1], r2 = group_mem[j + 2],
-                r3 = group_mem[j + 3];
-      u32x4 w[4][CPL];
+    sum_rows<CPL>(x, group_mem, lo, hi, C, nch, lane, a);
+    if (wave > 0) {
 #pragma unroll
-      for (int c = 0; c < CPL; ++c) {
-        const int ch = lane + 64 * c;
-        if (ch < nch) {
-          w[0][c] = ((const u32x4 *)(x + (size_t)r0 * C))[ch];
-          w[1][c] = ((const u32x4 *)(x + (size_t)r1 * C))[ch];
-          w[2][c] = ((const u32x4 *)(x + (size_t)r2 * C))[ch];
-          w[3][c] = ((const u32x4 *)(x + (size_t)r3 * C))[ch];
-        } else {
-          w[0][c] = w[1][c] = w[2][c] = w[3][c] = u32x4{0u, 0u, 0u, 0u};
-        }
-      }
+      for (int c = 0; c < CPL; ++c)
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int c = 0; c < CPL; ++c) acc8(a[c], w[u][c]);
+        for (int i = 0; i < 8; ++i) part[wave - 1][(c * 8 + i) * 64 + lane] = a[c][i];
     }
-    for (; j < e; ++j) {
-      const int r0 = group_mem[j];
+    __syncthreads();
+    if (wave == 0) {
 #pragma unroll
-      for (int c = 0; c < CPL; ++c) {
-        const int ch = lane + 64 * c;
-        if (ch < nch) acc8(a[c], ((const u32x4 *)(x + (size_t)r0 * C))[ch]);
-      }
+      for (int w = 0; w < 3; ++w)
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) a[c][i] += part[w][(c * 8 + i) * 64 + lane];
+      store_mean<CPL>(z, m, C, nch, lane, a, 1.0f / (float)n);
     }
-    const float inv = 1.0f / (float)(e - b);
+    __syncthreads();
+  }
+  const int m = m0 + wave;               // own slot, if small
+  if (m < M) {
+    const int b = group_off[m], e = group_off[m + 1];
+    if (e - b <= kCoopSize) {
+      float a[CPL][8];
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-      const int ch = lane + 64 * c;
-      if (ch < nch) {
-        u32x4 o;
-        o.x = pack_bf16(a[c][0] * inv, a[c][1] * inv);
-        o.y = pack_bf16(a[c][2] * inv, a[c][3] * inv);
-        o.z = pack_bf16(a[c][4] * inv, a[c][5] * inv);
-        o.w = pack_bf16(a[c][6] * inv, a[c][7] * inv);
-        ((u32x4 *)(z + (size_t)mu * C))[ch] = o;
-      }
+      for (int c = 0; c < CPL; ++c)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[c][i] = 0.f;
+      sum_rows<CPL>(x, group_mem, b, e, C, nch, lane, a);
+      store_mean<CPL>(z, m, C, nch, lane, a, 1.0f / (float)(e - b));
     }
   }
 }
@@ -101,37 +152,51 @@ int launch_merge(const uint16_t *x, const Dims &d, int64_t M, const litevggt_ind
   return LV_OK;
 }
 
-// out[i] = y[slot_of[i]] (+ residual[i]); one wave per token row, grid-stride over rows.
+#ifndef LV_UNMERGE_ROWS
+#define LV_UNMERGE_ROWS 2
+#endif
+// out[i] = y[slot_of[i]] (+ residual[i]); a wave moves LV_UNMERGE_ROWS token rows per step
+// (all loads of a step are issued before its stores), grid-stride over row groups.
 template <bool RES>
 __global__ __launch_bounds__(256) void k_unmerge(const uint16_t *__restrict__ y,
                                                  const int32_t *__restrict__ slot_of,
                                                  const uint16_t *residual, int64_t N, int C,
                                                  uint16_t *out) {
+  constexpr int R = LV_UNMERGE_ROWS;
   const int lane = threadIdx.x & 63;
   const int nch = C >> 3;
   const int wpb = blockDim.x >> 6;
-  for (int64_t i = (int64_t)blockIdx.x * wpb + (threadIdx.x >> 6); i < N;
-       i += (int64_t)gridDim.x * wpb) {
-    const int s = slot_of[i];
-    const u32x4 *src = (const u32x4 *)(y + (size_t)s * C);
-    u32x4 *dst = (u32x4 *)(out + (size_t)i * C);
+  for (int64_t i0 = ((int64_t)blockIdx.x * wpb + (threadIdx.x >> 6)) * R; i0 < N;
+       i0 += (int64_t)gridDim.x * wpb * R) {
+    int slot[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) slot[r] = slot_of[min(i0 + r, N - 1)];
     for (int ch = lane; ch < nch; ch += 64) {
-      u32x4 w = src[ch];
-      if (RES) {
-        const u32x4 r = ((const u32x4 *)(residual + (size_t)i * C))[ch];
-        w.x = pack_bf16(bf16_lo(w.x) + bf16_lo(r.x), bf16_hi(w.x) + bf16_hi(r.x));
-        w.y = pack_bf16(bf16_lo(w.y) + bf16_lo(r.y), bf16_hi(w.y) + bf16_hi(r.y));
-        w.z = pack_bf16(bf16_lo(w.z) + bf16_lo(r.z), bf16_hi(w.z) + bf16_hi(r.z));
-        w.w = pack_bf16(bf16_lo(w.w) + bf16_lo(r.w), bf16_hi(w.w) + bf16_hi(r.w));
+      u32x4 w[R], res[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        w[r] = ((const u32x4 *)(y + (size_t)slot[r] * C))[ch];
+        if (RES) res[r] = ((const u32x4 *)(residual + (size_t)min(i0 + r, N - 1) * C))[ch];
       }
-      __builtin_nontemporal_store(w, dst + ch);
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        if (i0 + r >= N) break;
+        u32x4 v = w[r];
+        if (RES) {
+          v.x = pack_bf16(bf16_lo(v.x) + bf16_lo(res[r].x), bf16_hi(v.x) + bf16_hi(res[r].x));
+          v.y = pack_bf16(bf16_lo(v.y) + bf16_lo(res[r].y), bf16_hi(v.y) + bf16_hi(res[r].y));
+          v.z = pack_bf16(bf16_lo(v.z) + bf16_lo(res[r].z), bf16_hi(v.z) + bf16_hi(res[r].z));
+          v.w = pack_bf16(bf16_lo(v.w) + bf16_lo(res[r].w), bf16_hi(v.w) + bf16_hi(res[r].w));
+        }
+        __builtin_nontemporal_store(v, (u32x4 *)(out + (size_t)(i0 + r) * C) + ch);
+      }
     }
   }
 }
 
 int launch_unmerge(const uint16_t *y, const Dims &d, const litevggt_index &ix,
                    const uint16_t *residual, uint16_t *out, hipStream_t st) {
-  const int64_t want = (d.N + 3) / 4;
+  const int64_t want = (d.N + 4 * LV_UNMERGE_ROWS - 1) / (4 * LV_UNMERGE_ROWS);
   const unsigned grid = (unsigned)(want < 256 * 64 ? want : 256 * 64);
   if (residual)
     hipLaunchKernelGGL(k_unmerge<true>, dim3(grid), dim3(256), 0, st, y, ix.slot_of, residual, d.N,

@@ -253,6 +253,35 @@ def test_unmerge(case, B):
     assert np.array_equal(dev_bf16_to_f64(res), O.round_bf16(ref))
 
 
+def test_merge_one_giant_group(B):
+    """Every src token merged into the same anchor (a group far larger than what one wave
+    sums alone): exercises the cooperative path; sizes 1, small and giant in one launch."""
+    import torch
+    wl = synth.Workload("g", frames=6, grid_h=12, grid_w=12, dim=192, heads=3, merge_ratio=0.8,
+                        canvas=24, seed=21)
+    bits, xf, im = stored_inputs(wl)
+    po, ph = oracle_params(wl), hip_params(wl)
+    pl = B.litevggt_plan(ph)
+    rng = np.random.default_rng(2)
+    sel = O.select_anchors(rng.random((6, 144)).astype(np.float32), po)
+    anchors = np.full(len(sel["src_idx"]), sel["dst_idx"][3], dtype=np.int32)
+    anchors[::7] = sel["dst_idx"][10]                     # a second, medium-sized group
+    idx = O.build_index(sel["role"], sel["src_idx"], anchors)
+    idx.update(role=sel["role"], dst_idx=sel["dst_idx"], src_idx=sel["src_idx"])
+    assert np.diff(idx["group_off"]).max() > 400
+    ib = _upload_index(B, pl, idx)
+    z = torch.zeros(pl.M, wl.dim, dtype=torch.bfloat16, device="cuda")
+    B.litevggt_merge(ph, to_dev_bf16(bits), ib, z)
+    torch.cuda.synchronize()
+    ref = O.merge(xf, idx["group_off"], idx["group_mem"])
+    got = dev_bf16_to_f64(z)
+    assert np.abs(got - ref).max() <= 2.0 ** -8 * np.abs(ref).max()
+    z2 = torch.zeros_like(z)
+    B.litevggt_merge(ph, to_dev_bf16(bits), ib, z2)
+    torch.cuda.synchronize()
+    assert torch.equal(z, z2)                              # reproducible
+
+
 def test_merge_unmerge_identity_at_ratio_zero(B):
     import torch
     wl = small_workload(frames=2, grid=6, dim=128, heads=2, r=0.0, seed=2)
