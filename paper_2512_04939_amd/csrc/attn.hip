@@ -439,10 +439,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   f32x16 sacc[2];      // [query block]: scores of its current 32-key tile
   u32x4 pb[2][2];      // [query block][u]: bf16 weights of its current 32-key tile
-  // Fragments held in registers: fv = V fragments of tile t, fk = K fragments of tile t+1.
-  // They are read from LDS once, during phase A(t) -- each right after the MFMAs that used
-  // the previous contents have been issued -- and feed both query blocks: phases B(t), A(t+1).
-  u32x4 fv[4], fk[4];
+  // Fragments held in registers feed both query blocks.  fv[t & 1] = V fragments of tile t,
+  // read from LDS at the start of phase A(t) (double-buffered, so the read is a whole phase
+  // ahead of its first use in B(t)) and used in B(t) and A(t+1).  fk = K fragments of tile
+  // t+1, re-read at the end of A(t) after the MFMAs that used the previous contents.
+  u32x4 fv[2][4], fk[4];
 
   auto load_v = [&](int t, u32x4(&dst)[4]) {
     const u32x4 *vt = &vs[(t >> 1) & (kBStages - 1)][(t & 1) * 4 * kFragU4 + lane];
@@ -501,31 +502,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // exp2/exp2/MFMA/pack/dot2 order with opaque pins was measured slower than this.)
   auto recipe = [&](bool with_loads) {
 #if LV_ATTN_RECIPE
+    if (with_loads) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);     // V reads first
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // 2 exp2
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // pack + dot2
-      }
-      if (with_loads) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);   // 4 LDS reads
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // 2 exp2
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // pack + dot2
     }
+    if (with_loads) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);     // K reads last
 #endif
   };
   // A(t), t >= 1: weights of block 0 || PV(t-1) and scores(t) of block 1
-  auto phase_a = [&](int t) {
+  auto phase_a = [&](int t, const u32x4(&v_prev)[4], u32x4(&v_cur)[4]) {
+    load_v(t, v_cur);
     weights(0);
-    mma_pv(1, fv);
-    load_v(t, fv);
+    mma_pv(1, v_prev);
     mma_s(1, fk);
     if (t + 1 < nkt) load_k(t + 1, fk);
     recipe(true);
   };
   // B(t), t <= nkt-2: weights of block 1 || PV(t) and scores(t+1) of block 0
-  auto phase_b = [&]() {
+  auto phase_b = [&](const u32x4(&v_cur)[4]) {
     weights(1);
-    mma_pv(0, fv);
+    mma_pv(0, v_cur);
     mma_s(0, fk);
     recipe(false);
   };
@@ -537,38 +536,38 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     r2s(1);
   }
   __syncthreads();
-  // prologue: scores of tile 0 for both blocks, weights of block 0, then fv = V(0), fk = K(1)
+  // prologue: scores of tile 0 for both blocks, weights of block 0, then fv[0] = V(0), fk = K(1)
   load_k(0, fk);
   mma_s(0, fk);
   mask_tail(0, 0);
   weights(0);
   mma_s(1, fk);
-  load_v(0, fv);
+  load_v(0, fv[0]);
   load_k(1, fk);
   if (nkv == 1) mask_tail(0, 1);
   // steady state: stage i holds tiles 2i, 2i+1; stage i+2 is fetched meanwhile
   for (int i = 0; i < nkv - 1; ++i) {
     if (i + 2 < nkv) g2r(i + 2);
-    phase_b();                             // B(2i)
-    phase_a(2 * i + 1);                    // A(2i+1)
-    phase_b();                             // B(2i+1)
+    phase_b(fv[0]);                        // B(2i)
+    phase_a(2 * i + 1, fv[0], fv[1]);      // A(2i+1)
+    phase_b(fv[1]);                        // B(2i+1)
     if (i == nkv - 2) {                    // entering the last stage: its tiles may be ragged
       mask_tail(2 * i + 1, 1);             // (no-op unless n is tiny)
       mask_tail(2 * i + 2, 0);
     }
-    phase_a(2 * i + 2);                    // A(2i+2)
+    phase_a(2 * i + 2, fv[1], fv[0]);      // A(2i+2)
     if (i == nkv - 2) mask_tail(2 * i + 2, 1);
     if (i + 2 < nkv) r2s(i + 2);
     __syncthreads();
   }
   // last stage: tiles nkt-2, nkt-1
-  phase_b();                               // B(nkt-2)
+  phase_b(fv[0]);                          // B(nkt-2)
   mask_tail(nkt - 1, 0);
-  phase_a(nkt - 1);                        // A(nkt-1): loads V(nkt-1) only
+  phase_a(nkt - 1, fv[0], fv[1]);          // A(nkt-1): loads V(nkt-1) only
   mask_tail(nkt - 1, 1);
   weights(1);
-  mma_pv(0, fv);
-  mma_pv(1, fv);
+  mma_pv(0, fv[1]);
+  mma_pv(1, fv[1]);
 
 #pragma unroll
   for (int sub = 0; sub < 2; ++sub) {

@@ -18,15 +18,15 @@ namespace lv {
 
 constexpr int kSrcTile = 64;         // src rows resident per workgroup
 #ifndef LV_MATCH_WAVES
-#define LV_MATCH_WAVES 8
+#define LV_MATCH_WAVES 12
 #endif
 #ifndef LV_MATCH_DEPTH
-#define LV_MATCH_DEPTH 3
+#define LV_MATCH_DEPTH 2
 #endif
 #ifndef LV_MATCH_PANEL_GROUPS
-#define LV_MATCH_PANEL_GROUPS 16   /* 16 groups x 512 rows x 2 KB = 16 MB of dst per launch */
+#define LV_MATCH_PANEL_GROUPS 11   /* 11 groups x 768 rows x 2 KB = 16.5 MB of dst per launch */
 #endif
-constexpr int kMatchWaves = LV_MATCH_WAVES;   // 8 = 2 waves per SIMD
+constexpr int kMatchWaves = LV_MATCH_WAVES;   // 12 = 3 waves per SIMD (measured best)
 constexpr int kDepth = LV_MATCH_DEPTH;        // register ring: chunks of dst fragments in flight per wave
 constexpr float kRescoreGap = 2e-4f; // similarity gap below which float64 decides
 
@@ -182,10 +182,15 @@ __global__ __launch_bounds__(kMatchWaves * 64) void k_match(
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
           const int s = sb * 4 + ks;
-          const bf16x8 b0 = __builtin_bit_cast(bf16x8, frag[(size_t)s * 64 + lane]);
-          const bf16x8 b1 = __builtin_bit_cast(bf16x8, frag[(size_t)(KS + s) * 64 + lane]);
           const bf16x8 a0 = __builtin_bit_cast(bf16x8, ring[j][ks]);
           const bf16x8 a1 = __builtin_bit_cast(bf16x8, ring[j][4 + ks]);
+#ifdef LV_MATCH_NOLDS   /* timing experiment only: wrong results */
+          const bf16x8 b0 = a1, b1 = a0;
+          (void)s;
+#else
+          const bf16x8 b0 = __builtin_bit_cast(bf16x8, frag[(size_t)s * 64 + lane]);
+          const bf16x8 b1 = __builtin_bit_cast(bf16x8, frag[(size_t)(KS + s) * 64 + lane]);
+#endif
           acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
           acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
           acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
