@@ -72,6 +72,22 @@ class HipEvents:
             self.lib.hipEventDestroy(ev)
 
 
+CALIBRATION_COPY_BYTES = 256 << 20     # read once and written once by one elementwise kernel
+
+
+def measured_traffic(workload, dtype):
+    """HBM bytes per attention launch from the committed counter summary of this workload
+    (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the calibration copy), or None."""
+    path = os.path.join(ROOT, "profiles", f"attn_{dtype}_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(wl, pl_full, n_frames):
     """Time the oracle on the first n_frames of the workload, one layer with a refresh, and
     scale each step to the full sequence by its operation count."""
@@ -134,7 +150,6 @@ def main():
 
     import numpy as np
     import torch
-    from helpers import hip_params
     from paper_2512_04939_amd import binding as B
     from paper_2512_04939_amd import synth
 
@@ -145,7 +160,9 @@ def main():
     over = {} if args.merge_ratio is None else dict(merge_ratio=args.merge_ratio)
     wl = synth.workload(args.workload, **over)
     attn_dtype = B.ATTN_BF16 if args.attn_dtype == "bf16" else B.ATTN_FP8_E4M3
-    ph = hip_params(wl, attn_dtype=attn_dtype)
+    ph = B.make_params(wl.frames, wl.grid_h, wl.grid_w, wl.dim, wl.heads, n_special=wl.n_special,
+                       patch=wl.patch, merge_ratio=wl.merge_ratio,
+                       refresh_interval=wl.refresh_interval, qk_norm=1, attn_dtype=attn_dtype)
     wl_qk_norm = bool(ph.qk_norm)
     pl = B.litevggt_plan(ph)
     L, C_ = wl.layers, wl.dim
@@ -155,13 +172,30 @@ def main():
     bits = gen.tokens(threads=min(16, os.cpu_count() or 1))
     if bits.dtype != np.uint16:
         bits = synth.f32_to_bf16_bits(bits)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
     x0 = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    torch.cuda.synchronize()
+    h2d_s = time.perf_counter() - t1       # pageable host memory -> HBM, not part of `value`
+    h2d_bytes = bits.nbytes
     del bits
     im = torch.empty(wl.frames, 3, wl.img_h, wl.img_w, dtype=torch.float32, device="cuda")
     for f0 in range(0, wl.frames, 50):
         fr = range(f0, min(wl.frames, f0 + 50))
-        im[f0:f0 + len(fr)].copy_(torch.from_numpy(gen.images(fr)))
+        host = torch.from_numpy(gen.images(fr))
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        im[f0:f0 + len(fr)].copy_(host)
+        torch.cuda.synchronize()
+        h2d_s += time.perf_counter() - t1
+        h2d_bytes += host.numel() * 4
     gen_s = time.perf_counter() - t0
+
+    # a plain copy of known size: the kernel the HBM counters of a profiler run are scaled by
+    cal = torch.ones(CALIBRATION_COPY_BYTES // 4, dtype=torch.float32, device="cuda")
+    cal_out = torch.mul(cal, 1.0)
+    torch.cuda.synchronize()
+    del cal, cal_out
 
     x = torch.empty_like(x0)
     ib = B.alloc_index(pl)
@@ -257,9 +291,13 @@ def main():
                    "token_layers_per_s": L * N / (ms_step * 1e-3),
                    "refresh_log": log, "output_finite": finite,
                    "peak_hbm_alloc_gib": torch.cuda.max_memory_allocated() / 2 ** 30,
-                   "input_generation_s": gen_s},
+                   "input_generation_s": gen_s,
+                   "h2d_upload_s": h2d_s, "h2d_upload_gbs": h2d_bytes / h2d_s / 1e9,
+                   "tokens_per_s_with_upload": N / (ms_step * 1e-3 + h2d_s),
+                   "calibration_copy_bytes": CALIBRATION_COPY_BYTES},
         "roofline": {"kernel": ("k_attn_fp8" if args.attn_dtype == "fp8" else "k_attn_bf16_bounded" if wl_qk_norm else "k_attn_bf16"), "bound": "mfma", "achieved": attn_tf, "peak": peak_tf,
-                     "unit": "TFLOP/s", "frac": attn_tf / peak_tf, "traffic": None,
+                     "unit": "TFLOP/s", "frac": attn_tf / peak_tf,
+                     "traffic": measured_traffic(wl.name, args.attn_dtype),
                      "flop_per_launch": attn_flop, "avg_launch_ms": avg["attn"],
                      "launches_timed": len(dur["attn"])},
         "ops": ops,
