@@ -365,11 +365,37 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
 //   B(t): weights of block 1, tile t   ||  PV of block 0, tile t;    scores of block 0, tile t+1
 // The MFMAs are interleaved with the VALU work by an explicit scheduling recipe.
 // ---------------------------------------------------------------------------------------
+// LDS address (byte offset in the workgroup's LDS) of a __shared__ object
+__device__ __forceinline__ uint32_t lds_addr(const void *p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+// Four 16-byte LDS reads at addr + 0, 1, 2, 3 KB, issued here and NOT waited for: the compiler
+// does not know that dst is still in flight, so every use of dst must come after an lds_wait
+// on the same registers.
+__device__ __forceinline__ void lds_read4_async(u32x4 (&dst)[4], uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:1024\n\t"
+               "ds_read_b128 %2, %4 offset:2048\n\tds_read_b128 %3, %4 offset:3072"
+               : "=&v"(dst[0]), "=&v"(dst[1]), "=&v"(dst[2]), "=&v"(dst[3])
+               : "v"(addr)
+               : "memory");
+}
+// waits until every LDS operation issued so far has completed
+__device__ __forceinline__ void lds_wait(u32x4 (&a)[4], u32x4 (&b)[4]) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]),
+                 "+v"(b[3])
+               :
+               : "memory");
+}
+
 constexpr int kBQB = 256;            // queries per workgroup (4 waves)
 constexpr int kBStages = 4;          // LDS ring of 64-key K/V stages
 
 #ifndef LV_ATTN_RECIPE
 #define LV_ATTN_RECIPE 1
+#endif
+#ifndef LV_ATTN_MIX
+#define LV_ATTN_MIX 0
 #endif
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_bf16_bounded(
@@ -414,8 +440,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[sub][dt][r] = 0.f;
-  float lrow[2] = {0.f, 0.f};
-  const bf16x2 kOnes = {(__bf16)1.0f, (__bf16)1.0f};
+  float lrow[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
   const f32x16 kZero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   const int nkv = n_kt >> 1, nkt = n_kt;
@@ -439,11 +464,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   f32x16 sacc[2];      // [query block]: scores of its current 32-key tile
   u32x4 pb[2][2];      // [query block][u]: bf16 weights of its current 32-key tile
-  // Fragments held in registers feed both query blocks.  fv[t & 1] = V fragments of tile t,
-  // read from LDS at the start of phase A(t) (double-buffered, so the read is a whole phase
-  // ahead of its first use in B(t)) and used in B(t) and A(t+1).  fk = K fragments of tile
-  // t+1, re-read at the end of A(t) after the MFMAs that used the previous contents.
-  u32x4 fv[2][4], fk[4];
+  // Fragments held in registers feed both query blocks: fv[t & 1] = V fragments of tile t
+  // (used in B(t), A(t+1)), fk[t & 1] = K fragments of tile t (used in B(t-1), A(t)).
+  u32x4 fv[2][4], fk[2][4];
 
   auto load_v = [&](int t, u32x4(&dst)[4]) {
     const u32x4 *vt = &vs[(t >> 1) & (kBStages - 1)][(t & 1) * 4 * kFragU4 + lane];
@@ -472,6 +495,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             __builtin_bit_cast(bf16x8, vf[u * 2 + dt]), __builtin_bit_cast(bf16x8, pb[sub][u]),
             oacc[sub][dt], 0, 0, 0);
   };
+  // PV of block sub_pv and scores of block sub_s, alternating, so that no MFMA needs the
+  // result of the one issued just before it (the score chain is spaced by two, the two output
+  // accumulators by four)
+  auto mma_mix = [&](int sub_pv, const u32x4(&vf)[4], int sub_s, const u32x4(&kf)[4]) {
+    f32x16 acc = kZero;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[s]), qf[sub_s][s],
+                                                    acc, 0, 0, 0);
+      oacc[sub_pv][s & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+          __builtin_bit_cast(bf16x8, vf[s]), __builtin_bit_cast(bf16x8, pb[sub_pv][s >> 1]),
+          oacc[sub_pv][s & 1], 0, 0, 0);
+    }
+    sacc[sub_s] = acc;
+  };
   auto mask_tail = [&](int t, int sub) {   // keys beyond the sequence end
     if ((int64_t)(t + 1) * kKT > n) {
 #pragma unroll
@@ -481,25 +519,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       }
     }
   };
-  auto weights = [&](int sub) {            // exp2 of the scaled scores, bf16 pack, row sums
-    float ls = lrow[sub];
+  // exp2 of the scaled scores, bf16 pack, row sums.  The sums are plain fp32 adds of the
+  // unrounded weights in two chains: v_dot2c_f32_bf16 on the packed pairs would halve the
+  // instruction count, but it does not overlap with MFMAs (measured: a phase with dot2 row sums
+  // takes as long as its MFMA and VALU parts one after the other, with adds it takes 1.1x its
+  // MFMA part).
+  auto weights = [&](int sub) {
+    float l0 = lrow[sub][0], l1 = lrow[sub][1];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       uint32_t w[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        w[e] = pack_bf16(__builtin_amdgcn_exp2f(sacc[sub][8 * u + 2 * e]),
-                         __builtin_amdgcn_exp2f(sacc[sub][8 * u + 2 * e + 1]));
-        ls = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e]), kOnes, ls, false);
+        const float p0 = __builtin_amdgcn_exp2f(sacc[sub][8 * u + 2 * e]);
+        const float p1 = __builtin_amdgcn_exp2f(sacc[sub][8 * u + 2 * e + 1]);
+        w[e] = pack_bf16(p0, p1);
+        l0 += p0;
+        l1 += p1;
       }
       pb[sub][u] = u32x4{w[0], w[1], w[2], w[3]};
     }
-    lrow[sub] = ls;
+    lrow[sub][0] = l0;
+    lrow[sub][1] = l1;
   };
-  // One phase = 8 MFMAs + the weights of 16 scores per lane (16 exp2, 8 pack, 8 dot2).  The
+  // One phase = 8 MFMAs + the weights of 16 scores per lane (16 exp2, 8 pack, 16 add).  The
   // recipe asks the scheduler to spread the MFMAs over the VALU work; A phases re-fill fv
   // after their 4 PV MFMAs and fk after their 4 score MFMAs.  (Forcing a strict
-  // exp2/exp2/MFMA/pack/dot2 order with opaque pins was measured slower than this.)
+  // exp2/exp2/MFMA/pack/sum order with opaque pins was measured slower than this.)
   auto recipe = [&](bool with_loads) {
 #if LV_ATTN_RECIPE
     if (with_loads) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);     // V reads first
@@ -507,25 +553,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // 2 exp2
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // pack + dot2
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // pack + 2 adds
     }
     if (with_loads) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);     // K reads last
 #endif
   };
-  // A(t), t >= 1: weights of block 0 || PV(t-1) and scores(t) of block 1
-  auto phase_a = [&](int t, const u32x4(&v_prev)[4], u32x4(&v_cur)[4]) {
-    load_v(t, v_cur);
-    weights(0);
-    mma_pv(1, v_prev);
-    mma_s(1, fk);
-    if (t + 1 < nkt) load_k(t + 1, fk);
-    recipe(true);
+  // In the steady state the fragment reads are issued by hand (lds_read4_async): V(t) and
+  // K(t+1) at the start of A(t); B(t) is their first user and waits for them a whole phase
+  // later.  Both are double-buffered, so the registers a read overwrites were last used by
+  // MFMAs a whole phase before it is issued.
+  const uint32_t ks_lane = lds_addr(&ks[0][lane]), vs_lane = lds_addr(&vs[0][lane]);
+  auto frag_off = [&](int t) {   // byte offset of tile t's four fragments in a ring array
+    return (uint32_t)((((t >> 1) & (kBStages - 1)) * 8 + (t & 1) * 4) * kFragU4 * 16);
   };
-  // B(t), t <= nkt-2: weights of block 1 || PV(t) and scores(t+1) of block 0
-  auto phase_b = [&](const u32x4(&v_cur)[4]) {
+  // A(t), t >= 1: weights of block 0 || PV(t-1) and scores(t) of block 1
+  auto phase_a = [&](int t, const u32x4(&v_prev)[4], u32x4(&v_cur)[4], const u32x4(&k_cur)[4],
+                     u32x4(&k_next)[4]) {
+    lds_read4_async(v_cur, vs_lane + frag_off(t));
+    lds_read4_async(k_next, ks_lane + frag_off(t + 1));   // past the last tile: a stale slot, never used
+    __builtin_amdgcn_sched_barrier(0);
+    weights(0);
+#if LV_ATTN_MIX
+    mma_mix(1, v_prev, 1, k_cur);
+#else
+    mma_pv(1, v_prev);
+    mma_s(1, k_cur);
+#endif
+    recipe(false);
+  };
+  // B(t), t <= nkt-2: weights of block 1 || PV(t) and scores(t+1) of block 0.  With store it
+  // also moves the staged global loads into the LDS ring: right after the wait no read is in
+  // flight, so the barrier that follows the phase waits for nothing else.
+  auto phase_b = [&](u32x4(&v_cur)[4], u32x4(&k_next)[4], bool store = false, int store_stage = 0) {
+    lds_wait(v_cur, k_next);
+    if (store) r2s(store_stage);
     weights(1);
+#if LV_ATTN_MIX
+    mma_mix(0, v_cur, 0, k_next);
+#else
     mma_pv(0, v_cur);
-    mma_s(0, fk);
+    mma_s(0, k_next);
+#endif
     recipe(false);
   };
 
@@ -536,42 +604,48 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     r2s(1);
   }
   __syncthreads();
-  // prologue: scores of tile 0 for both blocks, weights of block 0, then fv[0] = V(0), fk = K(1)
-  load_k(0, fk);
-  mma_s(0, fk);
+  // prologue: scores of tile 0 for both blocks, weights of block 0, then V(0) and K(1)
+  load_k(0, fk[0]);
+  mma_s(0, fk[0]);
   mask_tail(0, 0);
   weights(0);
-  mma_s(1, fk);
+  mma_s(1, fk[0]);
   load_v(0, fv[0]);
-  load_k(1, fk);
+  load_k(1, fk[1]);
   if (nkv == 1) mask_tail(0, 1);
-  // steady state: stage i holds tiles 2i, 2i+1; stage i+2 is fetched meanwhile
-  for (int i = 0; i < nkv - 1; ++i) {
-    if (i + 2 < nkv) g2r(i + 2);
-    phase_b(fv[0]);                        // B(2i)
-    phase_a(2 * i + 1, fv[0], fv[1]);      // A(2i+1)
-    phase_b(fv[1]);                        // B(2i+1)
-    if (i == nkv - 2) {                    // entering the last stage: its tiles may be ragged
-      mask_tail(2 * i + 1, 1);             // (no-op unless n is tiny)
-      mask_tail(2 * i + 2, 0);
-    }
-    phase_a(2 * i + 2, fv[1], fv[0]);      // A(2i+2)
-    if (i == nkv - 2) mask_tail(2 * i + 2, 1);
-    if (i + 2 < nkv) r2s(i + 2);
-    __syncthreads();
+  // steady state: stage i holds tiles 2i, 2i+1; stage i+2 is fetched meanwhile.  The loop
+  // body has no branches.
+  for (int i = 0; i < nkv - 2; ++i) {
+    g2r(i + 2);
+    phase_b(fv[0], fk[1]);                              // B(2i)
+    phase_a(2 * i + 1, fv[0], fv[1], fk[1], fk[0]);     // A(2i+1)
+    phase_b(fv[1], fk[0], true, i + 2);                 // B(2i+1); slot (i+2)&3 was last read two iterations ago
+    __syncthreads();                                    // stage i+2 is first read in A(2i+3)
+    phase_a(2 * i + 2, fv[1], fv[0], fk[0], fk[1]);     // A(2i+2)
+  }
+  if (nkv >= 2) {                          // stage nkv-2; it enters the last stage, whose tiles may be ragged
+    const int i = nkv - 2;
+    phase_b(fv[0], fk[1]);
+    phase_a(2 * i + 1, fv[0], fv[1], fk[1], fk[0]);
+    phase_b(fv[1], fk[0]);
+    mask_tail(2 * i + 2, 0);
+    phase_a(2 * i + 2, fv[1], fv[0], fk[0], fk[1]);
+    mask_tail(2 * i + 2, 1);
   }
   // last stage: tiles nkt-2, nkt-1
-  phase_b(fv[0]);                          // B(nkt-2)
+  phase_b(fv[0], fk[1]);                   // B(nkt-2)
   mask_tail(nkt - 1, 0);
-  phase_a(nkt - 1, fv[0], fv[1]);          // A(nkt-1): loads V(nkt-1) only
+  phase_a(nkt - 1, fv[0], fv[1], fk[1], fk[0]);   // A(nkt-1)
   mask_tail(nkt - 1, 1);
+  lds_wait(fv[1], fk[0]);
   weights(1);
   mma_pv(0, fv[1]);
   mma_pv(1, fv[1]);
 
 #pragma unroll
   for (int sub = 0; sub < 2; ++sub) {
-    const float l = lrow[sub] + __shfl_xor(lrow[sub], 32, 64);
+    const float lsum = lrow[sub][0] + lrow[sub][1];
+    const float l = lsum + __shfl_xor(lsum, 32, 64);
     const float inv = 1.0f / l;
     const int64_t row = q0 + sub * 32 + ql;
     if (row < n) {
