@@ -394,6 +394,14 @@ constexpr int kBStages = 4;          // LDS ring of 64-key K/V stages
 #ifndef LV_ATTN_RECIPE
 #define LV_ATTN_RECIPE 1
 #endif
+// timing experiments only (results are wrong when set): skip the global->LDS staging (bit 0)
+// and the barrier (bit 1) of the steady state / skip the fragment reads
+#ifndef LV_ATTN_TIMING_NOSTAGE
+#define LV_ATTN_TIMING_NOSTAGE 0
+#endif
+#ifndef LV_ATTN_TIMING_NOLDS
+#define LV_ATTN_TIMING_NOLDS 0
+#endif
 #ifndef LV_ATTN_MIX
 #define LV_ATTN_MIX 0
 #endif
@@ -446,20 +454,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int nkv = n_kt >> 1, nkt = n_kt;
   const u32x4 *kh = kp + (size_t)head * n_kt * 4 * kFragU4;
   const u32x4 *vh = vp + (size_t)head * n_kt * 4 * kFragU4;
-  u32x4 rk[2], rv[2];
-  auto g2r = [&](int stage) {
-    const size_t off = (size_t)stage * 8 * kFragU4;
-    rk[0] = kh[off + tid];
-    rk[1] = kh[off + 256 + tid];
-    rv[0] = vh[off + tid];
-    rv[1] = vh[off + 256 + tid];
-  };
-  auto r2s = [&](int stage) {
+  // Stage `stage` of this head's packed K and V (64 keys, 8 KB each) goes from global memory
+  // straight into its ring slot, 1 KB per wave and instruction (global_load_lds_dwordx4: lane l
+  // of a wave lands at the wave's LDS base + 16 l).  No registers are staged, so a stage can be
+  // fetched three iterations before its first use.  Completion is per wave (vmcnt) and is
+  // published to the workgroup by the barrier of the steady-state loop.
+  auto fetch = [&](int stage) {
     const int slot = stage & (kBStages - 1);
-    ks[slot][tid] = rk[0];
-    ks[slot][256 + tid] = rk[1];
-    vs[slot][tid] = rv[0];
-    vs[slot][256 + tid] = rv[1];
+    const size_t off = (size_t)stage * 8 * kFragU4 + tid;
+    __builtin_amdgcn_global_load_lds(kh + off, &ks[slot][wave * 64], 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(kh + off + 256, &ks[slot][256 + wave * 64], 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(vh + off, &vs[slot][wave * 64], 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(vh + off + 256, &vs[slot][256 + wave * 64], 16, 0, 0);
   };
 
   f32x16 sacc[2];      // [query block]: scores of its current 32-key tile
@@ -569,27 +575,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // A(t), t >= 1: weights of block 0 || PV(t-1) and scores(t) of block 1
   auto phase_a = [&](int t, const u32x4(&v_prev)[4], u32x4(&v_cur)[4], const u32x4(&k_cur)[4],
                      u32x4(&k_next)[4]) {
+#if LV_ATTN_TIMING_NOLDS
+    asm volatile("" : "+v"(v_cur[0]), "+v"(v_cur[1]), "+v"(v_cur[2]), "+v"(v_cur[3]), "+v"(k_next[0]),
+                 "+v"(k_next[1]), "+v"(k_next[2]), "+v"(k_next[3]));
+#else
     lds_read4_async(v_cur, vs_lane + frag_off(t));
     lds_read4_async(k_next, ks_lane + frag_off(t + 1));   // past the last tile: a stale slot, never used
+#endif
     __builtin_amdgcn_sched_barrier(0);
     weights(0);
-#if LV_ATTN_MIX
+#if LV_ATTN_MIX == 1
     mma_mix(1, v_prev, 1, k_cur);
+#elif LV_ATTN_MIX == 2
+    mma_s(1, k_cur);
+    mma_pv(1, v_prev);
 #else
     mma_pv(1, v_prev);
     mma_s(1, k_cur);
 #endif
     recipe(false);
   };
-  // B(t), t <= nkt-2: weights of block 1 || PV(t) and scores(t+1) of block 0.  With store it
-  // also moves the staged global loads into the LDS ring: right after the wait no read is in
-  // flight, so the barrier that follows the phase waits for nothing else.
-  auto phase_b = [&](u32x4(&v_cur)[4], u32x4(&k_next)[4], bool store = false, int store_stage = 0) {
+  // B(t), t <= nkt-2: weights of block 1 || PV(t) and scores(t+1) of block 0
+  auto phase_b = [&](u32x4(&v_cur)[4], u32x4(&k_next)[4]) {
+    __builtin_amdgcn_sched_barrier(0);     // the work of A(t) stays ahead of the wait
     lds_wait(v_cur, k_next);
-    if (store) r2s(store_stage);
     weights(1);
-#if LV_ATTN_MIX
+#if LV_ATTN_MIX == 1
     mma_mix(0, v_cur, 0, k_next);
+#elif LV_ATTN_MIX == 2
+    mma_s(0, k_next);
+    mma_pv(0, v_cur);
 #else
     mma_pv(0, v_cur);
     mma_s(0, k_next);
@@ -597,13 +612,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     recipe(false);
   };
 
-  g2r(0);
-  r2s(0);
-  if (nkv > 1) {
-    g2r(1);
-    r2s(1);
-  }
+  fetch(0);
+  fetch(min(1, nkv - 1));
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  fetch(min(2, nkv - 1));                  // in flight during the prologue and the first iteration
   // prologue: scores of tile 0 for both blocks, weights of block 0, then V(0) and K(1)
   load_k(0, fk[0]);
   mma_s(0, fk[0]);
@@ -613,16 +626,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   load_v(0, fv[0]);
   load_k(1, fk[1]);
   if (nkv == 1) mask_tail(0, 1);
-  // steady state: stage i holds tiles 2i, 2i+1; stage i+2 is fetched meanwhile.  The loop
-  // body has no branches.
+  // steady state: stage i holds tiles 2i, 2i+1; iteration i reads stages i and i+1, stage i+2
+  // is in flight since the previous iteration and stage i+3 is fetched now, into the slot of
+  // stage i-1, which every wave finished reading before the previous barrier.  (Past the end
+  // the last stage is fetched again into a slot nobody reads: the loop body has no branches.)
   for (int i = 0; i < nkv - 2; ++i) {
-    g2r(i + 2);
+#if !(LV_ATTN_TIMING_NOSTAGE & 1)
+    {
+      const int slot = (i + 3) & (kBStages - 1);
+      const size_t off = (size_t)min(i + 3, nkv - 1) * 8 * kFragU4 + tid;
+      __builtin_amdgcn_global_load_lds(kh + off, &ks[slot][wave * 64], 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(kh + off + 256, &ks[slot][256 + wave * 64], 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(vh + off, &vs[slot][wave * 64], 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(vh + off + 256, &vs[slot][256 + wave * 64], 16, 0, 0);
+    }
+#endif
     phase_b(fv[0], fk[1]);                              // B(2i)
     phase_a(2 * i + 1, fv[0], fv[1], fk[1], fk[0]);     // A(2i+1)
-    phase_b(fv[1], fk[0], true, i + 2);                 // B(2i+1); slot (i+2)&3 was last read two iterations ago
-    __syncthreads();                                    // stage i+2 is first read in A(2i+3)
+    phase_b(fv[1], fk[0]);                              // B(2i+1)
+#if !(LV_ATTN_TIMING_NOSTAGE & 2)
+    // this wave's part of stage i+2 has landed (the four newest loads, stage i+3, may still be
+    // in flight); after the barrier all of stage i+2 is readable: first read in A(2i+3)
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#endif
     phase_a(2 * i + 2, fv[1], fv[0], fk[0], fk[1]);     // A(2i+2)
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing may land after the workgroup ends
   if (nkv >= 2) {                          // stage nkv-2; it enters the last stage, whose tiles may be ragged
     const int i = nkv - 2;
     phase_b(fv[0], fk[1]);
