@@ -573,8 +573,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     return (uint32_t)((((t >> 1) & (kBStages - 1)) * 8 + (t & 1) * 4) * kFragU4 * 16);
   };
   // A(t), t >= 1: weights of block 0 || PV(t-1) and scores(t) of block 1
+  int fslot = 0;       // ring slot and source offset of the stage being fetched
+  size_t foff = 0;
+  auto fetch1 = [&](int q) {   // one of the four fetch instructions of a stage
+    const u32x4 *src = (q < 2 ? kh : vh) + foff + (q & 1) * 256;
+    u32x4 *dst = (q < 2 ? &ks[fslot][0] : &vs[fslot][0]) + (q & 1) * 256 + wave * 64;
+    __builtin_amdgcn_global_load_lds(src, dst, 16, 0, 0);
+  };
   auto phase_a = [&](int t, const u32x4(&v_prev)[4], u32x4(&v_cur)[4], const u32x4(&k_cur)[4],
-                     u32x4(&k_next)[4]) {
+                     u32x4(&k_next)[4], int fq = -1) {
 #if LV_ATTN_TIMING_NOLDS
     asm volatile("" : "+v"(v_cur[0]), "+v"(v_cur[1]), "+v"(v_cur[2]), "+v"(v_cur[3]), "+v"(k_next[0]),
                  "+v"(k_next[1]), "+v"(k_next[2]), "+v"(k_next[3]));
@@ -582,6 +589,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     lds_read4_async(v_cur, vs_lane + frag_off(t));
     lds_read4_async(k_next, ks_lane + frag_off(t + 1));   // past the last tile: a stale slot, never used
 #endif
+    if (fq >= 0) fetch1(fq);
     __builtin_amdgcn_sched_barrier(0);
     weights(0);
 #if LV_ATTN_MIX == 1
@@ -596,9 +604,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     recipe(false);
   };
   // B(t), t <= nkt-2: weights of block 1 || PV(t) and scores(t+1) of block 0
-  auto phase_b = [&](u32x4(&v_cur)[4], u32x4(&k_next)[4]) {
+  auto phase_b = [&](u32x4(&v_cur)[4], u32x4(&k_next)[4], int fq = -1) {
     __builtin_amdgcn_sched_barrier(0);     // the work of A(t) stays ahead of the wait
     lds_wait(v_cur, k_next);
+    if (fq >= 0) {
+      fetch1(fq);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     weights(1);
 #if LV_ATTN_MIX == 1
     mma_mix(0, v_cur, 0, k_next);
@@ -631,28 +643,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // stage i-1, which every wave finished reading before the previous barrier.  (Past the end
   // the last stage is fetched again into a slot nobody reads: the loop body has no branches.)
   for (int i = 0; i < nkv - 2; ++i) {
-#if !(LV_ATTN_TIMING_NOSTAGE & 1)
-    {
-      const int slot = (i + 3) & (kBStages - 1);
-      const size_t off = (size_t)min(i + 3, nkv - 1) * 8 * kFragU4 + tid;
-      __builtin_amdgcn_global_load_lds(kh + off, &ks[slot][wave * 64], 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(kh + off + 256, &ks[slot][256 + wave * 64], 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(vh + off, &vs[slot][wave * 64], 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(vh + off + 256, &vs[slot][256 + wave * 64], 16, 0, 0);
-    }
-#endif
-    phase_b(fv[0], fk[1]);                              // B(2i)
-    phase_a(2 * i + 1, fv[0], fv[1], fk[1], fk[0]);     // A(2i+1)
-    phase_b(fv[1], fk[0]);                              // B(2i+1)
-#if !(LV_ATTN_TIMING_NOSTAGE & 2)
-    // this wave's part of stage i+2 has landed (the four newest loads, stage i+3, may still be
-    // in flight); after the barrier all of stage i+2 is readable: first read in A(2i+3)
+    // one fetch instruction at the head of each phase
+    fslot = (i + 3) & (kBStages - 1);
+    foff = (size_t)min(i + 3, nkv - 1) * 8 * kFragU4 + tid;
+    phase_b(fv[0], fk[1], 0);                           // B(2i)
+    phase_a(2 * i + 1, fv[0], fv[1], fk[1], fk[0], 1);  // A(2i+1)
+    phase_b(fv[1], fk[0], 2);                           // B(2i+1)
+    // this wave's part of stage i+2 has landed (the three newest loads, of stage i+3, may still
+    // be in flight); after the barrier all of stage i+2 is readable: first read in A(2i+3)
     __builtin_amdgcn_sched_barrier(0);
-    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-#endif
-    phase_a(2 * i + 2, fv[1], fv[0], fk[0], fk[1]);     // A(2i+2)
+    phase_a(2 * i + 2, fv[1], fv[0], fk[0], fk[1], 3);  // A(2i+2)
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing may land after the workgroup ends
   if (nkv >= 2) {                          // stage nkv-2; it enters the last stage, whose tiles may be ragged
