@@ -365,20 +365,6 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
 //   B(t): weights of block 1, tile t   ||  PV of block 0, tile t;    scores of block 0, tile t+1
 // The MFMAs are interleaved with the VALU work by an explicit scheduling recipe.
 // ---------------------------------------------------------------------------------------
-// LDS address (byte offset in the workgroup's LDS) of a __shared__ object
-__device__ __forceinline__ uint32_t lds_addr(const void *p) {
-  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
-}
-// Four 16-byte LDS reads at addr + 0, 1, 2, 3 KB, issued here and NOT waited for: the compiler
-// does not know that dst is still in flight, so every use of dst must come after an lds_wait
-// on the same registers.
-__device__ __forceinline__ void lds_read4_async(u32x4 (&dst)[4], uint32_t addr) {
-  asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:1024\n\t"
-               "ds_read_b128 %2, %4 offset:2048\n\tds_read_b128 %3, %4 offset:3072"
-               : "=&v"(dst[0]), "=&v"(dst[1]), "=&v"(dst[2]), "=&v"(dst[3])
-               : "v"(addr)
-               : "memory");
-}
 // waits until every LDS operation issued so far has completed
 __device__ __forceinline__ void lds_wait(u32x4 (&a)[4], u32x4 (&b)[4]) {
   asm volatile("s_waitcnt lgkmcnt(0)"

@@ -57,6 +57,28 @@ __device__ __forceinline__ uint32_t xcd_contiguous(uint32_t b, uint32_t n) {
   return (b % kXcd) * per + b / kXcd;   // may be >= n: caller skips
 }
 
+// LDS address (byte offset in the workgroup's LDS) of a __shared__ object
+__device__ __forceinline__ uint32_t lds_addr(const void *p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+// Four 16-byte LDS reads at addr + 0, 1, 2, 3 KB, issued here and NOT waited for: the compiler
+// does not know that dst is still in flight, so every use of dst must come after an lds_wait
+// on the same registers.
+__device__ __forceinline__ void lds_read4_async(u32x4 (&dst)[4], uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:1024\n\t"
+               "ds_read_b128 %2, %4 offset:2048\n\tds_read_b128 %3, %4 offset:3072"
+               : "=&v"(dst[0]), "=&v"(dst[1]), "=&v"(dst[2]), "=&v"(dst[3])
+               : "v"(addr)
+               : "memory");
+}
+// Two such reads, at addr and addr + 1 KB.
+__device__ __forceinline__ void lds_read2_async(u32x4 (&dst)[2], uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:1024"
+               : "=&v"(dst[0]), "=&v"(dst[1])
+               : "v"(addr)
+               : "memory");
+}
+
 }  // namespace lv
 
 #define LV_HIP_CHECK_LAUNCH()                                  \

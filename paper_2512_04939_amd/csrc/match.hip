@@ -2,32 +2,14 @@
 // construction of the merge index (CSR groups).
 //
 // The similarity is a dense contraction dst[n_dst,C] x src[n_src,C]^T that is never
-// materialised: a workgroup keeps 64 src rows resident in LDS as ready-made MFMA B
-// fragments, its waves stream 64-row blocks of the (pre-packed, fragment-major) dst matrix
-// straight from L2 into registers as A fragments, run v_mfma_f32_32x32x16_bf16 over the
-// whole channel dimension, and fold each finished 32x32 tile into a per-lane running
-// (best, second best) pair.  With dst as the MFMA row dimension every lane owns one src
-// column, so the running arg-max needs no cross-lane traffic until the very end.
-// bf16 x bf16 products are exact in fp32, only the accumulation order differs from an
-// exact dot product; rows whose two best candidates are closer than kRescoreGap are
-// re-decided from float64 dot products in a cheap second kernel.
+// materialised (see k_match_sim).  bf16 x bf16 products are exact in fp32, only the
+// accumulation order differs from an exact dot product; rows whose two best candidates are
+// closer than kRescoreGap are re-decided from float64 dot products in a cheap second kernel.
 #include "common.h"
 #include "internal.h"
 
 namespace lv {
 
-constexpr int kSrcTile = 64;         // src rows resident per workgroup
-#ifndef LV_MATCH_WAVES
-#define LV_MATCH_WAVES 12
-#endif
-#ifndef LV_MATCH_DEPTH
-#define LV_MATCH_DEPTH 2
-#endif
-#ifndef LV_MATCH_PANEL_GROUPS
-#define LV_MATCH_PANEL_GROUPS 11   /* 11 groups x 768 rows x 2 KB = 16.5 MB of dst per launch */
-#endif
-constexpr int kMatchWaves = LV_MATCH_WAVES;   // 12 = 3 waves per SIMD (measured best)
-constexpr int kDepth = LV_MATCH_DEPTH;        // register ring: chunks of dst fragments in flight per wave
 constexpr float kRescoreGap = 2e-4f; // similarity gap below which float64 decides
 
 struct Top2 {
@@ -55,43 +37,29 @@ __global__ __launch_bounds__(256) void k_inv_norm(const uint16_t *__restrict__ x
   }
 }
 
-// Gather dst rows into fragment-major order: fragment (tile t of 32 rows, k-step s of 16
+// Gather token rows into fragment-major order: fragment (tile t of 32 rows, k-step s of 16
 // channels) is 1 KB contiguous, lane (h*32 + r) holds row r, channels 16s+8h .. 16s+8h+7.
-// Rows beyond n_dst are zero.
-__global__ __launch_bounds__(256) void k_pack_dst(const uint16_t *__restrict__ x,
-                                                  const int32_t *__restrict__ dst_idx,
-                                                  const float *__restrict__ inv, int n_dst,
-                                                  int n_dst_pad, int C, u32x4 *__restrict__ packed,
-                                                  float *__restrict__ invd,
-                                                  int32_t *__restrict__ belt) {
+// Rows beyond n are zero.  inv_out (optional) receives the rows' inverse norms, 0 beyond n.
+__global__ __launch_bounds__(256) void k_pack_rows(const uint16_t *__restrict__ x,
+                                                   const int32_t *__restrict__ idx_of,
+                                                   const float *__restrict__ inv, int n, int n_pad,
+                                                   int C, u32x4 *__restrict__ packed,
+                                                   float *__restrict__ inv_out) {
   const int nch = C >> 3, KS = C >> 4;
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < kXcd) belt[idx] = 0;   // sweep positions of the matching kernel start at 0
-  if (idx >= (int64_t)n_dst_pad * nch) return;
+  if (idx >= (int64_t)n_pad * nch) return;
   const int j = (int)(idx / nch), c = (int)(idx % nch);
   u32x4 w = {0u, 0u, 0u, 0u};
   int row = -1;
-  if (j < n_dst) {
-    row = dst_idx[j];
+  if (j < n) {
+    row = idx_of[j];
     w = ((const u32x4 *)(x + (size_t)row * C))[c];
   }
   const int t = j >> 5, r = j & 31, s = c >> 1, h = c & 1;
   packed[((size_t)t * KS + s) * 64 + h * 32 + r] = w;
-  if (c == 0) invd[j] = row >= 0 ? inv[row] : 0.f;
+  if (inv_out && c == 0) inv_out[j] = row >= 0 ? inv[row] : 0.f;
 }
 
-__device__ __forceinline__ void top2_insert_ordered(Top2 &t, float v, int i) {
-  // candidates arrive in ascending index order: strict > keeps the lowest index on ties
-  if (v > t.v1) {
-    t.v2 = t.v1;
-    t.i2 = t.i1;
-    t.v1 = v;
-    t.i1 = i;
-  } else if (v > t.v2) {
-    t.v2 = v;
-    t.i2 = i;
-  }
-}
 __device__ __forceinline__ void top2_insert_any(Top2 &t, float v, int i) {
   if (i < 0) return;
   if (v > t.v1 || (v == t.v1 && (t.i1 < 0 || i < t.i1))) {
@@ -105,170 +73,197 @@ __device__ __forceinline__ void top2_insert_any(Top2 &t, float v, int i) {
   }
 }
 
-__global__ __launch_bounds__(kMatchWaves * 64) void k_match(
-    const uint16_t *__restrict__ x, const int32_t *__restrict__ src_idx, int n_src,
-    const u32x4 *__restrict__ dstp, const float *__restrict__ invd, int n_dst, int g_first,
-    int n_groups, int C, Top2 *__restrict__ top2, int32_t *belt) {
-  extern __shared__ u32x4 frag[];   // [2 src tiles][KS][64 lanes]
-  __shared__ int g_start;
-  const int KS = C >> 4, nch = C >> 3, NCHUNK = KS >> 2;
+// ---------------------------------------------------------------------------------
+// Similarity kernel.  A workgroup (8 waves) computes 256 src x 256 dst tiles of the similarity
+// matrix with the channel dimension as the inner loop: both operands come pre-packed in
+// fragment-major order, go from global memory straight into a 4-stage LDS ring (2 k-steps =
+// 32 KB per stage, fetched 3 stages ahead) and are read from there as MFMA fragments, so every
+// byte fetched from L2 feeds 128 flop (a src-resident design with streamed dst reaches 64 and
+// was bound by the L2 -> CU rate).  Wave (wd, ws) owns the 64 dst x 128 src sub-tile: dst is
+// the MFMA row dimension, so a lane owns one src column per 32-column block and folds every
+// finished tile into its running (best, second best) pair without cross-lane traffic.
+//
+// Workgroup (src tile st, lane dl) sweeps the dst tiles dl, dl + L, dl + 2L, ...; the L
+// partial results of a src row are merged by k_match_finish.  Workgroups are dealt to the
+// XCDs round-robin by the hardware; the block index is decoded so that the 32 workgroups an
+// XCD runs together are 8 src tiles x 4 lanes at the same sweep position, which share both
+// operands in that XCD's L2.
+// ---------------------------------------------------------------------------------
+constexpr int kGTile = 256;          // src and dst rows per workgroup tile
+constexpr int kGStages = 4;          // LDS ring depth
+constexpr int kGStageU4 = 2 * 2 * 8 * 64;   // u32x4 per stage: [src|dst][2 k-steps][8 fragments][64 lanes]
+constexpr int kGLanes = 4;           // dst tiles are dealt to this many workgroups per src tile
+
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_match_sim(
+    const u32x4 *__restrict__ srcp, const u32x4 *__restrict__ dstp, const float *__restrict__ invd,
+    int n_dst, int n_src_tiles, int n_dst_tiles, int n_lanes, int KS, int n_src_pad,
+    Top2 *__restrict__ top2p) {
+  extern __shared__ u32x4 ring[];    // kGStages stages
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // keeps address math scalar
-  // All workgroups of an XCD share one L2.  They sweep the dst matrix circularly and a new
-  // workgroup joins the sweep where its XCD's others currently are (belt[xcd], a hint that
-  // wave 0 keeps publishing), so the same dst rows are requested by many CUs while they
-  // are still resident in that L2 instead of each CU streaming them from memory.
-  const int xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kXcd - 1);   // XCC_ID[3:0]
-  if (tid == 0) {
-    int g = __atomic_load_n(&belt[xcd], __ATOMIC_RELAXED);
-    g_start = (g >= 0 && g < n_groups) ? g : 0;
-  }
-  const int src0 = blockIdx.x * kSrcTile;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wd = wave & 3, wsrc = wave >> 2;
+  const int xcd = blockIdx.x & (kXcd - 1), q = blockIdx.x >> 3;
+  const int dl = q % n_lanes, st = (q / n_lanes) * kXcd + xcd;
+  if (st >= n_src_tiles) return;
+  const int nt = dl < n_dst_tiles ? (n_dst_tiles - dl + n_lanes - 1) / n_lanes : 0;   // my dst tiles
+  const int SPT = KS >> 1;           // stages per tile
+  const int total = nt * SPT;
 
-  for (int idx = tid; idx < kSrcTile * nch; idx += blockDim.x) {
-    const int row = idx / nch, c = idx - row * nch;
-    const int srow = min(src0 + row, n_src - 1);
-    const u32x4 w = ((const u32x4 *)(x + (size_t)src_idx[srow] * C))[c];
-    frag[((row >> 5) * KS + (c >> 1)) * 64 + (c & 1) * 32 + (row & 31)] = w;
-  }
-  __syncthreads();
+  Top2 best[4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b) best[b] = Top2{-INFINITY, -1, -INFINITY, -1};
 
-  Top2 best[2];
+  if (total > 0) {
+    // fetch: this wave moves fragments f = 4*wave .. 4*wave+3 of a stage (f = op*16 + ks*8 + a)
+    const int f_op = wave >> 2, f_ks = (wave >> 1) & 1, f_a0 = (wave & 1) * 4;
+    int pf_tile = dl, pf_s = 0, pf_g = 0;      // next stage to fetch: dst tile, stage in tile, flat index
+    auto fetch = [&]() {
+      const int tile = f_op ? pf_tile : st;
+      const u32x4 *src = (f_op ? dstp : srcp) +
+                         ((size_t)(tile * 8 + f_a0) * KS + (size_t)(pf_s * 2 + f_ks)) * 64 + lane;
+      u32x4 *dst = ring + (size_t)(pf_g & (kGStages - 1)) * kGStageU4 + (size_t)(wave * 4) * 64;
 #pragma unroll
-  for (int b = 0; b < 2; ++b) best[b] = Top2{-INFINITY, -1, -INFINITY, -1};
-
-  // A group is kMatchWaves consecutive tile pairs (64 dst rows each), one per wave.  This
-  // wave's K-chunks (4 k-steps = 8 fragments) over all groups form one flat stream that is
-  // prefetched kDepth-1 chunks ahead through a register ring, across tile-pair boundaries,
-  // so that enough bytes are in flight to cover L2 latency.
-  const int g0 = g_start;
-  const int total = n_groups * NCHUNK;
-  const size_t a1off = (size_t)KS * 64;
-  u32x4 ring[kDepth][8];
-  int pgrp = g0, psb = 0, pg = 0;            // next chunk to fetch: group, chunk, flat index
-  auto fetch = [&](u32x4(&buf)[8]) {
-    const int ptp = (g_first + pgrp) * kMatchWaves + wave;
-    const u32x4 *ap = dstp + ((size_t)(2 * ptp) * KS + (size_t)psb * 4) * 64 + lane;
+      for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_global_load_lds(src + (size_t)i * KS * 64, dst + i * 64, 16, 0, 0);
+      ++pf_g;
+      // past the end the last stage is fetched again (into a free slot nobody reads)
+      if (pf_g < total && ++pf_s == SPT) {
+        pf_s = 0;
+        pf_tile += n_lanes;
+      }
+    };
+    const uint32_t ring_lane = lds_addr(&ring[lane]);
+    // byte offsets of this wave's fragments inside a stage, k-step 0: src (B operand) fragments
+    // 4*wsrc .. +3, dst (A operand) fragments 2*wd, 2*wd+1; k-step 1 is 8 KB further
+    const uint32_t b_off = (uint32_t)((0 * 16 + wsrc * 4) * 1024), a_off = (uint32_t)((16 + wd * 2) * 1024);
+    u32x4 fb[2][4], fa[2][2];
+    auto read_frags = [&](int g, int ks, u32x4(&b)[4], u32x4(&a)[2]) {
+      const uint32_t base = ring_lane + (uint32_t)((g & (kGStages - 1)) * kGStageU4 * 16 + ks * 8 * 1024);
+      lds_read4_async(b, base + b_off);
+      lds_read2_async(a, base + a_off);
+    };
+    auto wait_frags = [&](u32x4(&b)[4], u32x4(&a)[2]) {
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(a[0]), "+v"(a[1])
+                   :
+                   : "memory");
+    };
+    f32x16 acc[2][4];
+    auto clear_acc = [&]() {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      buf[ks] = ap[(size_t)ks * 64];
-      buf[4 + ks] = ap[a1off + (size_t)ks * 64];
-    }
-    ++pg;
-    if (++psb == NCHUNK) {
-      psb = 0;
-      if (++pgrp == n_groups) pgrp = 0;
-    }
-  };
-  f32x16 acc[2][2];
-  auto clear_acc = [&]() {
+      for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+          for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    };
+    auto mma = [&](const u32x4(&b)[4], const u32x4(&a)[2]) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-  };
-  clear_acc();
+      for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
-  for (int j = 0; j < kDepth - 1; ++j)
-    if (pg < total) fetch(ring[j]);
-  int grp = g0, sb = 0;                      // chunk being computed
-  for (int f0 = 0; f0 < total; f0 += kDepth) {
+        for (int ai = 0; ai < 2; ++ai)
+          acc[ai][bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[ai]),
+                                                               __builtin_bit_cast(bf16x8, b[bi]),
+                                                               acc[ai][bi], 0, 0, 0);
+    };
+    // fold the eight finished 32x32 tiles into the running top-2 of this lane's four columns
+    auto fold = [&](int tile) {
 #pragma unroll
-    for (int j = 0; j < kDepth; ++j) {
-      if (f0 + j < total) {
-        if (pg < total) fetch(ring[(j + kDepth - 1) % kDepth]);
+      for (int a = 0; a < 2; ++a) {
+        const int row0 = tile * kGTile + wd * 64 + a * 32 + h * 4;
+        const f32x4 *ip = (const f32x4 *)(invd + row0);
+        f32x4 iv[4];
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          const int s = sb * 4 + ks;
-          const bf16x8 a0 = __builtin_bit_cast(bf16x8, ring[j][ks]);
-          const bf16x8 a1 = __builtin_bit_cast(bf16x8, ring[j][4 + ks]);
-#ifdef LV_MATCH_NOLDS   /* timing experiment only: wrong results */
-          const bf16x8 b0 = a1, b1 = a0;
-          (void)s;
-#else
-          const bf16x8 b0 = __builtin_bit_cast(bf16x8, frag[(size_t)s * 64 + lane]);
-          const bf16x8 b1 = __builtin_bit_cast(bf16x8, frag[(size_t)(KS + s) * 64 + lane]);
-#endif
-          acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
-          acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
-          acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
-          acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
-        }
-        if (++sb == NCHUNK) {
-          // fold the four finished 32x32 tiles into the running top-2 of this lane's columns
-          const int tp = (g_first + grp) * kMatchWaves + wave;
+        for (int g = 0; g < 4; ++g) iv[g] = ip[2 * g];
 #pragma unroll
-          for (int a = 0; a < 2; ++a) {
-            const int row0 = (2 * tp + a) * 32 + h * 4;
-            const f32x4 *ip = (const f32x4 *)(invd + row0);
-            f32x4 iv[4];
+        for (int b = 0; b < 4; ++b) {
+          float v[16];
+          float m = -INFINITY;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) iv[g] = ip[2 * g];
+          for (int r = 0; r < 16; ++r) {
+            v[r] = acc[a][b][r] * iv[r >> 2][r & 3];
+            m = fmaxf(m, v[r]);
+          }
+          if (__builtin_amdgcn_ballot_w64(m > best[b].v2) != 0) {
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
-              float v[16];
-              float m = -INFINITY;
-#pragma unroll
-              for (int r = 0; r < 16; ++r) {
-                v[r] = acc[a][b][r] * iv[r >> 2][r & 3];
-                m = fmaxf(m, v[r]);
-              }
-              if (__builtin_amdgcn_ballot_w64(m > best[b].v2) != 0) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                  const int j2 = row0 + (r >> 2) * 8 + (r & 3);
-                  if (j2 < n_dst) top2_insert_any(best[b], v[r], j2);   // sweep order is circular
-                }
-              }
+            for (int r = 0; r < 16; ++r) {
+              const int j2 = row0 + (r >> 2) * 8 + (r & 3);
+              if (j2 < n_dst) top2_insert_any(best[b], v[r], j2);
             }
           }
-          clear_acc();
-          sb = 0;
-          if (++grp == n_groups) grp = 0;
-          if (wave == 0 && lane == 0) __atomic_store_n(&belt[xcd], grp, __ATOMIC_RELAXED);
         }
       }
-    }
-  }
+    };
 
-  __syncthreads();   // everyone is done with the resident fragments: reuse LDS
-  Top2 *cand = (Top2 *)frag;
+    clear_acc();
 #pragma unroll
-  for (int b = 0; b < 2; ++b) cand[(wave * 2 + b) * 64 + lane] = best[b];
-  __syncthreads();
-  if (tid < kSrcTile) {
-    const int b = tid >> 5, q = tid & 31;
-    Top2 t = Top2{-INFINITY, -1, -INFINITY, -1};
-    for (int w = 0; w < kMatchWaves; ++w)
-      for (int hh = 0; hh < 2; ++hh) {
-        const Top2 c = cand[(w * 2 + b) * 64 + hh * 32 + q];
-        top2_insert_any(t, c.v1, c.i1);
-        top2_insert_any(t, c.v2, c.i2);
+    for (int i = 0; i < kGStages; ++i) fetch();                // stages 0..3
+    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");          // stage 0 has landed (this wave's part)
+    __builtin_amdgcn_s_barrier();
+    read_frags(0, 0, fb[0], fa[0]);
+    int tile = dl, sidx = 0;
+    for (int g = 0; g < total; ++g) {
+      // k-step 0 of stage g
+      __builtin_amdgcn_sched_barrier(0);
+      wait_frags(fb[0], fa[0]);
+      read_frags(g, 1, fb[1], fa[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(fb[0], fa[0]);
+      // k-step 1 of stage g: its fragments are in registers, so the slot of stage g is free once
+      // every wave is here; stage g+1 is published by the same barrier
+      __builtin_amdgcn_sched_barrier(0);
+      wait_frags(fb[1], fa[1]);
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");         // stage g+1 has landed; g+2, g+3 may be in flight
+      __builtin_amdgcn_s_barrier();
+      fetch();                                                 // stage g+4 -> slot of stage g
+      read_frags(g + 1, 0, fb[0], fa[0]);                      // past the end: a stale slot, never used
+      __builtin_amdgcn_sched_barrier(0);
+      mma(fb[1], fa[1]);
+      if (++sidx == SPT) {
+        fold(tile);
+        clear_acc();
+        sidx = 0;
+        tile += n_lanes;
       }
-    if (src0 + tid < n_src) {
-      if (g_first > 0) {   // earlier launches covered the dst rows before this panel
-        const Top2 prev = top2[src0 + tid];
-        top2_insert_any(t, prev.v1, prev.i1);
-        top2_insert_any(t, prev.v2, prev.i2);
-      }
-      top2[src0 + tid] = t;
     }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // nothing may land in LDS any more
+  }
+  __syncthreads();
+  // merge the two half-wave copies of a column and the four dst quarters (waves wd = 0..3)
+  Top2 *cand = (Top2 *)ring;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) cand[(wave * 4 + b) * 64 + lane] = best[b];
+  __syncthreads();
+  if (tid < kGTile) {
+    const int ws2 = tid >> 7, b = (tid >> 5) & 3, c = tid & 31;
+    Top2 t = Top2{-INFINITY, -1, -INFINITY, -1};
+    for (int w = 0; w < 4; ++w)
+      for (int hh = 0; hh < 2; ++hh) {
+        const Top2 cd = cand[((ws2 * 4 + w) * 4 + b) * 64 + hh * 32 + c];
+        top2_insert_any(t, cd.v1, cd.i1);
+        top2_insert_any(t, cd.v2, cd.i2);
+      }
+    top2p[(size_t)dl * n_src_pad + (size_t)st * kGTile + tid] = t;
   }
 }
 
-// Final decision per src row (one wave each).  Rows whose two best fp32 similarities are
+// Final decision per src row (one wave each): merge the partial results of the sweeps; rows
+// whose two best fp32 similarities are
 // closer than kRescoreGap recompute both in float64 and decide on the fp32-rounded values,
 // lowest token index on a tie.
 __global__ __launch_bounds__(256) void k_match_finish(
     const uint16_t *__restrict__ x, const int32_t *__restrict__ src_idx,
     const int32_t *__restrict__ dst_idx, const float *__restrict__ inv,
-    const Top2 *__restrict__ top2, int n_src, int C, int32_t *__restrict__ anchor_of,
-    int32_t *slot_of, float *__restrict__ best_sim) {
+    const Top2 *__restrict__ top2p, int n_lanes, int n_src_pad, int n_src, int C,
+    int32_t *__restrict__ anchor_of, int32_t *slot_of, float *__restrict__ best_sim) {
   const int lane = threadIdx.x & 63, wpb = blockDim.x >> 6, nch = C >> 3;
   for (int p = blockIdx.x * wpb + (threadIdx.x >> 6); p < n_src; p += gridDim.x * wpb) {
-    const Top2 t = top2[p];
+    Top2 t = top2p[p];
+    for (int l = 1; l < n_lanes; ++l) {    // the other sweeps' candidates for this row
+      const Top2 o = top2p[(size_t)l * n_src_pad + p];
+      top2_insert_any(t, o.v1, o.i1);
+      top2_insert_any(t, o.v2, o.i2);
+    }
     const int s = src_idx[p];
     const float invs = inv[s];
     int choose = t.i1 < 0 ? 0 : t.i1;
@@ -417,15 +412,14 @@ __global__ __launch_bounds__(256) void k_csr_finish(const uint32_t *__restrict__
 // ---------------------------------------------------------------------------------
 struct MatchWs {
   float *inv;
-  u32x4 *dstp;
+  u32x4 *dstp, *srcp;
   float *invd;
-  Top2 *top2;
+  Top2 *top2p;
   uint32_t *keys[2];
   int32_t *vals[2];
   uint32_t *hist;
-  int32_t *belt;
   size_t bytes;
-  int n_dst_pad, nchunks;
+  int n_dst_pad, n_src_pad, n_lanes, nchunks;
 };
 
 static MatchWs carve(const Dims &d, const litevggt_plan_t &pl, char *base) {
@@ -436,18 +430,21 @@ static MatchWs carve(const Dims &d, const litevggt_plan_t &pl, char *base) {
     off += align_up(bytes, 256);
     return p;
   };
-  w.n_dst_pad = (int)align_up((size_t)pl.n_dst, 64 * kMatchWaves);   // whole groups
+  w.n_dst_pad = (int)align_up((size_t)pl.n_dst, kGTile);
+  w.n_src_pad = (int)align_up((size_t)pl.n_src, kGTile);
+  const int dst_tiles = w.n_dst_pad / kGTile;
+  w.n_lanes = dst_tiles < kGLanes ? (dst_tiles > 0 ? dst_tiles : 1) : kGLanes;
   w.nchunks = (int)((d.N + kSortChunk - 1) / kSortChunk);
   w.inv = (float *)take((size_t)d.N * 4);
   w.dstp = (u32x4 *)take((size_t)w.n_dst_pad * d.C * 2);
+  w.srcp = (u32x4 *)take((size_t)w.n_src_pad * d.C * 2);
   w.invd = (float *)take((size_t)w.n_dst_pad * 4);
-  w.top2 = (Top2 *)take(align_up((size_t)pl.n_src, 64) * sizeof(Top2));
+  w.top2p = (Top2 *)take((size_t)w.n_lanes * w.n_src_pad * sizeof(Top2));
   for (int i = 0; i < 2; ++i) {
     w.keys[i] = (uint32_t *)take((size_t)d.N * 4);
     w.vals[i] = (int32_t *)take((size_t)d.N * 4);
   }
   w.hist = (uint32_t *)take((size_t)256 * w.nchunks * 4);
-  w.belt = (int32_t *)take(kXcd * sizeof(int32_t));
   w.bytes = off;
   return w;
 }
@@ -459,35 +456,30 @@ int launch_match(const uint16_t *x, const Dims &d, const litevggt_plan_t &pl,
   MatchWs w = carve(d, pl, (char *)ws);
   const int n_src = (int)pl.n_src, n_dst = (int)pl.n_dst;
   if (n_src > 0) {
-    size_t lds = (size_t)2 * (d.C / 16) * 64 * 16;     // resident src fragments
-    const size_t cand = (size_t)kMatchWaves * 2 * 64 * sizeof(Top2);   // reused at the end
-    if (lds < cand) lds = cand;
-    if (lds > 160 * 1024 - 1024) return LV_ERR_SHAPE;
-    static size_t lds_set = 0;
-    if (lds > lds_set) {
-      if (hipFuncSetAttribute((const void *)k_match, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (d.C % 32 != 0 || n_dst <= 0) return LV_ERR_SHAPE;
+    const size_t lds = (size_t)kGStages * kGStageU4 * 16;        // 128 KB ring (reused for the final merge)
+    static bool lds_set = false;
+    if (!lds_set) {
+      if (hipFuncSetAttribute((const void *)k_match_sim, hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)lds) != hipSuccess)
         return LV_ERR_HIP;
-      lds_set = lds;
+      lds_set = true;
     }
     const unsigned rows_grid = (unsigned)(((d.N + 3) / 4) < 16384 ? ((d.N + 3) / 4) : 16384);
     hipLaunchKernelGGL(k_inv_norm, dim3(rows_grid), dim3(256), 0, st, x, d.N, d.C, w.inv);
-    const int64_t pk = (int64_t)w.n_dst_pad * (d.C / 8);
-    hipLaunchKernelGGL(k_pack_dst, dim3((unsigned)((pk + 255) / 256)), dim3(256), 0, st, x,
-                       ix.dst_idx, w.inv, n_dst, w.n_dst_pad, d.C, w.dstp, w.invd, w.belt);
-    // The dst matrix is processed in panels small enough to stay resident in every XCD's L2
-    // (one launch per panel, all workgroups of a launch stream the same panel); the running
-    // top-2 of each src row is carried from launch to launch in `top2`.
-    const int groups = w.n_dst_pad / (64 * kMatchWaves);
-    const int per_panel = LV_MATCH_PANEL_GROUPS > 0 ? LV_MATCH_PANEL_GROUPS : groups;
-    for (int g = 0; g < groups; g += per_panel)
-      hipLaunchKernelGGL(k_match, dim3((unsigned)((n_src + kSrcTile - 1) / kSrcTile)),
-                         dim3(kMatchWaves * 64), lds, st, x, ix.src_idx, n_src, w.dstp, w.invd,
-                         n_dst, g, (groups - g < per_panel ? groups - g : per_panel), d.C, w.top2,
-                         w.belt);
+    const int64_t pkd = (int64_t)w.n_dst_pad * (d.C / 8), pks = (int64_t)w.n_src_pad * (d.C / 8);
+    hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)((pkd + 255) / 256)), dim3(256), 0, st, x,
+                       ix.dst_idx, w.inv, n_dst, w.n_dst_pad, d.C, w.dstp, w.invd);
+    hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)((pks + 255) / 256)), dim3(256), 0, st, x,
+                       ix.src_idx, w.inv, n_src, w.n_src_pad, d.C, w.srcp, (float *)nullptr);
+    const int src_tiles = w.n_src_pad / kGTile, dst_tiles = w.n_dst_pad / kGTile;
+    const unsigned grid = (unsigned)(((src_tiles + kXcd - 1) / kXcd) * kXcd * w.n_lanes);
+    hipLaunchKernelGGL(k_match_sim, dim3(grid), dim3(512), lds, st, w.srcp, w.dstp, w.invd, n_dst,
+                       src_tiles, dst_tiles, w.n_lanes, d.C / 16, w.n_src_pad, w.top2p);
     const unsigned fin = (unsigned)(((n_src + 3) / 4) < 16384 ? ((n_src + 3) / 4) : 16384);
     hipLaunchKernelGGL(k_match_finish, dim3(fin), dim3(256), 0, st, x, ix.src_idx, ix.dst_idx,
-                       w.inv, w.top2, n_src, d.C, ix.anchor_of, ix.slot_of, best_sim);
+                       w.inv, w.top2p, w.n_lanes, w.n_src_pad, n_src, d.C, ix.anchor_of, ix.slot_of,
+                       best_sim);
     LV_HIP_CHECK_LAUNCH();
   }
   // CSR groups by stable radix sort of slot_of
