@@ -84,12 +84,6 @@ __global__ __launch_bounds__(256) void k_attn_pack(const uint16_t *__restrict__ 
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
-#ifdef LV_ATTN_TRACE
-__device__ unsigned long long g_attn_trace[8][4096];
-#define LV_TRACE(slot) do { if (blockIdx.x == 8 && lane == 0 && (slot) < 4096) g_attn_trace[wave][(slot)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define LV_TRACE(slot) do {} while (0)
-#endif
 constexpr int kKSlots = 2;           // LDS ring slots of 64-key K tiles
 constexpr int kVSlots = 3;           // LDS ring slots of 64-key V tiles
 
@@ -299,14 +293,10 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
   if (grp == 0) {
     for (int j = 0; j < nkv; ++j) {
       if (j + 1 < nkv) g2r(j + 1);
-      LV_TRACE(4 * j);
       phase_m(j);                        // phase 2j
-      LV_TRACE(4 * j + 1);
       __syncthreads();
       if (j + 1 < nkv) r2s(j + 1);
-      LV_TRACE(4 * j + 2);
       phase_v(j);                        // phase 2j+1
-      LV_TRACE(4 * j + 3);
       __syncthreads();
     }
     phase_m(nkv);                        // phase 2*nkv: last PV
@@ -320,14 +310,10 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
     __syncthreads();
     for (int j = 1; j < nkv; ++j) {
       if (j + 1 < nkv) g2r(j + 1);
-      LV_TRACE(4 * j);
       phase_v(j - 1);                    // phase 2j
-      LV_TRACE(4 * j + 1);
       __syncthreads();
       if (j + 1 < nkv) r2s(j + 1);
-      LV_TRACE(4 * j + 2);
       phase_m(j);                        // phase 2j+1
-      LV_TRACE(4 * j + 3);
       __syncthreads();
     }
     phase_v(nkv - 1);                    // phase 2*nkv
@@ -377,20 +363,6 @@ __device__ __forceinline__ void lds_wait(u32x4 (&a)[4], u32x4 (&b)[4]) {
 constexpr int kBQB = 256;            // queries per workgroup (4 waves)
 constexpr int kBStages = 4;          // LDS ring of 64-key K/V stages
 
-#ifndef LV_ATTN_RECIPE
-#define LV_ATTN_RECIPE 1
-#endif
-// timing experiments only (results are wrong when set): skip the global->LDS staging (bit 0)
-// and the barrier (bit 1) of the steady state / skip the fragment reads
-#ifndef LV_ATTN_TIMING_NOSTAGE
-#define LV_ATTN_TIMING_NOSTAGE 0
-#endif
-#ifndef LV_ATTN_TIMING_NOLDS
-#define LV_ATTN_TIMING_NOLDS 0
-#endif
-#ifndef LV_ATTN_MIX
-#define LV_ATTN_MIX 0
-#endif
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_bf16_bounded(
     const uint16_t *__restrict__ q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp,
@@ -487,21 +459,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             __builtin_bit_cast(bf16x8, vf[u * 2 + dt]), __builtin_bit_cast(bf16x8, pb[sub][u]),
             oacc[sub][dt], 0, 0, 0);
   };
-  // PV of block sub_pv and scores of block sub_s, alternating, so that no MFMA needs the
-  // result of the one issued just before it (the score chain is spaced by two, the two output
-  // accumulators by four)
-  auto mma_mix = [&](int sub_pv, const u32x4(&vf)[4], int sub_s, const u32x4(&kf)[4]) {
-    f32x16 acc = kZero;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[s]), qf[sub_s][s],
-                                                    acc, 0, 0, 0);
-      oacc[sub_pv][s & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-          __builtin_bit_cast(bf16x8, vf[s]), __builtin_bit_cast(bf16x8, pb[sub_pv][s >> 1]),
-          oacc[sub_pv][s & 1], 0, 0, 0);
-    }
-    sacc[sub_s] = acc;
-  };
   auto mask_tail = [&](int t, int sub) {   // keys beyond the sequence end
     if ((int64_t)(t + 1) * kKT > n) {
 #pragma unroll
@@ -538,17 +495,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // recipe asks the scheduler to spread the MFMAs over the VALU work; A phases re-fill fv
   // after their 4 PV MFMAs and fk after their 4 score MFMAs.  (Forcing a strict
   // exp2/exp2/MFMA/pack/sum order with opaque pins was measured slower than this.)
-  auto recipe = [&](bool with_loads) {
-#if LV_ATTN_RECIPE
-    if (with_loads) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);     // V reads first
+  auto recipe = [&]() {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // 2 exp2
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
       __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // pack + 2 adds
     }
-    if (with_loads) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);     // K reads last
-#endif
   };
   // In the steady state the fragment reads are issued by hand (lds_read4_async): V(t) and
   // K(t+1) at the start of A(t); B(t) is their first user and waits for them a whole phase
@@ -568,26 +521,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   };
   auto phase_a = [&](int t, const u32x4(&v_prev)[4], u32x4(&v_cur)[4], const u32x4(&k_cur)[4],
                      u32x4(&k_next)[4], int fq = -1) {
-#if LV_ATTN_TIMING_NOLDS
-    asm volatile("" : "+v"(v_cur[0]), "+v"(v_cur[1]), "+v"(v_cur[2]), "+v"(v_cur[3]), "+v"(k_next[0]),
-                 "+v"(k_next[1]), "+v"(k_next[2]), "+v"(k_next[3]));
-#else
     lds_read4_async(v_cur, vs_lane + frag_off(t));
     lds_read4_async(k_next, ks_lane + frag_off(t + 1));   // past the last tile: a stale slot, never used
-#endif
     if (fq >= 0) fetch1(fq);
     __builtin_amdgcn_sched_barrier(0);
     weights(0);
-#if LV_ATTN_MIX == 1
-    mma_mix(1, v_prev, 1, k_cur);
-#elif LV_ATTN_MIX == 2
-    mma_s(1, k_cur);
-    mma_pv(1, v_prev);
-#else
     mma_pv(1, v_prev);
     mma_s(1, k_cur);
-#endif
-    recipe(false);
+    recipe();
   };
   // B(t), t <= nkt-2: weights of block 1 || PV(t) and scores(t+1) of block 0
   auto phase_b = [&](u32x4(&v_cur)[4], u32x4(&k_next)[4], int fq = -1) {
@@ -598,16 +539,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       __builtin_amdgcn_sched_barrier(0);
     }
     weights(1);
-#if LV_ATTN_MIX == 1
-    mma_mix(0, v_cur, 0, k_next);
-#elif LV_ATTN_MIX == 2
-    mma_s(0, k_next);
-    mma_pv(0, v_cur);
-#else
     mma_pv(0, v_cur);
     mma_s(0, k_next);
-#endif
-    recipe(false);
+    recipe();
   };
 
   fetch(0);
@@ -1022,11 +956,6 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
   }
 }
 
-#ifdef LV_ATTN_TRACE
-extern "C" int lv_debug_attn_trace(unsigned long long *host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_attn_trace), sizeof(g_attn_trace));
-}
-#endif
 
 static int n_key_tiles(int64_t n) { return (int)(2 * ((n + kKV - 1) / kKV)); }
 

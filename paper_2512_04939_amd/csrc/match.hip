@@ -166,7 +166,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                                                __builtin_bit_cast(bf16x8, b[bi]),
                                                                acc[ai][bi], 0, 0, 0);
     };
-    // fold the eight finished 32x32 tiles into the running top-2 of this lane's four columns
+    // Fold the eight finished 32x32 tiles into the running top-2 of this lane's four columns.
+    // Almost no element beats its column's second best once a few tiles have been seen, but
+    // with 64 columns per wave "some lane of the wave has such an element in this tile" is true
+    // nearly always, so the test is made per element: a compare per element and one branch per
+    // tile in the common case, the insertion code only for the elements that need it.
     auto fold = [&](int tile) {
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
@@ -178,17 +182,20 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
           float v[16];
-          float m = -INFINITY;
+          uint64_t hit[16], any = 0;       // lanes whose element r beats their second best (scalar masks)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             v[r] = acc[a][b][r] * iv[r >> 2][r & 3];
-            m = fmaxf(m, v[r]);
+            hit[r] = __builtin_amdgcn_ballot_w64(v[r] > best[b].v2);
+            any |= hit[r];
           }
-          if (__builtin_amdgcn_ballot_w64(m > best[b].v2) != 0) {
+          if (any != 0) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-              const int j2 = row0 + (r >> 2) * 8 + (r & 3);
-              if (j2 < n_dst) top2_insert_any(best[b], v[r], j2);
+              if (hit[r] != 0) {   // insertions only raise the thresholds: the masks stay a superset
+                const int j2 = row0 + (r >> 2) * 8 + (r & 3);
+                if (j2 < n_dst) top2_insert_any(best[b], v[r], j2);
+              }
             }
           }
         }
