@@ -39,14 +39,17 @@ __global__ __launch_bounds__(256) void k_inv_norm(const uint16_t *__restrict__ x
 
 // Gather token rows into fragment-major order: fragment (tile t of 32 rows, k-step s of 16
 // channels) is 1 KB contiguous, lane (h*32 + r) holds row r, channels 16s+8h .. 16s+8h+7.
-// Rows beyond n are zero.  inv_out (optional) receives the rows' inverse norms, 0 beyond n.
+// Rows beyond n are zero.  inv_out (optional) receives the rows' inverse norms, 0 beyond n;
+// zero256 (optional) is a 256-word array to clear.
 __global__ __launch_bounds__(256) void k_pack_rows(const uint16_t *__restrict__ x,
                                                    const int32_t *__restrict__ idx_of,
                                                    const float *__restrict__ inv, int n, int n_pad,
                                                    int C, u32x4 *__restrict__ packed,
-                                                   float *__restrict__ inv_out) {
+                                                   float *__restrict__ inv_out,
+                                                   uint32_t *__restrict__ zero256) {
   const int nch = C >> 3, KS = C >> 4;
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (zero256 && idx < 256) zero256[idx] = 0u;   // the similarity kernel's team counters
   if (idx >= (int64_t)n_pad * nch) return;
   const int j = (int)(idx / nch), c = (int)(idx % nch);
   u32x4 w = {0u, 0u, 0u, 0u};
@@ -83,37 +86,47 @@ __device__ __forceinline__ void top2_insert_any(Top2 &t, float v, int i) {
 // the MFMA row dimension, so a lane owns one src column per 32-column block and folds every
 // finished tile into its running (best, second best) pair without cross-lane traffic.
 //
-// Workgroup (src tile st, lane dl) sweeps the dst tiles dl, dl + L, dl + 2L, ...; the L
-// partial results of a src row are merged by k_match_finish.  Workgroups are dealt to the
-// XCDs round-robin by the hardware; the block index is decoded so that the 32 workgroups an
-// XCD runs together are 8 src tiles x 4 lanes at the same sweep position, which share both
-// operands in that XCD's L2.
+// The kernel is persistent: one workgroup per CU.  The workgroups the hardware deals to one
+// XCD (block index mod 8) form a team of 8 src tiles x 4 sweeps; the team takes every 8th
+// super-row of 8 src tiles, and in it workgroup (src tile, sweep dl) visits the dst tiles dl,
+// dl + 4, dl + 8, ...  The team moves from one dst tile to the next together (a bounded,
+// advisory wait on a counter in the XCD's L2), so its 32 workgroups ask for the same 8 src
+// and 4 dst tiles within a few microseconds of each other and 4 of 5 requests hit that L2.
+// The four partial results of a src row are merged by k_match_finish.
 // ---------------------------------------------------------------------------------
 constexpr int kGTile = 256;          // src and dst rows per workgroup tile
 constexpr int kGStages = 4;          // LDS ring depth
 constexpr int kGStageU4 = 2 * 2 * 8 * 64;   // u32x4 per stage: [src|dst][2 k-steps][8 fragments][64 lanes]
+constexpr int kTeamSpin = 512;       // polls of the team counter before a workgroup goes on alone
 constexpr int kGLanes = 4;           // dst tiles are dealt to this many workgroups per src tile
 
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_match_sim(
     const u32x4 *__restrict__ srcp, const u32x4 *__restrict__ dstp, const float *__restrict__ invd,
     int n_dst, int n_src_tiles, int n_dst_tiles, int n_lanes, int KS, int n_src_pad,
-    Top2 *__restrict__ top2p) {
+    int team_size, int spin_budget, uint32_t *team_ctr, Top2 *__restrict__ top2p) {
   extern __shared__ u32x4 ring[];    // kGStages stages
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wd = wave & 3, wsrc = wave >> 2;
-  const int xcd = blockIdx.x & (kXcd - 1), q = blockIdx.x >> 3;
-  const int dl = q % n_lanes, st = (q / n_lanes) * kXcd + xcd;
-  if (st >= n_src_tiles) return;
+  const int team = blockIdx.x & (kXcd - 1), rank = blockIdx.x >> 3;
+  if (rank >= team_size) return;     // not a member of its team: nothing to do
+  const int dl = rank % n_lanes, sti = rank / n_lanes, sr_tiles = team_size / n_lanes;
+  const int n_super = (n_src_tiles + sr_tiles - 1) / sr_tiles;
+  const int nt_max = (n_dst_tiles + n_lanes - 1) / n_lanes;
   const int nt = dl < n_dst_tiles ? (n_dst_tiles - dl + n_lanes - 1) / n_lanes : 0;   // my dst tiles
   const int SPT = KS >> 1;           // stages per tile
   const int total = nt * SPT;
+  uint32_t *ctr = team_ctr + team * 32;      // one counter per team, 128 bytes apart
+  uint32_t rounds = 0;                       // sweep steps of the super-rows the team has finished
 
+  for (int sr = team; sr < n_super; sr += kXcd) {   // super-row: sr_tiles consecutive src tiles
+  const int st = sr * sr_tiles + sti;
+  const bool active = st < n_src_tiles && total > 0;
   Top2 best[4];
 #pragma unroll
   for (int b = 0; b < 4; ++b) best[b] = Top2{-INFINITY, -1, -INFINITY, -1};
 
-  if (total > 0) {
+  if (active) {
     // fetch: this wave moves fragments f = 4*wave .. 4*wave+3 of a stage (f = op*16 + ks*8 + a)
     const int f_op = wave >> 2, f_ks = (wave >> 1) & 1, f_a0 = (wave & 1) * 4;
     int pf_tile = dl, pf_s = 0, pf_g = 0;      // next stage to fetch: dst tile, stage in tile, flat index
@@ -208,7 +221,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     asm volatile("s_waitcnt vmcnt(12)" ::: "memory");          // stage 0 has landed (this wave's part)
     __builtin_amdgcn_s_barrier();
     read_frags(0, 0, fb[0], fa[0]);
-    int tile = dl, sidx = 0;
+    int tile = dl, sidx = 0, steps = 0;
     for (int g = 0; g < total; ++g) {
       // k-step 0 of stage g
       __builtin_amdgcn_sched_barrier(0);
@@ -227,31 +240,56 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       __builtin_amdgcn_sched_barrier(0);
       mma(fb[1], fa[1]);
       if (++sidx == SPT) {
+        // Team step: the workgroups of a team finish a dst tile at about the same time and
+        // start the next one together, so that what one of them fetches is still in their
+        // XCD's L2 when the others ask for it.  The wait is advisory: it is bounded, and no
+        // result depends on it.
+        if (tid == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         fold(tile);
         clear_acc();
         sidx = 0;
         tile += n_lanes;
+        ++steps;
+        if (tid == 0) {
+          const uint32_t target = (uint32_t)team_size * (rounds + (uint32_t)steps);
+          for (int spin = 0; spin < spin_budget; ++spin) {
+            if (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) break;
+            __builtin_amdgcn_s_sleep(8);
+          }
+        }
+        __builtin_amdgcn_s_barrier();
       }
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // nothing may land in LDS any more
   }
   __syncthreads();
-  // merge the two half-wave copies of a column and the four dst quarters (waves wd = 0..3)
-  Top2 *cand = (Top2 *)ring;
-#pragma unroll
-  for (int b = 0; b < 4; ++b) cand[(wave * 4 + b) * 64 + lane] = best[b];
-  __syncthreads();
-  if (tid < kGTile) {
-    const int ws2 = tid >> 7, b = (tid >> 5) & 3, c = tid & 31;
-    Top2 t = Top2{-INFINITY, -1, -INFINITY, -1};
-    for (int w = 0; w < 4; ++w)
-      for (int hh = 0; hh < 2; ++hh) {
-        const Top2 cd = cand[((ws2 * 4 + w) * 4 + b) * 64 + hh * 32 + c];
-        top2_insert_any(t, cd.v1, cd.i1);
-        top2_insert_any(t, cd.v2, cd.i2);
-      }
-    top2p[(size_t)dl * n_src_pad + (size_t)st * kGTile + tid] = t;
+  // sweep steps this workgroup did not take still count for its team
+  {
+    const uint32_t missing = (uint32_t)(nt_max - (active ? nt : 0));
+    if (tid == 0 && missing)
+      __hip_atomic_fetch_add(ctr, missing, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    rounds += (uint32_t)nt_max;
   }
+  if (st < n_src_tiles) {
+    // merge the two half-wave copies of a column and the four dst quarters (waves wd = 0..3)
+    Top2 *cand = (Top2 *)ring;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) cand[(wave * 4 + b) * 64 + lane] = best[b];
+    __syncthreads();
+    if (tid < kGTile) {
+      const int ws2 = tid >> 7, b = (tid >> 5) & 3, c = tid & 31;
+      Top2 t = Top2{-INFINITY, -1, -INFINITY, -1};
+      for (int w = 0; w < 4; ++w)
+        for (int hh = 0; hh < 2; ++hh) {
+          const Top2 cd = cand[((ws2 * 4 + w) * 4 + b) * 64 + hh * 32 + c];
+          top2_insert_any(t, cd.v1, cd.i1);
+          top2_insert_any(t, cd.v2, cd.i2);
+        }
+      top2p[(size_t)dl * n_src_pad + (size_t)st * kGTile + tid] = t;
+    }
+    __syncthreads();   // the ring is reused by the next super-row
+  }
+  }   // super-rows
 }
 
 // Final decision per src row (one wave each): merge the partial results of the sweeps; rows
@@ -424,7 +462,7 @@ struct MatchWs {
   Top2 *top2p;
   uint32_t *keys[2];
   int32_t *vals[2];
-  uint32_t *hist;
+  uint32_t *hist, *team_ctr;
   size_t bytes;
   int n_dst_pad, n_src_pad, n_lanes, nchunks;
 };
@@ -452,6 +490,7 @@ static MatchWs carve(const Dims &d, const litevggt_plan_t &pl, char *base) {
     w.vals[i] = (int32_t *)take((size_t)d.N * 4);
   }
   w.hist = (uint32_t *)take((size_t)256 * w.nchunks * 4);
+  w.team_ctr = (uint32_t *)take(256 * 4);
   w.bytes = off;
   return w;
 }
@@ -476,13 +515,23 @@ int launch_match(const uint16_t *x, const Dims &d, const litevggt_plan_t &pl,
     hipLaunchKernelGGL(k_inv_norm, dim3(rows_grid), dim3(256), 0, st, x, d.N, d.C, w.inv);
     const int64_t pkd = (int64_t)w.n_dst_pad * (d.C / 8), pks = (int64_t)w.n_src_pad * (d.C / 8);
     hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)((pkd + 255) / 256)), dim3(256), 0, st, x,
-                       ix.dst_idx, w.inv, n_dst, w.n_dst_pad, d.C, w.dstp, w.invd);
+                       ix.dst_idx, w.inv, n_dst, w.n_dst_pad, d.C, w.dstp, w.invd, w.team_ctr);
     hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)((pks + 255) / 256)), dim3(256), 0, st, x,
-                       ix.src_idx, w.inv, n_src, w.n_src_pad, d.C, w.srcp, (float *)nullptr);
+                       ix.src_idx, w.inv, n_src, w.n_src_pad, d.C, w.srcp, (float *)nullptr,
+                       (uint32_t *)nullptr);
+    // One workgroup per CU, all resident at once; the workgroups the hardware deals to one
+    // XCD (block index mod 8) form a team of (src tiles per super-row) x (sweeps).
     const int src_tiles = w.n_src_pad / kGTile, dst_tiles = w.n_dst_pad / kGTile;
-    const unsigned grid = (unsigned)(((src_tiles + kXcd - 1) / kXcd) * kXcd * w.n_lanes);
-    hipLaunchKernelGGL(k_match_sim, dim3(grid), dim3(512), lds, st, w.srcp, w.dstp, w.invd, n_dst,
-                       src_tiles, dst_tiles, w.n_lanes, d.C / 16, w.n_src_pad, w.top2p);
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      return LV_ERR_HIP;
+    int per_team = n_cu / kXcd;
+    if (per_team < w.n_lanes) per_team = w.n_lanes;
+    const int team_size = per_team / w.n_lanes * w.n_lanes;
+    hipLaunchKernelGGL(k_match_sim, dim3((unsigned)(per_team * kXcd)), dim3(512), lds, st, w.srcp,
+                       w.dstp, w.invd, n_dst, src_tiles, dst_tiles, w.n_lanes, d.C / 16, w.n_src_pad,
+                       team_size, kTeamSpin, w.team_ctr, w.top2p);
     const unsigned fin = (unsigned)(((n_src + 3) / 4) < 16384 ? ((n_src + 3) / 4) : 16384);
     hipLaunchKernelGGL(k_match_finish, dim3(fin), dim3(256), 0, st, x, ix.src_idx, ix.dst_idx,
                        w.inv, w.top2p, w.n_lanes, w.n_src_pad, n_src, d.C, ix.anchor_of, ix.slot_of,
