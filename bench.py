@@ -36,8 +36,10 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="f1000", help="f32 | f100 | f500 | f1000 | tiny2")
+    ap.add_argument("--workload", default="f1000", help="f32 | f100 | f500 | f1000 | tiny2 | paper1000")
     ap.add_argument("--merge-ratio", type=float, default=None)
+    ap.add_argument("--refresh-interval", type=int, default=None,
+                    help="layers between index refreshes (default: the workload's, 6)")
     ap.add_argument("--attn-dtype", default="bf16", choices=["bf16", "fp8"])
     ap.add_argument("--no-unmerged", action="store_true",
                     help="skip the one-launch unmerged attention baseline")
@@ -158,6 +160,8 @@ def main():
     lib = B.lib()
 
     over = {} if args.merge_ratio is None else dict(merge_ratio=args.merge_ratio)
+    if args.refresh_interval is not None:
+        over["refresh_interval"] = args.refresh_interval
     wl = synth.workload(args.workload, **over)
     attn_dtype = B.ATTN_BF16 if args.attn_dtype == "bf16" else B.ATTN_FP8_E4M3
     ph = B.make_params(wl.frames, wl.grid_h, wl.grid_w, wl.dim, wl.heads, n_special=wl.n_special,

@@ -87,6 +87,10 @@ WORKLOADS = {
                      merge_ratio=0.9, seed=4, motion="walk"),
     "f1000": Workload("f1000", frames=1000, grid_h=37, grid_w=37, dim=1024, heads=16,
                       merge_ratio=0.9, seed=5, motion="walk"),
+    # the paper's own shape: 392 x 518 images (28 x 37 patches), its fixed partition rule
+    # (merge_ratio < 0: top 10 % GA tokens, one dst per 2 x 2 cell)
+    "paper1000": Workload("paper1000", frames=1000, grid_h=28, grid_w=37, dim=1024, heads=16,
+                          merge_ratio=-1.0, seed=6, motion="walk"),
 }
 
 
