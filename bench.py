@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--refresh-interval", type=int, default=None,
                     help="layers between index refreshes (default: the workload's, 6)")
     ap.add_argument("--attn-dtype", default="bf16", choices=["bf16", "fp8"])
+    ap.add_argument("--anchor-policy", default="ga", choices=["ga", "fixed", "random"],
+                    help="what ranks the tokens: the GA map, or a geometry-blind partition")
     ap.add_argument("--no-unmerged", action="store_true",
                     help="skip the one-launch unmerged attention baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -166,7 +168,9 @@ def main():
     attn_dtype = B.ATTN_BF16 if args.attn_dtype == "bf16" else B.ATTN_FP8_E4M3
     ph = B.make_params(wl.frames, wl.grid_h, wl.grid_w, wl.dim, wl.heads, n_special=wl.n_special,
                        patch=wl.patch, merge_ratio=wl.merge_ratio,
-                       refresh_interval=wl.refresh_interval, qk_norm=1, attn_dtype=attn_dtype)
+                       refresh_interval=wl.refresh_interval, qk_norm=1, attn_dtype=attn_dtype,
+                       anchor_policy=dict(ga=B.POLICY_GA, fixed=B.POLICY_FIXED,
+                                          random=B.POLICY_RANDOM)[args.anchor_policy])
     wl_qk_norm = bool(ph.qk_norm)
     pl = B.litevggt_plan(ph)
     L, C_ = wl.layers, wl.dim
@@ -293,6 +297,7 @@ def main():
                                f"{wl.merge_ratio} (M={M}), {L} global layers, index refreshed "
                                f"every {wl.refresh_interval}",
                    "token_layers_per_s": L * N / (ms_step * 1e-3),
+                   "anchor_policy": args.anchor_policy,
                    "refresh_log": log, "output_finite": finite,
                    "peak_hbm_alloc_gib": torch.cuda.max_memory_allocated() / 2 ** 30,
                    "input_generation_s": gen_s,

@@ -43,6 +43,7 @@ enum {
 enum { LV_IMG_F32 = 0, LV_IMG_U8 = 1 };        /* image element type              */
 enum { LV_ATTN_BF16 = 0, LV_ATTN_FP8_E4M3 = 1 }; /* attention MFMA operand type   */
 enum { LV_ROLE_PROTECTED = 0, LV_ROLE_DST = 1, LV_ROLE_SRC = 2 };
+enum { LV_POLICY_GA = 0, LV_POLICY_FIXED = 1, LV_POLICY_RANDOM = 2 }; /* what ranks the tokens */
 
 /* Shape and hyper-parameters (host memory). */
 typedef struct {
@@ -65,6 +66,9 @@ typedef struct {
                               frame that become src; < 0 selects the paper's fixed
                               rule (top ga_frac GA tokens, one dst per 2x2 cell)   */
   double  ga_frac;         /* 0.10; used only when merge_ratio < 0                 */
+  int32_t anchor_policy;   /* LV_POLICY_GA, or one of the geometry-blind partitions
+                              of Sec. 3.2 (see litevggt_importance)                  */
+  uint32_t policy_seed;    /* seed of LV_POLICY_RANDOM                              */
 } litevggt_params;
 
 /* Token counts that follow from the parameters (closed form, Sec. 3.4 partition). */
@@ -105,6 +109,14 @@ size_t litevggt_attn_ws_bytes(const litevggt_params *p, int64_t n_tokens);
  * kernels, replicated border) averaged over each patch; Psi_v = variance of the
  * patch tokens over a var_pool x var_pool grid neighbourhood (clipped at the grid
  * border), averaged over channels; norm = per-frame min-max (a flat map -> 0).
+ * With anchor_policy != LV_POLICY_GA the score carries no geometry (Sec. 3.2 "Naive
+ * Token Merging": dst/src sets from a fixed pattern or from random sampling) and images,
+ * x, grad_cache are not read and may be NULL:
+ *   LV_POLICY_FIXED   score[f][p] = ((p+1) * 2654435769 mod 2^32) >> 8, / 2^24: the same
+ *                     low-discrepancy pattern in every frame
+ *   LV_POLICY_RANDOM  score[f][p] = fmix32(policy_seed ^ f*0x9E3779B9 ^ p*0x85EBCA6B) >> 8,
+ *                     / 2^24, fmix32 = the 32-bit finaliser of MurmurHash3
+ * The partition rule of litevggt_select_anchors is the same for every policy.
  *   images     [device] [F,3,grid_h*patch,grid_w*patch] img_dtype; may be NULL when
  *              recompute_grad == 0
  *   x          [device] [N,dim] bf16 tokens entering the layer
@@ -170,6 +182,8 @@ int litevggt_unmerge(const litevggt_params *p, const void *y, const litevggt_ind
  * l % refresh_interval == 0, then x <- x + unmerge(attn(merge(x))) with
  * Q = K = V = the merged tokens viewed as [M, heads, 64] (q, k normalised when qk_norm).
  *   x           [device] [N,dim] bf16, in/out
+ *   images      [device] as for litevggt_importance; with anchor_policy != LV_POLICY_GA
+ *               images and grad_cache are not read and may be NULL
  *   grad_cache, score [device] [F,P] fp32 scratch/outputs of the last refresh
  *   refresh_log [host] [n_layers] set to 1 where the index was recomputed, or NULL
  *   events      [host] NULL, or LV_EVENTS_PER_LAYER*n_layers hipEvent_t handles (as

@@ -46,6 +46,8 @@ class Params:
     beta: float = 0.5
     var_pool: int = 3           # window of the local average pooling (paper silent)
     refresh_interval: int = 6   # Sec. 3.4 "Cached Token Merging"
+    anchor_policy: int = 0      # 0: GA map (Sec. 3.4); 1, 2: the naive partitions of Sec. 3.2 (naive_score)
+    policy_seed: int = 0        # seed of the random policy
     qk_norm: bool = False       # layer loop: RMS-normalise q and k per head (see global_layer)
     attn_fp8: bool = False      # layer loop: FP8 E4M3 attention emulation (see attention_fp8)
 
@@ -173,9 +175,46 @@ def ga_map(psi_g: np.ndarray, psi_v: np.ndarray, p: Params) -> np.ndarray:
     return p.alpha * minmax_norm(psi_g) + p.beta * minmax_norm(psi_v)
 
 
+POLICY_GA, POLICY_FIXED, POLICY_RANDOM = 0, 1, 2
+
+
+def naive_score(p: Params) -> np.ndarray:
+    """Score map [F,P] of the geometry-blind partitions the paper argues against (Sec. 3.2
+    "Naive Token Merging": dst/src sets chosen by random sampling or by a fixed pattern, as in
+    generic token merging).  The partition rule itself (one dst per cell = lowest score, extra
+    kept tokens = highest scores) is unchanged; only the score carries no geometry:
+
+    * POLICY_FIXED: the same pattern in every frame, score(p) = frac((p+1) * golden ratio) taken
+      in 32-bit integer arithmetic (Knuth's multiplicative hash), a low-discrepancy sequence
+      over the token index, so the kept tokens are spread evenly over the grid;
+    * POLICY_RANDOM: an independent pseudo-random value per (frame, token): the 32-bit
+      finaliser of MurmurHash3 applied to seed ^ f*0x9E3779B9 ^ p*0x85EBCA6B.
+
+    Both keep the top 24 bits, so every score is exactly representable in float32."""
+    F, P = p.frames, p.patches
+    f = np.arange(F, dtype=np.uint64)[:, None]
+    t = np.arange(P, dtype=np.uint64)[None, :]
+    m32 = np.uint64(0xFFFFFFFF)
+    if p.anchor_policy == POLICY_FIXED:
+        h = np.broadcast_to(((t + np.uint64(1)) * np.uint64(2654435769)) & m32, (F, P))
+    elif p.anchor_policy == POLICY_RANDOM:
+        h = (np.uint64(p.policy_seed) & m32) ^ ((f * np.uint64(0x9E3779B9)) & m32) \
+            ^ ((t * np.uint64(0x85EBCA6B)) & m32)
+        h ^= h >> np.uint64(16)
+        h = (h * np.uint64(0x85EBCA6B)) & m32
+        h ^= h >> np.uint64(13)
+        h = (h * np.uint64(0xC2B2AE35)) & m32
+        h ^= h >> np.uint64(16)
+    else:
+        raise ValueError("naive_score needs POLICY_FIXED or POLICY_RANDOM")
+    return (h >> np.uint64(8)).astype(np.float64) / 16777216.0
+
+
 def importance(images: np.ndarray, x: np.ndarray, p: Params,
                psi_g: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
     """Score [F,P] (float64) and the gradient map it used (cacheable: images only)."""
+    if p.anchor_policy != POLICY_GA:
+        return naive_score(p), (psi_g if psi_g is not None else np.zeros((p.frames, p.grid_h, p.grid_w)))
     if psi_g is None:
         psi_g = grad_map(images, p.patch)
     score = ga_map(psi_g, var_map(x, p), p)

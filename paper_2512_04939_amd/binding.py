@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "liblitevggt.so")
 
 IMG_F32, IMG_U8 = 0, 1
 ATTN_BF16, ATTN_FP8_E4M3 = 0, 1
+POLICY_GA, POLICY_FIXED, POLICY_RANDOM = 0, 1, 2
 ROLE_PROTECTED, ROLE_DST, ROLE_SRC = 0, 1, 2
 
 EXPORTS = ["litevggt_strerror", "litevggt_plan", "litevggt_attn_ws_bytes", "litevggt_importance",
@@ -35,7 +36,7 @@ class Params(C.Structure):
                 ("var_pool", C.c_int32), ("refresh_interval", C.c_int32),
                 ("attn_dtype", C.c_int32), ("qk_norm", C.c_int32), ("alpha", C.c_float), ("beta", C.c_float),
                 ("softmax_scale", C.c_float), ("merge_ratio", C.c_double),
-                ("ga_frac", C.c_double)]
+                ("ga_frac", C.c_double), ("anchor_policy", C.c_int32), ("policy_seed", C.c_uint32)]
 
 
 class Plan(C.Structure):
@@ -55,10 +56,11 @@ class Index(C.Structure):
 
 def make_params(frames, grid_h, grid_w, dim, heads, *, head_dim=64, n_special=5, patch=14,
                 img_dtype=IMG_F32, var_pool=3, refresh_interval=6, attn_dtype=ATTN_BF16,
-                qk_norm=0, alpha=0.5, beta=0.5, softmax_scale=0.0, merge_ratio=0.9, ga_frac=0.10) -> Params:
+                qk_norm=0, alpha=0.5, beta=0.5, softmax_scale=0.0, merge_ratio=0.9, ga_frac=0.10,
+                anchor_policy=POLICY_GA, policy_seed=0) -> Params:
     return Params(frames, grid_h, grid_w, n_special, dim, heads, head_dim, patch, img_dtype,
                   var_pool, refresh_interval, attn_dtype, qk_norm, alpha, beta, softmax_scale,
-                  merge_ratio, ga_frac)
+                  merge_ratio, ga_frac, anchor_policy, policy_seed)
 
 
 _lib = None

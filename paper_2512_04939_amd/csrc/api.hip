@@ -19,6 +19,7 @@ int check_params(const litevggt_params *p, Dims *d) {
   if (p->attn_dtype != LV_ATTN_BF16 && p->attn_dtype != LV_ATTN_FP8_E4M3) return LV_ERR_DTYPE;
   if (p->var_pool != 1 && p->var_pool != 3 && p->var_pool != 5) return LV_ERR_PARAM;
   if (p->refresh_interval < 1) return LV_ERR_PARAM;
+  if (p->anchor_policy < LV_POLICY_GA || p->anchor_policy > LV_POLICY_RANDOM) return LV_ERR_PARAM;
   if (!(p->merge_ratio < 1.0)) return LV_ERR_PARAM;            // also rejects NaN
   if (p->merge_ratio < 0 && !(p->ga_frac >= 0.0 && p->ga_frac <= 1.0)) return LV_ERR_PARAM;
   if (!isfinite(p->alpha) || !isfinite(p->beta) || !isfinite(p->softmax_scale)) return LV_ERR_PARAM;
@@ -143,9 +144,13 @@ int litevggt_importance(const litevggt_params *p, const void *images, const void
   Dims d;
   int rc = check_params(p, &d);
   if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  if (p->anchor_policy != LV_POLICY_GA) {
+    if (!score) return LV_ERR_NULL;
+    return launch_naive_score(d, p->anchor_policy, p->policy_seed, score, st);
+  }
   if (!x || !grad_cache || !score || (recompute_grad && !images)) return LV_ERR_NULL;
   if (!ws_ok(ws, ws_bytes, importance_ws_bytes(d))) return LV_ERR_WORKSPACE;
-  hipStream_t st = (hipStream_t)stream;
   float *psi_v = (float *)ws;
   if (recompute_grad) {
     rc = launch_grad_map(images, p->img_dtype, d, p->patch, grad_cache, st);
@@ -227,7 +232,8 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
   rc = make_plan(p, d, &pl);
   if (rc) return rc;
   if (n_layers < 0) return LV_ERR_PARAM;
-  if (!images || !x || !grad_cache || !score || !index_ok(index)) return LV_ERR_NULL;
+  const bool ga = p->anchor_policy == LV_POLICY_GA;   // the other policies read no image, cache no map
+  if (!x || !score || !index_ok(index) || (ga && (!images || !grad_cache))) return LV_ERR_NULL;
   if (d.C > 1024) return LV_ERR_SHAPE;
   if (!ws_ok(ws, ws_bytes, driver_ws_bytes(p, d, pl))) return LV_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
@@ -245,7 +251,7 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
       return LV_OK;
     };
     if ((rc = mark(LV_EV_LAYER_BEGIN))) return rc;
-    if (refresh) {
+    if (refresh && ga) {
       if (l == 0) {
         rc = launch_grad_map(images, p->img_dtype, d, p->patch, grad_cache, st);
         if (rc) return rc;
@@ -253,6 +259,9 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
       rc = launch_var_map(xx, d, p->var_pool, (float *)op_ws, st);
       if (rc) return rc;
       rc = launch_ga_fuse(grad_cache, (const float *)op_ws, d, p->alpha, p->beta, score, st);
+      if (rc) return rc;
+    } else if (refresh) {
+      rc = launch_naive_score(d, p->anchor_policy, p->policy_seed, score, st);
       if (rc) return rc;
     }
     if ((rc = mark(LV_EV_IMPORTANCE_END))) return rc;

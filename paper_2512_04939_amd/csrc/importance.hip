@@ -205,4 +205,34 @@ int launch_ga_fuse(const float *psi_g, const float *psi_v, const Dims &d, float 
   return LV_OK;
 }
 
+// Scores of the geometry-blind partitions (Sec. 3.2 "Naive Token Merging"): a fixed
+// low-discrepancy pattern over the token index, or an independent hash per (frame, token).
+// 24-bit values, exact in fp32.
+__global__ __launch_bounds__(256) void k_naive_score(int F, int P, int policy, uint32_t seed,
+                                                     float *__restrict__ score) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)F * P) return;
+  const uint32_t f = (uint32_t)(idx / P), t = (uint32_t)(idx % P);
+  uint32_t hsh;
+  if (policy == LV_POLICY_FIXED) {
+    hsh = (t + 1u) * 2654435769u;                 // multiplicative hash by 2^32 / golden ratio
+  } else {
+    hsh = seed ^ (f * 0x9E3779B9u) ^ (t * 0x85EBCA6Bu);
+    hsh ^= hsh >> 16;                             // 32-bit finaliser of MurmurHash3
+    hsh *= 0x85EBCA6Bu;
+    hsh ^= hsh >> 13;
+    hsh *= 0xC2B2AE35u;
+    hsh ^= hsh >> 16;
+  }
+  score[idx] = (float)(hsh >> 8) * (1.0f / 16777216.0f);
+}
+
+int launch_naive_score(const Dims &d, int policy, uint32_t seed, float *score, hipStream_t st) {
+  const int64_t n = (int64_t)d.F * d.P;
+  hipLaunchKernelGGL(k_naive_score, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d.F, d.P,
+                     policy, seed, score);
+  LV_HIP_CHECK_LAUNCH();
+  return LV_OK;
+}
+
 }  // namespace lv

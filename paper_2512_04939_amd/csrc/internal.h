@@ -19,6 +19,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // importance.hip
 int launch_grad_map(const void *images, int img_dtype, const Dims &d, int patch, float *psi_g,
                     hipStream_t st);
+int launch_naive_score(const Dims &d, int policy, uint32_t seed, float *score, hipStream_t st);
 int launch_var_map(const uint16_t *x, const Dims &d, int pool, float *psi_v, hipStream_t st);
 int launch_ga_fuse(const float *psi_g, const float *psi_v, const Dims &d, float alpha, float beta,
                    float *score, hipStream_t st);

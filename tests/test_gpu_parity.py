@@ -458,6 +458,39 @@ def test_layers_run_fp8_attention(B):
     assert max_rel_err(got, emu) <= 2e-2
 
 
+# ------------------------------------------------------------- geometry-blind anchor policies
+@pytest.mark.parametrize("policy", ["fixed", "random"])
+def test_naive_anchor_policies(B, policy):
+    """Sec. 3.2: the score map of the fixed-pattern / random partitions is bit-exact, the
+    partition that follows is the oracle's, and a layer of the driver agrees with the oracle
+    (no image, no gradient cache needed)."""
+    import torch
+    wl = small_workload(frames=3, grid=37, dim=256, heads=4, r=0.9, seed=11)
+    pol = dict(fixed=(O.POLICY_FIXED, B.POLICY_FIXED), random=(O.POLICY_RANDOM, B.POLICY_RANDOM))[policy]
+    po = oracle_params(wl, anchor_policy=pol[0], policy_seed=77)
+    ph = hip_params(wl, anchor_policy=pol[1], policy_seed=77)
+    pl = B.litevggt_plan(ph)
+    bits, xf, im = stored_inputs(wl)
+    want = O.naive_score(po)
+    score = torch.full((wl.frames, wl.patches), -1.0, device="cuda")
+    B.litevggt_importance(ph, None, None, None, False, score, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(score.cpu().numpy().astype(np.float64), want)
+    ref = O.select_anchors(want.astype(np.float32), po)
+    ib = B.alloc_index(pl)
+    B.litevggt_select_anchors(ph, score, ib)
+    torch.cuda.synchronize()
+    assert np.array_equal(ib.role.cpu().numpy(), ref["role"])
+    assert np.array_equal(_i32(ib.dst_idx)[:pl.n_dst], ref["dst_idx"])
+    # one layer of the driver
+    x_dev = to_dev_bf16(bits)
+    log = B.litevggt_layers_run(ph, 1, None, x_dev, ib, None, score, B.alloc_ws(pl.ws_bytes))
+    torch.cuda.synchronize()
+    assert log == [1]
+    exp, _ = O.layers_run(None, xf, po, 1, store=_store_bf16)
+    assert max_rel_err(dev_bf16_to_f64(x_dev), exp) <= BF16_TOL
+
+
 # ------------------------------------------------------------------------- the layer driver
 @pytest.mark.parametrize("name,layers,interval", [("tiny2", 2, 6), ("tiny2", 4, 2),
                                                    ("small_r09", 3, 2), ("tiny2", 24, 6)])

@@ -226,3 +226,65 @@ def test_build_index_structure():
         assert np.all(idx["slot_of"][mem] == mm)
     prot = np.flatnonzero(sel["role"] == O.ROLE_PROTECTED)
     assert np.all(sizes[idx["slot_of"][prot]] == 1)                 # never a merge target
+
+
+# ---------------------------------------------------------------------------
+# geometry-blind score maps (Sec. 3.2 "Naive Token Merging")
+# ---------------------------------------------------------------------------
+def _fmix32(h):
+    h ^= h >> 16
+    h = (h * 0x85EBCA6B) & 0xFFFFFFFF
+    h ^= h >> 13
+    h = (h * 0xC2B2AE35) & 0xFFFFFFFF
+    h ^= h >> 16
+    return h
+
+
+def test_naive_score_fixed_pattern_is_the_golden_ratio_sequence():
+    p = O.Params(frames=3, grid_h=16, grid_w=16, anchor_policy=O.POLICY_FIXED)
+    s = O.naive_score(p)
+    assert s.shape == (3, 256) and (s[0] == s[1]).all() and (s[0] == s[2]).all()
+    # frac((p+1)/phi) up to the 2^-24 truncation: 2654435769 = round(2^32 / phi)
+    phi = (1 + 5 ** 0.5) / 2
+    want = np.modf((np.arange(256) + 1) / phi)[0]
+    assert np.abs(s[0] - want).max() < 1e-6
+    assert len(np.unique(s[0])) == 256                       # no ties inside a frame
+    assert (s >= 0).all() and (s < 1).all()
+    assert (s.astype(np.float32).astype(np.float64) == s).all()   # exact in float32
+    # low discrepancy: every run of 8 consecutive tokens has a value in each quarter of [0,1)
+    q = (s[0] * 4).astype(int)
+    assert all(len(set(q[i:i + 8])) == 4 for i in range(0, 248))
+
+
+def test_naive_score_random_matches_a_scalar_murmur_finaliser():
+    p = O.Params(frames=5, grid_h=7, grid_w=9, anchor_policy=O.POLICY_RANDOM, policy_seed=1234)
+    s = O.naive_score(p)
+    for f in range(5):
+        for t in range(63):
+            h = _fmix32((1234 ^ ((f * 0x9E3779B9) & 0xFFFFFFFF) ^ ((t * 0x85EBCA6B) & 0xFFFFFFFF)))
+            assert s[f, t] == (h >> 8) / 2 ** 24
+    big = O.naive_score(O.Params(frames=64, grid_h=37, grid_w=37, anchor_policy=O.POLICY_RANDOM))
+    assert abs(big.mean() - 0.5) < 5e-3 and abs(big.var() - 1 / 12) < 2e-3
+    assert abs(np.corrcoef(big[:-1].ravel(), big[1:].ravel())[0, 1]) < 0.02   # frames independent
+    other = O.naive_score(O.Params(frames=64, grid_h=37, grid_w=37, anchor_policy=O.POLICY_RANDOM,
+                                   policy_seed=1))
+    assert (other != big).mean() > 0.99
+
+
+@pytest.mark.parametrize("policy", [O.POLICY_FIXED, O.POLICY_RANDOM])
+def test_naive_policies_keep_the_partition_rule(policy):
+    p = O.Params(frames=4, grid_h=16, grid_w=16, dim=64, heads=1, merge_ratio=0.5,
+                 anchor_policy=policy, policy_seed=9)
+    score, _ = O.importance(None, None, p)
+    sel = O.select_anchors(score.astype(np.float32), p)
+    pl = O.plan(p)
+    role = sel["role"].reshape(p.frames, p.tokens_per_frame)
+    assert (role[:, :5] == O.ROLE_PROTECTED).all() and (role[0, 5:] == O.ROLE_DST).all()
+    for f in range(1, p.frames):
+        r = role[f, 5:]
+        assert (r == O.ROLE_DST).sum() == pl["n_dst_per_frame"]
+        assert (r == O.ROLE_SRC).sum() == pl["n_src_per_frame"]
+    if policy == O.POLICY_FIXED:                    # same pattern in every non-first frame
+        assert (role[1] == role[2]).all() and (role[2] == role[3]).all()
+    else:
+        assert (role[1] != role[2]).any()
