@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--attn-dtype", default="bf16", choices=["bf16", "fp8"])
     ap.add_argument("--anchor-policy", default="ga", choices=["ga", "fixed", "random"],
                     help="what ranks the tokens: the GA map, or a geometry-blind partition")
+    ap.add_argument("--frame-attn", action="store_true",
+                    help="run a frame attention after every global layer (not part of the metric's default)")
     ap.add_argument("--no-unmerged", action="store_true",
                     help="skip the one-launch unmerged attention baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -170,7 +172,8 @@ def main():
                        patch=wl.patch, merge_ratio=wl.merge_ratio,
                        refresh_interval=wl.refresh_interval, qk_norm=1, attn_dtype=attn_dtype,
                        anchor_policy=dict(ga=B.POLICY_GA, fixed=B.POLICY_FIXED,
-                                          random=B.POLICY_RANDOM)[args.anchor_policy])
+                                          random=B.POLICY_RANDOM)[args.anchor_policy],
+                       frame_attn=1 if args.frame_attn else 0)
     wl_qk_norm = bool(ph.qk_norm)
     pl = B.litevggt_plan(ph)
     L, C_ = wl.layers, wl.dim
@@ -234,7 +237,8 @@ def main():
              "merge": (B.EV_MATCH_END, B.EV_MERGE_END),
              "attn_pack": (B.EV_MERGE_END, B.EV_ATTN_PACK_END),
              "attn": (B.EV_ATTN_PACK_END, B.EV_ATTN_END),
-             "unmerge": (B.EV_ATTN_END, B.EV_UNMERGE_END)}
+             "unmerge": (B.EV_ATTN_END, B.EV_UNMERGE_END),
+             "frame_attn": (B.EV_UNMERGE_END, B.EV_FRAME_ATTN_END)}
     dur = {k: [] for k in names}
     for ev in evs:
         for l in range(L):
@@ -263,6 +267,10 @@ def main():
         "importance": dict(ms=avg["importance"]),
         "select": dict(ms=avg["select"]),
     }
+    if args.frame_attn:
+        fa_flop = 4.0 * wl.frames * wl.tokens_per_frame ** 2 * C_
+        ops["frame_attn"] = dict(ms=avg["frame_attn"], tflops=fa_flop / (avg["frame_attn"] * 1e-3) / 1e12,
+                                 note="pack + kernel, F independent sequences of P + 5 tokens")
     ops["match"]["frac_mfma"] = ops["match"]["tflops"] / PEAK_BF16_MFMA_TFLOPS
     ops["merge"]["frac_hbm"] = ops["merge"]["gbs"] / PEAK_HBM_GBS
     ops["unmerge"]["frac_hbm"] = ops["unmerge"]["gbs"] / PEAK_HBM_GBS
@@ -297,7 +305,7 @@ def main():
                                f"{wl.merge_ratio} (M={M}), {L} global layers, index refreshed "
                                f"every {wl.refresh_interval}",
                    "token_layers_per_s": L * N / (ms_step * 1e-3),
-                   "anchor_policy": args.anchor_policy,
+                   "anchor_policy": args.anchor_policy, "frame_attn": bool(args.frame_attn),
                    "refresh_log": log, "output_finite": finite,
                    "peak_hbm_alloc_gib": torch.cuda.max_memory_allocated() / 2 ** 30,
                    "input_generation_s": gen_s,

@@ -69,6 +69,8 @@ typedef struct {
   int32_t anchor_policy;   /* LV_POLICY_GA, or one of the geometry-blind partitions
                               of Sec. 3.2 (see litevggt_importance)                  */
   uint32_t policy_seed;    /* seed of LV_POLICY_RANDOM                              */
+  int32_t frame_attn;      /* != 0: the layer driver runs a frame attention after every
+                              global layer (see litevggt_frame_attn)                */
 } litevggt_params;
 
 /* Token counts that follow from the parameters (closed form, Sec. 3.4 partition). */
@@ -177,10 +179,28 @@ int litevggt_global_attn(const litevggt_params *p, int64_t n_tokens, const void 
 int litevggt_unmerge(const litevggt_params *p, const void *y, const litevggt_index *index,
                      const void *residual, void *out, void *stream);
 
+/* Frame attention, Sec. 3.1 (VGGT alternates frame-wise and global self-attention; Sec. 3.4
+ * "Token Unmerging": the unmerged tokens go to the next frame attention): for every frame f
+ * separately, O_f = softmax(Q_f K_f^T * softmax_scale) V_f over that frame's own P + n_special
+ * tokens, all heads; q and k RMS-normalised per head first when qk_norm is set.  Always
+ * computed with bf16 MFMAs (attn_dtype is ignored).
+ *   q, k, v   [device] [N,dim] bf16
+ *   residual  [device] [N,dim] bf16 or NULL; when given, o = residual + O with one rounding.
+ *             residual may be the same buffer as o (and as q, k, v): K and V are re-laid out
+ *             into ws before any output is written and every query row is read by the
+ *             workgroup that writes it.
+ *   o         [device] [N,dim] bf16 out
+ *   ws        litevggt_frame_attn_ws_bytes(p) bytes
+ */
+size_t litevggt_frame_attn_ws_bytes(const litevggt_params *p);
+int litevggt_frame_attn(const litevggt_params *p, const void *q, const void *k, const void *v,
+                        const void *residual, void *o, void *ws, size_t ws_bytes, void *stream);
+
 /* Cached-index layer driver, Sec. 3.4: for layer l = 0..n_layers-1, recompute the
  * merge index (steps 1-3; the gradient map only at l = 0) when
  * l % refresh_interval == 0, then x <- x + unmerge(attn(merge(x))) with
- * Q = K = V = the merged tokens viewed as [M, heads, 64] (q, k normalised when qk_norm).
+ * Q = K = V = the merged tokens viewed as [M, heads, 64] (q, k normalised when qk_norm),
+ * then, when frame_attn is set, x <- x + frame_attn(x) with Q = K = V = x.
  *   x           [device] [N,dim] bf16, in/out
  *   images      [device] as for litevggt_importance; with anchor_policy != LV_POLICY_GA
  *               images and grad_cache are not read and may be NULL
@@ -200,7 +220,8 @@ enum {
   LV_EV_MERGE_END,         /* after merge, before the K/V re-layout of attention   */
   LV_EV_ATTN_PACK_END,     /* after the re-layout, before the attention kernel     */
   LV_EV_ATTN_END,          /* after the attention kernel, before unmerge           */
-  LV_EV_UNMERGE_END,       /* after unmerge                                        */
+  LV_EV_UNMERGE_END,       /* after unmerge, before the frame attention (if any)   */
+  LV_EV_FRAME_ATTN_END,    /* after the frame attention                            */
   LV_EVENTS_PER_LAYER
 };
 int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *images,

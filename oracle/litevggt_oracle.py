@@ -48,6 +48,7 @@ class Params:
     refresh_interval: int = 6   # Sec. 3.4 "Cached Token Merging"
     anchor_policy: int = 0      # 0: GA map (Sec. 3.4); 1, 2: the naive partitions of Sec. 3.2 (naive_score)
     policy_seed: int = 0        # seed of the random policy
+    frame_attn: bool = False    # layer loop: a frame attention after every global layer (frame_layer)
     qk_norm: bool = False       # layer loop: RMS-normalise q and k per head (see global_layer)
     attn_fp8: bool = False      # layer loop: FP8 E4M3 attention emulation (see attention_fp8)
 
@@ -475,10 +476,32 @@ def global_layer(x: np.ndarray, idx: Dict[str, np.ndarray], p: Params,
     return store(unmerge(y, idx["slot_of"], residual=x))
 
 
+def frame_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, p: Params,
+                    scale: Optional[float] = None) -> np.ndarray:
+    """Frame-wise self-attention (Sec. 3.1: VGGT alternates frame-wise and global attention):
+    q, k, v [N, heads, head_dim]; every frame attends over its own P + n_special tokens only."""
+    T = p.tokens_per_frame
+    out = np.empty(np.shape(q), dtype=np.float64)
+    for f in range(p.frames):
+        r = slice(f * T, (f + 1) * T)
+        out[r] = attention(q[r], k[r], v[r], scale)
+    return out
+
+
+def frame_layer(x: np.ndarray, p: Params, store=lambda a: a) -> np.ndarray:
+    """x + FrameAttn(x) with Q = K = V = the tokens viewed as [N, heads, head_dim] (Q, K
+    normalised and stored when p.qk_norm); the sum is stored once (Sec. 3.4 "Token Unmerging":
+    the unmerged tokens go to the next frame attention)."""
+    xx = np.asarray(x, dtype=np.float64).reshape(x.shape[0], p.heads, p.head_dim)
+    qk = store(qk_normalize(xx)) if p.qk_norm else xx
+    return store(x + frame_attention(qk, qk, xx, p).reshape(x.shape))
+
+
 def layers_run(images: np.ndarray, x: np.ndarray, p: Params, n_layers: int,
                store=lambda a: a, trace: Optional[list] = None):
-    """Run n_layers merged global layers, recomputing the merge index when
-    layer % refresh_interval == 0 (the gradient map only once)."""
+    """Run n_layers merged global layers (each followed by a frame attention when
+    p.frame_attn), recomputing the merge index when layer % refresh_interval == 0 (the
+    gradient map only once)."""
     x = np.asarray(x, dtype=np.float64)
     psi_g, idx = None, None
     log = refresh_schedule(n_layers, p.refresh_interval)
@@ -488,4 +511,6 @@ def layers_run(images: np.ndarray, x: np.ndarray, p: Params, n_layers: int,
         if trace is not None:
             trace.append(dict(layer=l, x_in=x, index=idx))
         x = global_layer(x, idx, p, store)
+        if p.frame_attn:
+            x = frame_layer(x, p, store)
     return x, log

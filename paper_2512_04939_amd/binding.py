@@ -21,7 +21,8 @@ ROLE_PROTECTED, ROLE_DST, ROLE_SRC = 0, 1, 2
 
 EXPORTS = ["litevggt_strerror", "litevggt_plan", "litevggt_attn_ws_bytes", "litevggt_importance",
            "litevggt_select_anchors", "litevggt_match", "litevggt_merge", "litevggt_global_attn",
-           "litevggt_unmerge", "litevggt_layers_run"]
+           "litevggt_unmerge", "litevggt_frame_attn_ws_bytes", "litevggt_frame_attn",
+           "litevggt_layers_run"]
 
 
 class LiteVGGTError(RuntimeError):
@@ -36,7 +37,8 @@ class Params(C.Structure):
                 ("var_pool", C.c_int32), ("refresh_interval", C.c_int32),
                 ("attn_dtype", C.c_int32), ("qk_norm", C.c_int32), ("alpha", C.c_float), ("beta", C.c_float),
                 ("softmax_scale", C.c_float), ("merge_ratio", C.c_double),
-                ("ga_frac", C.c_double), ("anchor_policy", C.c_int32), ("policy_seed", C.c_uint32)]
+                ("ga_frac", C.c_double), ("anchor_policy", C.c_int32), ("policy_seed", C.c_uint32),
+                ("frame_attn", C.c_int32)]
 
 
 class Plan(C.Structure):
@@ -57,10 +59,10 @@ class Index(C.Structure):
 def make_params(frames, grid_h, grid_w, dim, heads, *, head_dim=64, n_special=5, patch=14,
                 img_dtype=IMG_F32, var_pool=3, refresh_interval=6, attn_dtype=ATTN_BF16,
                 qk_norm=0, alpha=0.5, beta=0.5, softmax_scale=0.0, merge_ratio=0.9, ga_frac=0.10,
-                anchor_policy=POLICY_GA, policy_seed=0) -> Params:
+                anchor_policy=POLICY_GA, policy_seed=0, frame_attn=0) -> Params:
     return Params(frames, grid_h, grid_w, n_special, dim, heads, head_dim, patch, img_dtype,
                   var_pool, refresh_interval, attn_dtype, qk_norm, alpha, beta, softmax_scale,
-                  merge_ratio, ga_frac, anchor_policy, policy_seed)
+                  merge_ratio, ga_frac, anchor_policy, policy_seed, frame_attn)
 
 
 _lib = None
@@ -87,10 +89,13 @@ def lib() -> C.CDLL:
         L.litevggt_merge.argtypes = [PP, vp, C.POINTER(Index), vp, vp]
         L.litevggt_global_attn.argtypes = [PP, i64, vp, vp, vp, vp, vp, sz, vp]
         L.litevggt_unmerge.argtypes = [PP, vp, C.POINTER(Index), vp, vp, vp]
+        L.litevggt_frame_attn_ws_bytes.restype = sz
+        L.litevggt_frame_attn_ws_bytes.argtypes = [PP]
+        L.litevggt_frame_attn.argtypes = [PP, vp, vp, vp, vp, vp, vp, sz, vp]
         L.litevggt_layers_run.argtypes = [PP, i32, vp, vp, C.POINTER(Index), vp, vp,
                                           C.POINTER(C.c_int32), C.POINTER(C.c_void_p), vp, sz, vp]
         for name in EXPORTS[1:]:
-            if name != "litevggt_attn_ws_bytes":
+            if name not in ("litevggt_attn_ws_bytes", "litevggt_frame_attn_ws_bytes"):
                 getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -205,9 +210,19 @@ def litevggt_unmerge(p: Params, y, index: IndexBuffers, residual, out) -> None:
                                   _stream()), "litevggt_unmerge")
 
 
-EVENTS_PER_LAYER = 8
+def litevggt_frame_attn_ws_bytes(p: Params) -> int:
+    return int(lib().litevggt_frame_attn_ws_bytes(C.byref(p)))
+
+
+def litevggt_frame_attn(p: Params, q, k, v, residual, o, ws) -> None:
+    wp, wn = _ws_args(ws)
+    _check(lib().litevggt_frame_attn(C.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(residual), _ptr(o),
+                                     wp, wn, _stream()), "litevggt_frame_attn")
+
+
+EVENTS_PER_LAYER = 9
 (EV_LAYER_BEGIN, EV_IMPORTANCE_END, EV_SELECT_END, EV_MATCH_END, EV_MERGE_END, EV_ATTN_PACK_END,
- EV_ATTN_END, EV_UNMERGE_END) = range(EVENTS_PER_LAYER)
+ EV_ATTN_END, EV_UNMERGE_END, EV_FRAME_ATTN_END) = range(EVENTS_PER_LAYER)
 
 
 def litevggt_layers_run(p: Params, n_layers: int, images, x, index: IndexBuffers, grad_cache,

@@ -87,6 +87,10 @@ size_t driver_ws_bytes(const litevggt_params *p, const Dims &d, const litevggt_p
   if (m > op) op = m;
   size_t a = attn_ws_bytes(d.heads, pl.M, p->attn_dtype);
   if (a > op) op = a;
+  if (p->frame_attn) {
+    a = attn_ws_bytes(d.heads, d.T, LV_ATTN_BF16, d.F);
+    if (a > op) op = a;
+  }
   return zy + op;
 }
 
@@ -211,6 +215,24 @@ int litevggt_global_attn(const litevggt_params *p, int64_t n_tokens, const void 
                      n_tokens, d.heads, scale_of(p), p->attn_dtype, p->qk_norm, ws, (hipStream_t)stream);
 }
 
+size_t litevggt_frame_attn_ws_bytes(const litevggt_params *p) {
+  Dims d;
+  if (check_params(p, &d)) return 0;
+  return attn_ws_bytes(d.heads, d.T, LV_ATTN_BF16, d.F);
+}
+
+int litevggt_frame_attn(const litevggt_params *p, const void *q, const void *k, const void *v,
+                        const void *residual, void *o, void *ws, size_t ws_bytes, void *stream) {
+  Dims d;
+  int rc = check_params(p, &d);
+  if (rc) return rc;
+  if (!q || !k || !v || !o) return LV_ERR_NULL;
+  if (!ws_ok(ws, ws_bytes, attn_ws_bytes(d.heads, d.T, LV_ATTN_BF16, d.F))) return LV_ERR_WORKSPACE;
+  return launch_attn((const uint16_t *)q, (const uint16_t *)k, (const uint16_t *)v, (uint16_t *)o,
+                     d.T, d.heads, scale_of(p), LV_ATTN_BF16, p->qk_norm, ws, (hipStream_t)stream,
+                     nullptr, d.F, (const uint16_t *)residual);
+}
+
 int litevggt_unmerge(const litevggt_params *p, const void *y, const litevggt_index *index,
                      const void *residual, void *out, void *stream) {
   Dims d;
@@ -285,6 +307,12 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
     rc = launch_unmerge(y, d, *index, xx, xx, st);
     if (rc) return rc;
     if ((rc = mark(LV_EV_UNMERGE_END))) return rc;
+    if (p->frame_attn) {
+      rc = launch_attn(xx, xx, xx, xx, d.T, d.heads, scale_of(p), LV_ATTN_BF16, p->qk_norm, op_ws,
+                       st, nullptr, d.F, xx);
+      if (rc) return rc;
+    }
+    if ((rc = mark(LV_EV_FRAME_ATTN_END))) return rc;
   }
   return LV_OK;
 }

@@ -52,14 +52,19 @@ __device__ __forceinline__ u32x4 rms_scale8(const u32x4 w, int log2_lanes) {
 // V -> [head][key tile][u][dt][lane]    : lane (h*32+dr) holds, for e = 0..7,
 //      V[tile*32 + 16u + 8(e/4) + 4h + e%4][32dt + dr]   (the key order in which a lane of
 //      the S^T accumulator holds its rows, so P needs no shuffle before the second MFMA)
+// With several sequences of n tokens each in one call (frame attention: one per frame) the
+// second grid dimension runs over (sequence, head) pairs and so do the packed arrays.
 __global__ __launch_bounds__(256) void k_attn_pack(const uint16_t *__restrict__ k,
                                                    const uint16_t *__restrict__ v, int64_t n,
                                                    int heads, int n_kt, int qk_norm,
                                                    u32x4 *__restrict__ kp,
                                                    u32x4 *__restrict__ vp) {
   __shared__ __attribute__((aligned(16))) uint16_t vt[kKT][72];
-  const int kt = blockIdx.x, head = blockIdx.y, t = threadIdx.x;
+  const int kt = blockIdx.x, t = threadIdx.x;
+  const int seq = blockIdx.y / heads, head = blockIdx.y - seq * heads;
   const int C = heads * 64;
+  k += (size_t)seq * n * C;
+  v += (size_t)seq * n * C;
   const int key = t >> 3, chunk = t & 7;
   const int64_t row = (int64_t)kt * kKT + key;
   u32x4 wk = {0u, 0u, 0u, 0u}, wv = {0u, 0u, 0u, 0u};
@@ -68,7 +73,7 @@ __global__ __launch_bounds__(256) void k_attn_pack(const uint16_t *__restrict__ 
     wv = *(const u32x4 *)(v + (size_t)row * C + head * 64 + chunk * 8);
   }
   if (qk_norm) wk = rms_scale8(wk, 3);   // the 8 lanes that share a key hold its 64 values
-  const size_t tile = ((size_t)head * n_kt + kt) * 4 * kFragU4;
+  const size_t tile = ((size_t)blockIdx.y * n_kt + kt) * 4 * kFragU4;
   kp[tile + (chunk >> 1) * kFragU4 + (chunk & 1) * 32 + key] = wk;
   *(u32x4 *)&vt[key][chunk * 8] = wv;
   __syncthreads();
@@ -94,23 +99,28 @@ constexpr int kVSlots = 3;           // LDS ring slots of 64-key V tiles
 // phase boundary, so on every SIMD one wave feeds the matrix pipe while the other feeds the
 // VALU -- deterministically, not by luck of the wave scheduler.
 __global__ __launch_bounds__(512) void k_attn_bf16(
-    const uint16_t *__restrict__ q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp,
-    uint16_t *__restrict__ o, int64_t n, int heads, int n_kt, int nqb, float c, int qk_norm) {
+    const uint16_t *q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp, uint16_t *o,
+    const uint16_t *res, int64_t n, int heads, int n_seq, int n_kt, int nqb, float c,
+    int qk_norm) {
   __shared__ u32x4 ks[kKSlots][8 * kFragU4];
   __shared__ u32x4 vs[kVSlots][8 * kFragU4];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ql = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = wave >> 2;           // phase group
   const int C = heads * 64;
-  int head, qb;
-  if ((heads & 7) == 0) {
-    const int hp = heads >> 3, xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-    head = xcd * hp + local / nqb;
+  int sh, qb;   // (sequence, head) pair and query block; each XCD gets whole pairs
+  if (((heads * n_seq) & 7) == 0) {
+    const int hp = (heads * n_seq) >> 3, xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    sh = xcd * hp + local / nqb;
     qb = local % nqb;
   } else {
-    head = blockIdx.x / nqb;
+    sh = blockIdx.x / nqb;
     qb = blockIdx.x % nqb;
   }
+  const int seq = sh / heads, head = sh - seq * heads;
+  q += (size_t)seq * n * C;
+  o += (size_t)seq * n * C;
+  if (res) res += (size_t)seq * n * C;
   const int64_t q0 = (int64_t)qb * kQB + wave * kQW;
 
   // Q^T fragments (B operand): lane (h*32+ql) holds Q[q0+32*sub+ql][16s+8h .. +8]
@@ -144,8 +154,8 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
   const bf16x2 kOnes = {(__bf16)1.0f, (__bf16)1.0f};
 
   const int nkv = n_kt >> 1;           // 64-key tiles
-  const u32x4 *kh = kp + (size_t)head * n_kt * 4 * kFragU4;
-  const u32x4 *vh = vp + (size_t)head * n_kt * 4 * kFragU4;
+  const u32x4 *kh = kp + (size_t)sh * n_kt * 4 * kFragU4;
+  const u32x4 *vh = vp + (size_t)sh * n_kt * 4 * kFragU4;
   u32x4 rk, rv;
   auto g2r = [&](int j) {              // global -> registers, 64-key tile j (16 B of K and V per thread)
     const size_t off = (size_t)j * 8 * kFragU4;
@@ -334,8 +344,16 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
       for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          u32x2 w = {pack_bf16(oacc[sub][dt][4 * g] * inv, oacc[sub][dt][4 * g + 1] * inv),
-                     pack_bf16(oacc[sub][dt][4 * g + 2] * inv, oacc[sub][dt][4 * g + 3] * inv)};
+          float r0 = oacc[sub][dt][4 * g] * inv, r1 = oacc[sub][dt][4 * g + 1] * inv;
+          float r2 = oacc[sub][dt][4 * g + 2] * inv, r3 = oacc[sub][dt][4 * g + 3] * inv;
+          if (res) {   // out = res + attention, one rounding (res may be the output buffer)
+            const u32x2 x = *(const u32x2 *)(res + (size_t)row * C + head * 64 + 4 * h + 32 * dt + 8 * g);
+            r0 += bf16_lo(x.x);
+            r1 += bf16_hi(x.x);
+            r2 += bf16_lo(x.y);
+            r3 += bf16_hi(x.y);
+          }
+          const u32x2 w = {pack_bf16(r0, r1), pack_bf16(r2, r3)};
           *(u32x2 *)(op + 32 * dt + 8 * g) = w;
         }
     }
@@ -365,22 +383,26 @@ constexpr int kBStages = 4;          // LDS ring of 64-key K/V stages
 
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_bf16_bounded(
-    const uint16_t *__restrict__ q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp,
-    uint16_t *__restrict__ o, int64_t n, int heads, int n_kt, int nqb, float c) {
+    const uint16_t *q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp, uint16_t *o,
+    const uint16_t *res, int64_t n, int heads, int n_seq, int n_kt, int nqb, float c) {
   __shared__ u32x4 ks[kBStages][8 * kFragU4];
   __shared__ u32x4 vs[kBStages][8 * kFragU4];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ql = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int C = heads * 64;
-  int head, qb;
-  if ((heads & 7) == 0) {
-    const int hp = heads >> 3, xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-    head = xcd * hp + local / nqb;
+  int sh, qb;   // (sequence, head) pair and query block; each XCD gets whole pairs
+  if (((heads * n_seq) & 7) == 0) {
+    const int hp = (heads * n_seq) >> 3, xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    sh = xcd * hp + local / nqb;
     qb = local % nqb;
   } else {
-    head = blockIdx.x / nqb;
+    sh = blockIdx.x / nqb;
     qb = blockIdx.x % nqb;
   }
+  const int seq = sh / heads, head = sh - seq * heads;
+  q += (size_t)seq * n * C;
+  o += (size_t)seq * n * C;
+  if (res) res += (size_t)seq * n * C;
   const int64_t q0 = (int64_t)qb * kBQB + wave * kQW;
 
   // Q^T fragments, RMS-normalised per head with the softmax scale (log2 units) folded in
@@ -410,8 +432,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const f32x16 kZero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   const int nkv = n_kt >> 1, nkt = n_kt;
-  const u32x4 *kh = kp + (size_t)head * n_kt * 4 * kFragU4;
-  const u32x4 *vh = vp + (size_t)head * n_kt * 4 * kFragU4;
+  const u32x4 *kh = kp + (size_t)sh * n_kt * 4 * kFragU4;
+  const u32x4 *vh = vp + (size_t)sh * n_kt * 4 * kFragU4;
   // Stage `stage` of this head's packed K and V (64 keys, 8 KB each) goes from global memory
   // straight into its ring slot, 1 KB per wave and instruction (global_load_lds_dwordx4: lane l
   // of a wave lands at the wave's LDS base + 16 l).  No registers are staged, so a stage can be
@@ -609,8 +631,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          u32x2 w = {pack_bf16(oacc[sub][dt][4 * g] * inv, oacc[sub][dt][4 * g + 1] * inv),
-                     pack_bf16(oacc[sub][dt][4 * g + 2] * inv, oacc[sub][dt][4 * g + 3] * inv)};
+          float r0 = oacc[sub][dt][4 * g] * inv, r1 = oacc[sub][dt][4 * g + 1] * inv;
+          float r2 = oacc[sub][dt][4 * g + 2] * inv, r3 = oacc[sub][dt][4 * g + 3] * inv;
+          if (res) {   // out = res + attention, one rounding (res may be the output buffer)
+            const u32x2 x = *(const u32x2 *)(res + (size_t)row * C + head * 64 + 4 * h + 32 * dt + 8 * g);
+            r0 += bf16_lo(x.x);
+            r1 += bf16_hi(x.x);
+            r2 += bf16_lo(x.y);
+            r3 += bf16_hi(x.y);
+          }
+          const u32x2 w = {pack_bf16(r0, r1), pack_bf16(r2, r3)};
           *(u32x2 *)(op + 32 * dt + 8 * g) = w;
         }
     }
@@ -959,15 +989,21 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
 
 static int n_key_tiles(int64_t n) { return (int)(2 * ((n + kKV - 1) / kKV)); }
 
-size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype) {
+size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype, int n_seq) {
   const size_t elem = attn_dtype == LV_ATTN_FP8_E4M3 ? sizeof(u32x2) : sizeof(u32x4);
-  const size_t per = (size_t)heads * n_key_tiles(n_tokens) * 4 * kFragU4 * elem;
+  const size_t per = (size_t)heads * n_seq * n_key_tiles(n_tokens) * 4 * kFragU4 * elem;
   return 256 + 2 * align_up(per, 256);   // [amax block][K fragments][V fragments]
 }
 
+// n_seq independent sequences of n tokens each, stored one after the other (n_seq = 1: the
+// global attention over the merged sequence; n_seq = frames: frame attention).  Several
+// sequences and the fused residual (o = res + attention, res may be o: a workgroup reads the
+// rows it writes and nothing else of them) are supported by the bf16 kernels only.
 int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_t *o,
                 int64_t n, int heads, float scale, int attn_dtype, int qk_norm, void *ws,
-                hipStream_t st, hipEvent_t after_pack) {
+                hipStream_t st, hipEvent_t after_pack, int n_seq, const uint16_t *res) {
+  if (n_seq < 1 || (int64_t)heads * n_seq > 65535) return LV_ERR_SHAPE;
+  if ((n_seq > 1 || res) && attn_dtype != LV_ATTN_BF16) return LV_ERR_DTYPE;
   const int n_kt = n_key_tiles(n);
   const float c = scale * 1.4426950408889634f;
   const int nqb = (int)((n + kQB - 1) / kQB);
@@ -990,22 +1026,22 @@ int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_
     return LV_OK;
   }
   if (attn_dtype != LV_ATTN_BF16) return LV_ERR_DTYPE;
-  const size_t per = align_up((size_t)heads * n_kt * 4 * kFragU4 * sizeof(u32x4), 256);
+  const size_t per = align_up((size_t)heads * n_seq * n_kt * 4 * kFragU4 * sizeof(u32x4), 256);
   u32x4 *kp = (u32x4 *)frag;
   u32x4 *vp = (u32x4 *)(frag + per);
-  hipLaunchKernelGGL(k_attn_pack, dim3((unsigned)n_kt, (unsigned)heads), dim3(256), 0, st, k, v, n,
-                     heads, n_kt, qk_norm, kp, vp);
+  hipLaunchKernelGGL(k_attn_pack, dim3((unsigned)n_kt, (unsigned)(heads * n_seq)), dim3(256), 0, st,
+                     k, v, n, heads, n_kt, qk_norm, kp, vp);
   if (after_pack && hipEventRecord(after_pack, st) != hipSuccess) return LV_ERR_HIP;
   // |q.k| <= 64 * (1 + 2^-8) for unit-RMS heads rounded to bf16; exp2 of the scaled score must
   // stay well inside fp32 range even summed over the sequence
   const bool bounded = qk_norm && 64.25f * c <= 64.0f;
   if (bounded) {
     const int nqb2 = (int)((n + kBQB - 1) / kBQB);
-    hipLaunchKernelGGL(k_attn_bf16_bounded, dim3((unsigned)(nqb2 * heads)), dim3(256), 0, st, q,
-                       kp, vp, o, n, heads, n_kt, nqb2, c);
+    hipLaunchKernelGGL(k_attn_bf16_bounded, dim3((unsigned)(nqb2 * heads * n_seq)), dim3(256), 0,
+                       st, q, kp, vp, o, res, n, heads, n_seq, n_kt, nqb2, c);
   } else {
-    hipLaunchKernelGGL(k_attn_bf16, dim3((unsigned)(nqb * heads)), dim3(512), 0, st, q, kp, vp, o,
-                       n, heads, n_kt, nqb, c, qk_norm);
+    hipLaunchKernelGGL(k_attn_bf16, dim3((unsigned)(nqb * heads * n_seq)), dim3(512), 0, st, q, kp,
+                       vp, o, res, n, heads, n_seq, n_kt, nqb, c, qk_norm);
   }
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;

@@ -40,10 +40,12 @@ int launch_unmerge(const uint16_t *y, const Dims &d, const litevggt_index &ix,
                    const uint16_t *residual, uint16_t *out, hipStream_t st);
 
 // attn.hip
-size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype);
-// `after_pack`, when not NULL, is recorded between the K/V re-layout and the main kernel
+size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype, int n_seq = 1);
+// `after_pack`, when not NULL, is recorded between the K/V re-layout and the main kernel;
+// n_seq sequences of n_tokens each; res: optional residual added to the output
 int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_t *o,
                 int64_t n_tokens, int heads, float scale, int attn_dtype, int qk_norm, void *ws,
-                hipStream_t st, hipEvent_t after_pack = nullptr);
+                hipStream_t st, hipEvent_t after_pack = nullptr, int n_seq = 1,
+                const uint16_t *res = nullptr);
 
 }  // namespace lv

@@ -458,6 +458,67 @@ def test_layers_run_fp8_attention(B):
     assert max_rel_err(got, emu) <= 2e-2
 
 
+# ------------------------------------------------------------------------- frame attention
+@pytest.mark.parametrize("qk_norm", [1, 0])
+@pytest.mark.parametrize("frames,grid,heads", [(3, 37, 4), (5, 6, 2), (2, 16, 16)])
+def test_frame_attn(B, frames, grid, heads, qk_norm):
+    """Every frame attends over its own tokens only (Sec. 3.1); ragged frame length (1374 is
+    not a multiple of any tile), several (frame, head) pairs per XCD, both bf16 kernels."""
+    import torch
+    wl = small_workload(frames=frames, grid=grid, dim=64 * heads, heads=heads, r=0.5)
+    po, ph = oracle_params(wl, qk_norm=bool(qk_norm)), hip_params(wl, qk_norm=qk_norm)
+    rng = np.random.default_rng(frames * 100 + grid)
+    N, C = wl.n_tokens, wl.dim
+    qb, kb, vb = (synth.f32_to_bf16_bits(rng.standard_normal((N, C)).astype(np.float32)) for _ in range(3))
+    q, k, v = (synth.bf16_bits_to_f32(a).astype(np.float64).reshape(N, heads, 64) for a in (qb, kb, vb))
+    qn = _store_bf16(O.qk_normalize(q)) if qk_norm else q
+    kn = _store_bf16(O.qk_normalize(k)) if qk_norm else k
+    want = O.frame_attention(qn, kn, v, po).reshape(N, C)
+    ws = B.alloc_ws(B.litevggt_frame_attn_ws_bytes(ph))
+    o = torch.zeros(N, C, dtype=torch.bfloat16, device="cuda")
+    B.litevggt_frame_attn(ph, to_dev_bf16(qb), to_dev_bf16(kb), to_dev_bf16(vb), None, o, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(dev_bf16_to_f64(o), want) <= BF16_TOL
+    # fused residual, in place: x <- x + FrameAttn(x)
+    x = to_dev_bf16(qb)
+    B.litevggt_frame_attn(ph, x, x, x, x, x, ws)
+    torch.cuda.synchronize()
+    xf = q.reshape(N, C)
+    xn = _store_bf16(O.qk_normalize(q)) if qk_norm else q
+    want2 = xf + O.frame_attention(xn, xn, q, po).reshape(N, C)
+    assert max_rel_err(dev_bf16_to_f64(x), want2) <= BF16_TOL
+
+
+def test_layers_run_with_frame_attention(B):
+    """The driver with a frame attention after every global layer, teacher-forced per layer."""
+    import torch
+    wl = synth.workload("tiny2")
+    bits, xf, im = stored_inputs(wl)
+    po, ph = oracle_params(wl, frame_attn=True), hip_params(wl, frame_attn=1)
+    pl = B.litevggt_plan(ph)
+    trace = []
+    ref_out, ref_log = O.layers_run(im, xf, po, 2, store=_store_bf16, trace=trace)
+    im_dev = torch.from_numpy(im).cuda()
+    grad = torch.zeros(wl.frames, wl.patches, device="cuda")
+    score = torch.zeros(wl.frames, wl.patches, device="cuda")
+    ws = B.alloc_ws(pl.ws_bytes)
+    p1 = hip_params(wl, frame_attn=1, refresh_interval=1)
+    for t in trace:
+        x_dev = f32_to_dev_bf16(t["x_in"].astype(np.float32))
+        ib = B.alloc_index(pl)
+        B.litevggt_layers_run(p1, 1, im_dev, x_dev, ib, grad, score, ws)
+        torch.cuda.synchronize()
+        idx = O.compute_index(im, t["x_in"], po)[0]
+        exp = O.frame_layer(O.global_layer(t["x_in"], idx, po, _store_bf16), po, _store_bf16)
+        assert max_rel_err(dev_bf16_to_f64(x_dev), exp) <= BF16_TOL
+    x_dev = to_dev_bf16(bits)
+    ib = B.alloc_index(pl)
+    log = B.litevggt_layers_run(ph, 2, im_dev, x_dev, ib, grad, score, ws)
+    torch.cuda.synchronize()
+    assert log == ref_log
+    assert max_rel_err(dev_bf16_to_f64(x_dev), ref_out) <= BF16_TOL
+
+
 # ------------------------------------------------------------- geometry-blind anchor policies
 @pytest.mark.parametrize("policy", ["fixed", "random"])
 def test_naive_anchor_policies(B, policy):

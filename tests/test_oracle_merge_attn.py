@@ -226,3 +226,54 @@ def test_refresh_on_unchanged_features_reproduces_index():
     pl = O.plan(p)
     assert len(a["kept_idx"]) == pl["M"] and len(a["src_idx"]) == pl["n_src"]
     assert len(a["dst_idx"]) == pl["n_dst"]
+
+
+# ---------------------------------------------------------------------------
+# frame attention (Sec. 3.1)
+# ---------------------------------------------------------------------------
+def test_frame_attention_is_block_diagonal_attention():
+    rng = np.random.default_rng(3)
+    p = O.Params(frames=3, grid_h=2, grid_w=3, n_special=1, dim=128, heads=2)
+    T, N = p.tokens_per_frame, p.n_tokens
+    q, k, v = (rng.standard_normal((N, 2, 64)) for _ in range(3))
+    got = O.frame_attention(q, k, v, p)
+    # the same thing written as one masked softmax over the whole sequence
+    frame = np.arange(N) // T
+    for h in range(2):
+        s = (q[:, h] @ k[:, h].T) / 8.0
+        s[frame[:, None] != frame[None, :]] = -np.inf
+        w = np.exp(s - s.max(axis=1, keepdims=True))
+        w /= w.sum(axis=1, keepdims=True)
+        assert np.abs(got[:, h] - w @ v[:, h]).max() < 1e-12
+    # one frame: the plain attention; other frames' tokens do not matter
+    p1 = O.Params(frames=1, grid_h=2, grid_w=3, n_special=1, dim=128, heads=2)
+    assert np.array_equal(O.frame_attention(q[:T], k[:T], v[:T], p1), O.attention(q[:T], k[:T], v[:T]))
+    k2, v2 = k.copy(), v.copy()
+    k2[T:], v2[T:] = rng.standard_normal(k[T:].shape), rng.standard_normal(v[T:].shape)
+    assert np.array_equal(O.frame_attention(q, k2, v2, p)[:T], got[:T])
+
+
+def test_frame_attention_against_torch_sdpa_per_frame():
+    import torch
+    rng = np.random.default_rng(4)
+    p = O.Params(frames=2, grid_h=3, grid_w=3, n_special=5, dim=128, heads=2)
+    T = p.tokens_per_frame
+    q, k, v = (rng.standard_normal((2 * T, 2, 64)) for _ in range(3))
+    got = O.frame_attention(q, k, v, p)
+    for f in range(2):
+        tq, tk, tv = (torch.from_numpy(a[f * T:(f + 1) * T]).permute(1, 0, 2) for a in (q, k, v))
+        ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).permute(1, 0, 2).numpy()
+        assert np.abs(got[f * T:(f + 1) * T] - ref).max() < 1e-12
+
+
+def test_frame_layer_is_residual_plus_frame_attention():
+    rng = np.random.default_rng(5)
+    p = O.Params(frames=2, grid_h=2, grid_w=2, n_special=1, dim=64, heads=1, qk_norm=True)
+    x = rng.standard_normal((p.n_tokens, 64))
+    xx = x.reshape(-1, 1, 64)
+    qk = O.qk_normalize(xx)
+    want = x + O.frame_attention(qk, qk, xx, p).reshape(x.shape)
+    assert np.array_equal(O.frame_layer(x, p), want)
+    # constant value rows inside a frame: attention returns them, the layer doubles them
+    xc = np.repeat(rng.standard_normal((2, 1, 64)), p.tokens_per_frame, axis=0).reshape(-1, 64)
+    assert np.abs(O.frame_layer(xc, p) - 2 * xc).max() < 1e-12
