@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--attn-dtype", default="bf16", choices=["bf16", "fp8"])
     ap.add_argument("--anchor-policy", default="ga", choices=["ga", "fixed", "random"],
                     help="what ranks the tokens: the GA map, or a geometry-blind partition")
+    ap.add_argument("--block", action="store_true",
+                    help="global layer = LayerNorm, q|k|v projection, attention, output projection, "
+                         "MLP with seeded synthetic weights instead of the projection-free attention")
     ap.add_argument("--frame-attn", action="store_true",
                     help="run a frame attention after every global layer (not part of the metric's default)")
     ap.add_argument("--no-unmerged", action="store_true",
@@ -168,12 +171,18 @@ def main():
         over["refresh_interval"] = args.refresh_interval
     wl = synth.workload(args.workload, **over)
     attn_dtype = B.ATTN_BF16 if args.attn_dtype == "bf16" else B.ATTN_FP8_E4M3
+    bw = None
+    if args.block:
+        w_host = synth.block_weights(wl.dim, seed=wl.seed)
+        w_dev = {k: (torch.from_numpy(synth.f32_to_bf16_bits(v).view(np.int16)).cuda().view(torch.bfloat16)
+                     if v.ndim == 2 else torch.from_numpy(v).cuda()) for k, v in w_host.items()}
+        bw = B.block_weights(w_dev)
     ph = B.make_params(wl.frames, wl.grid_h, wl.grid_w, wl.dim, wl.heads, n_special=wl.n_special,
                        patch=wl.patch, merge_ratio=wl.merge_ratio,
                        refresh_interval=wl.refresh_interval, qk_norm=1, attn_dtype=attn_dtype,
                        anchor_policy=dict(ga=B.POLICY_GA, fixed=B.POLICY_FIXED,
                                           random=B.POLICY_RANDOM)[args.anchor_policy],
-                       frame_attn=1 if args.frame_attn else 0)
+                       frame_attn=1 if args.frame_attn else 0, block=bw)
     wl_qk_norm = bool(ph.qk_norm)
     pl = B.litevggt_plan(ph)
     L, C_ = wl.layers, wl.dim
@@ -237,7 +246,8 @@ def main():
              "merge": (B.EV_MATCH_END, B.EV_MERGE_END),
              "attn_pack": (B.EV_MERGE_END, B.EV_ATTN_PACK_END),
              "attn": (B.EV_ATTN_PACK_END, B.EV_ATTN_END),
-             "unmerge": (B.EV_ATTN_END, B.EV_UNMERGE_END),
+             "block_rest": (B.EV_ATTN_END, B.EV_BLOCK_END),
+             "unmerge": (B.EV_BLOCK_END, B.EV_UNMERGE_END),
              "frame_attn": (B.EV_UNMERGE_END, B.EV_FRAME_ATTN_END)}
     dur = {k: [] for k in names}
     for ev in evs:
@@ -267,6 +277,12 @@ def main():
         "importance": dict(ms=avg["importance"]),
         "select": dict(ms=avg["select"]),
     }
+    if args.block:
+        blk_flop = 2.0 * M * C_ * (3 * C_ + C_ + 4 * C_ + 4 * C_)
+        ops["block_linear"] = dict(ms=avg["attn_pack"] + avg["block_rest"],
+                                   tflops=blk_flop / ((avg["attn_pack"] + avg["block_rest"]) * 1e-3) / 1e12,
+                                   note="everything of the block except the attention kernel: 2 LayerNorms, "
+                                        "4 linear layers (24 M C^2 flop), operand re-layouts, K/V re-layout")
     if args.frame_attn:
         fa_flop = 4.0 * wl.frames * wl.tokens_per_frame ** 2 * C_
         ops["frame_attn"] = dict(ms=avg["frame_attn"], tflops=fa_flop / (avg["frame_attn"] * 1e-3) / 1e12,
@@ -305,7 +321,7 @@ def main():
                                f"{wl.merge_ratio} (M={M}), {L} global layers, index refreshed "
                                f"every {wl.refresh_interval}",
                    "token_layers_per_s": L * N / (ms_step * 1e-3),
-                   "anchor_policy": args.anchor_policy, "frame_attn": bool(args.frame_attn),
+                   "anchor_policy": args.anchor_policy, "frame_attn": bool(args.frame_attn), "block": bool(args.block),
                    "refresh_log": log, "output_finite": finite,
                    "peak_hbm_alloc_gib": torch.cuda.max_memory_allocated() / 2 ** 30,
                    "input_generation_s": gen_s,

@@ -45,6 +45,21 @@ enum { LV_ATTN_BF16 = 0, LV_ATTN_FP8_E4M3 = 1 }; /* attention MFMA operand type 
 enum { LV_ROLE_PROTECTED = 0, LV_ROLE_DST = 1, LV_ROLE_SRC = 2 };
 enum { LV_POLICY_GA = 0, LV_POLICY_FIXED = 1, LV_POLICY_RANDOM = 2 }; /* what ranks the tokens */
 
+/* Weights of the transformer block around the global attention (litevggt_global_block):
+ * device pointers, matrices bf16 row-major [out features, in features], vectors fp32. */
+typedef struct {
+  const float *ln1_g, *ln1_b;   /* [dim]  LayerNorm before the attention                  */
+  const void  *w_qkv;           /* [3 dim, dim]: rows 0..dim-1 give q, then k, then v     */
+  const float *b_qkv;           /* [3 dim]                                                */
+  const void  *w_o;             /* [dim, dim]   output projection                         */
+  const float *b_o;             /* [dim]                                                  */
+  const float *ln2_g, *ln2_b;   /* [dim]  LayerNorm before the MLP                        */
+  const void  *w_1;             /* [4 dim, dim] */
+  const float *b_1;             /* [4 dim]      */
+  const void  *w_2;             /* [dim, 4 dim] */
+  const float *b_2;             /* [dim]        */
+} litevggt_block_weights;
+
 /* Shape and hyper-parameters (host memory). */
 typedef struct {
   int32_t frames;          /* F                                                    */
@@ -71,6 +86,9 @@ typedef struct {
   uint32_t policy_seed;    /* seed of LV_POLICY_RANDOM                              */
   int32_t frame_attn;      /* != 0: the layer driver runs a frame attention after every
                               global layer (see litevggt_frame_attn)                */
+  const litevggt_block_weights *block; /* [host] NULL: the layer driver's global layer is the
+                              projection-free attention; else it is litevggt_global_block
+                              with these weights (the same in every layer)          */
 } litevggt_params;
 
 /* Token counts that follow from the parameters (closed form, Sec. 3.4 partition). */
@@ -179,6 +197,25 @@ int litevggt_global_attn(const litevggt_params *p, int64_t n_tokens, const void 
 int litevggt_unmerge(const litevggt_params *p, const void *y, const litevggt_index *index,
                      const void *residual, void *out, void *stream);
 
+/* The transformer block around the global attention core, on a sequence of n_tokens
+ * (Sec. 3.1: the aggregator's global layers are pre-norm attention + MLP blocks; the paper
+ * does not restate them, so this is the plain block, with caller-supplied weights):
+ *   h = LN(z; ln1)                q|k|v = h w_qkv^T + b_qkv       (LN eps 1e-6)
+ *   a = attention(q, k, v)        as litevggt_global_attn (attn_dtype, qk_norm, softmax_scale)
+ *   u1 = a w_o^T + b_o            h2 = LN(z + u1; ln2)
+ *   u2 = GELU(h2 w_1^T + b_1) w_2^T + b_2     (GELU with erf)
+ *   delta = u1 + u2               the block's output is z + delta
+ * Every intermediate (h, q, k, v, a, u1, h2, the MLP hidden layer, u2) is stored as bf16;
+ * accumulation is fp32.  dim must be a multiple of 256.
+ *   z      [device] [n_tokens, dim] bf16
+ *   delta  [device] [n_tokens, dim] bf16 out
+ *   ws     litevggt_global_block_ws_bytes(p, n_tokens) bytes
+ */
+size_t litevggt_global_block_ws_bytes(const litevggt_params *p, int64_t n_tokens);
+int litevggt_global_block(const litevggt_params *p, int64_t n_tokens, const void *z,
+                          const litevggt_block_weights *weights /*[host]*/, void *delta, void *ws,
+                          size_t ws_bytes, void *stream);
+
 /* Frame attention, Sec. 3.1 (VGGT alternates frame-wise and global self-attention; Sec. 3.4
  * "Token Unmerging": the unmerged tokens go to the next frame attention): for every frame f
  * separately, O_f = softmax(Q_f K_f^T * softmax_scale) V_f over that frame's own P + n_special
@@ -200,6 +237,8 @@ int litevggt_frame_attn(const litevggt_params *p, const void *q, const void *k, 
  * merge index (steps 1-3; the gradient map only at l = 0) when
  * l % refresh_interval == 0, then x <- x + unmerge(attn(merge(x))) with
  * Q = K = V = the merged tokens viewed as [M, heads, 64] (q, k normalised when qk_norm),
+ * or, when p->block is set, x <- x + unmerge(delta of litevggt_global_block(merge(x))),
+ * which at merge ratio 0 is the block applied to the unmerged sequence,
  * then, when frame_attn is set, x <- x + frame_attn(x) with Q = K = V = x.
  *   x           [device] [N,dim] bf16, in/out
  *   images      [device] as for litevggt_importance; with anchor_policy != LV_POLICY_GA
@@ -219,7 +258,8 @@ enum {
   LV_EV_MATCH_END,         /* after matching + CSR, before merge                   */
   LV_EV_MERGE_END,         /* after merge, before the K/V re-layout of attention   */
   LV_EV_ATTN_PACK_END,     /* after the re-layout, before the attention kernel     */
-  LV_EV_ATTN_END,          /* after the attention kernel, before unmerge           */
+  LV_EV_ATTN_END,          /* after the attention kernel                           */
+  LV_EV_BLOCK_END,         /* after the rest of the block (if any), before unmerge */
   LV_EV_UNMERGE_END,       /* after unmerge, before the frame attention (if any)   */
   LV_EV_FRAME_ATTN_END,    /* after the frame attention                            */
   LV_EVENTS_PER_LAYER

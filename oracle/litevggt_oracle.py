@@ -49,6 +49,7 @@ class Params:
     anchor_policy: int = 0      # 0: GA map (Sec. 3.4); 1, 2: the naive partitions of Sec. 3.2 (naive_score)
     policy_seed: int = 0        # seed of the random policy
     frame_attn: bool = False    # layer loop: a frame attention after every global layer (frame_layer)
+    block: Optional[dict] = None  # layer loop: weights of global_block, or None (projection-free attention)
     qk_norm: bool = False       # layer loop: RMS-normalise q and k per head (see global_layer)
     attn_fp8: bool = False      # layer loop: FP8 E4M3 attention emulation (see attention_fp8)
 
@@ -462,6 +463,51 @@ def compute_index(images, x, p: Params, psi_g=None, score_dtype=np.float32):
     return idx, psi_g, score, mt
 
 
+LN_EPS = 1e-6
+
+
+def layer_norm(x: np.ndarray, gamma: np.ndarray, beta: np.ndarray, eps: float = LN_EPS) -> np.ndarray:
+    """(x - mean) / sqrt(var + eps) * gamma + beta over the last axis, population variance."""
+    x = np.asarray(x, dtype=np.float64)
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps) * gamma + beta
+
+
+def gelu(x: np.ndarray) -> np.ndarray:
+    """x * Phi(x), Phi the standard normal CDF (the erf form, not the tanh approximation)."""
+    from scipy.special import erf
+    x = np.asarray(x, dtype=np.float64)
+    return 0.5 * x * (1.0 + erf(x / np.sqrt(2.0)))
+
+
+def linear(x: np.ndarray, w: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """x w^T + b with w [out features, in features]."""
+    return np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T + b
+
+
+def global_block(z: np.ndarray, w: dict, p: Params, store=lambda a: a) -> np.ndarray:
+    """delta = Block(z) - z of the pre-norm transformer block around the global attention
+    (Sec. 3.1: the aggregator's global layers; the paper does not restate the block and there
+    are no trained weights, so this is the plain one with the weights given):
+    LN -> q|k|v projection -> attention (q, k normalised per head when p.qk_norm) -> output
+    projection u1; LN(z + u1) -> GELU MLP u2; delta = u1 + u2.  ``store`` models the storage
+    rounding of every intermediate the HIP path keeps in bf16."""
+    C = z.shape[1]
+    h = store(layer_norm(z, w["ln1_g"], w["ln1_b"]))
+    qkv = store(linear(h, w["w_qkv"], w["b_qkv"]))
+    q, k, v = (qkv[:, i * C:(i + 1) * C].reshape(-1, p.heads, p.head_dim) for i in range(3))
+    if p.qk_norm:
+        q, k = store(qk_normalize(q)), store(qk_normalize(k))
+    attn = attention_fp8 if p.attn_fp8 else attention
+    a = store(attn(q, k, v).reshape(z.shape))
+    u1 = store(linear(a, w["w_o"], w["b_o"]))
+    h2 = store(layer_norm(z + u1, w["ln2_g"], w["ln2_b"]))
+    h3 = store(gelu(linear(h2, w["w_1"], w["b_1"])))
+    u2 = store(linear(h3, w["w_2"], w["b_2"]))
+    return store(u1 + u2)
+
+
 def global_layer(x: np.ndarray, idx: Dict[str, np.ndarray], p: Params,
                  store=lambda a: a) -> np.ndarray:
     """One merged global layer: x + U(Attn(M(x))) with Q = K = V = merged tokens viewed
@@ -469,6 +515,8 @@ def global_layer(x: np.ndarray, idx: Dict[str, np.ndarray], p: Params,
     p.qk_norm, Q = K = the per-head RMS-normalised merged tokens (stored, i.e. rounded).
     ``store`` models the storage rounding applied to z, the normalised q/k, y and the output."""
     z = store(merge(x, idx["group_off"], idx["group_mem"]))
+    if p.block is not None:   # x + U(Block(z) - z): at merge ratio 0 this is Block(x)
+        return store(unmerge(global_block(z, p.block, p, store), idx["slot_of"], residual=x))
     zz = z.reshape(z.shape[0], p.heads, p.head_dim)
     qk = store(qk_normalize(zz)) if p.qk_norm else zz
     attn = attention_fp8 if p.attn_fp8 else attention

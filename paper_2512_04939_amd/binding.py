@@ -22,11 +22,18 @@ ROLE_PROTECTED, ROLE_DST, ROLE_SRC = 0, 1, 2
 EXPORTS = ["litevggt_strerror", "litevggt_plan", "litevggt_attn_ws_bytes", "litevggt_importance",
            "litevggt_select_anchors", "litevggt_match", "litevggt_merge", "litevggt_global_attn",
            "litevggt_unmerge", "litevggt_frame_attn_ws_bytes", "litevggt_frame_attn",
+           "litevggt_global_block_ws_bytes", "litevggt_global_block",
            "litevggt_layers_run"]
 
 
 class LiteVGGTError(RuntimeError):
     pass
+
+
+class BlockWeights(C.Structure):
+    """Mirror of ``litevggt_block_weights`` (device pointers)."""
+    _fields_ = [(n, C.c_void_p) for n in ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g",
+                                          "ln2_b", "w_1", "b_1", "w_2", "b_2")]
 
 
 class Params(C.Structure):
@@ -38,7 +45,7 @@ class Params(C.Structure):
                 ("attn_dtype", C.c_int32), ("qk_norm", C.c_int32), ("alpha", C.c_float), ("beta", C.c_float),
                 ("softmax_scale", C.c_float), ("merge_ratio", C.c_double),
                 ("ga_frac", C.c_double), ("anchor_policy", C.c_int32), ("policy_seed", C.c_uint32),
-                ("frame_attn", C.c_int32)]
+                ("frame_attn", C.c_int32), ("block", C.POINTER(BlockWeights))]
 
 
 class Plan(C.Structure):
@@ -59,10 +66,12 @@ class Index(C.Structure):
 def make_params(frames, grid_h, grid_w, dim, heads, *, head_dim=64, n_special=5, patch=14,
                 img_dtype=IMG_F32, var_pool=3, refresh_interval=6, attn_dtype=ATTN_BF16,
                 qk_norm=0, alpha=0.5, beta=0.5, softmax_scale=0.0, merge_ratio=0.9, ga_frac=0.10,
-                anchor_policy=POLICY_GA, policy_seed=0, frame_attn=0) -> Params:
+                anchor_policy=POLICY_GA, policy_seed=0, frame_attn=0, block=None) -> Params:
+    """``block``: a BlockWeights the caller keeps alive, or None."""
     return Params(frames, grid_h, grid_w, n_special, dim, heads, head_dim, patch, img_dtype,
                   var_pool, refresh_interval, attn_dtype, qk_norm, alpha, beta, softmax_scale,
-                  merge_ratio, ga_frac, anchor_policy, policy_seed, frame_attn)
+                  merge_ratio, ga_frac, anchor_policy, policy_seed, frame_attn,
+                  C.pointer(block) if block is not None else None)
 
 
 _lib = None
@@ -89,13 +98,16 @@ def lib() -> C.CDLL:
         L.litevggt_merge.argtypes = [PP, vp, C.POINTER(Index), vp, vp]
         L.litevggt_global_attn.argtypes = [PP, i64, vp, vp, vp, vp, vp, sz, vp]
         L.litevggt_unmerge.argtypes = [PP, vp, C.POINTER(Index), vp, vp, vp]
+        L.litevggt_global_block_ws_bytes.restype = sz
+        L.litevggt_global_block_ws_bytes.argtypes = [PP, i64]
+        L.litevggt_global_block.argtypes = [PP, i64, vp, C.POINTER(BlockWeights), vp, vp, sz, vp]
         L.litevggt_frame_attn_ws_bytes.restype = sz
         L.litevggt_frame_attn_ws_bytes.argtypes = [PP]
         L.litevggt_frame_attn.argtypes = [PP, vp, vp, vp, vp, vp, vp, sz, vp]
         L.litevggt_layers_run.argtypes = [PP, i32, vp, vp, C.POINTER(Index), vp, vp,
                                           C.POINTER(C.c_int32), C.POINTER(C.c_void_p), vp, sz, vp]
         for name in EXPORTS[1:]:
-            if name not in ("litevggt_attn_ws_bytes", "litevggt_frame_attn_ws_bytes"):
+            if not name.endswith("_ws_bytes"):
                 getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -220,9 +232,24 @@ def litevggt_frame_attn(p: Params, q, k, v, residual, o, ws) -> None:
                                      wp, wn, _stream()), "litevggt_frame_attn")
 
 
-EVENTS_PER_LAYER = 9
+def block_weights(tensors: dict) -> BlockWeights:
+    """BlockWeights from a dict of device tensors (keys = field names); keep the dict alive."""
+    return BlockWeights(**{k: tensors[k].data_ptr() for k, _ in BlockWeights._fields_})
+
+
+def litevggt_global_block_ws_bytes(p: Params, n_tokens: int) -> int:
+    return int(lib().litevggt_global_block_ws_bytes(C.byref(p), n_tokens))
+
+
+def litevggt_global_block(p: Params, n_tokens: int, z, weights: BlockWeights, delta, ws) -> None:
+    wp, wn = _ws_args(ws)
+    _check(lib().litevggt_global_block(C.byref(p), n_tokens, _ptr(z), C.byref(weights), _ptr(delta),
+                                       wp, wn, _stream()), "litevggt_global_block")
+
+
+EVENTS_PER_LAYER = 10
 (EV_LAYER_BEGIN, EV_IMPORTANCE_END, EV_SELECT_END, EV_MATCH_END, EV_MERGE_END, EV_ATTN_PACK_END,
- EV_ATTN_END, EV_UNMERGE_END, EV_FRAME_ATTN_END) = range(EVENTS_PER_LAYER)
+ EV_ATTN_END, EV_BLOCK_END, EV_UNMERGE_END, EV_FRAME_ATTN_END) = range(EVENTS_PER_LAYER)
 
 
 def litevggt_layers_run(p: Params, n_layers: int, images, x, index: IndexBuffers, grad_cache,

@@ -91,6 +91,10 @@ size_t driver_ws_bytes(const litevggt_params *p, const Dims &d, const litevggt_p
     a = attn_ws_bytes(d.heads, d.T, LV_ATTN_BF16, d.F);
     if (a > op) op = a;
   }
+  if (p->block) {
+    a = block_ws_bytes(pl.M, d.C, d.heads, p->attn_dtype);
+    if (a > op) op = a;
+  }
   return zy + op;
 }
 
@@ -215,6 +219,30 @@ int litevggt_global_attn(const litevggt_params *p, int64_t n_tokens, const void 
                      n_tokens, d.heads, scale_of(p), p->attn_dtype, p->qk_norm, ws, (hipStream_t)stream);
 }
 
+static bool block_weights_ok(const litevggt_block_weights *w) {
+  return w && w->ln1_g && w->ln1_b && w->w_qkv && w->b_qkv && w->w_o && w->b_o && w->ln2_g &&
+         w->ln2_b && w->w_1 && w->b_1 && w->w_2 && w->b_2;
+}
+
+size_t litevggt_global_block_ws_bytes(const litevggt_params *p, int64_t n_tokens) {
+  Dims d;
+  if (check_params(p, &d) || n_tokens < 1) return 0;
+  return block_ws_bytes(n_tokens, d.C, d.heads, p->attn_dtype);
+}
+
+int litevggt_global_block(const litevggt_params *p, int64_t n_tokens, const void *z,
+                          const litevggt_block_weights *weights, void *delta, void *ws,
+                          size_t ws_bytes, void *stream) {
+  Dims d;
+  int rc = check_params(p, &d);
+  if (rc) return rc;
+  if (!z || !delta || !block_weights_ok(weights)) return LV_ERR_NULL;
+  if (n_tokens < 1 || n_tokens >= ((int64_t)1 << 31) || d.C % 256 != 0) return LV_ERR_SHAPE;
+  if (!ws_ok(ws, ws_bytes, block_ws_bytes(n_tokens, d.C, d.heads, p->attn_dtype))) return LV_ERR_WORKSPACE;
+  return launch_global_block((const uint16_t *)z, n_tokens, d.C, d.heads, scale_of(p), p->attn_dtype,
+                             p->qk_norm, *weights, (uint16_t *)delta, ws, (hipStream_t)stream);
+}
+
 size_t litevggt_frame_attn_ws_bytes(const litevggt_params *p) {
   Dims d;
   if (check_params(p, &d)) return 0;
@@ -257,6 +285,8 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
   const bool ga = p->anchor_policy == LV_POLICY_GA;   // the other policies read no image, cache no map
   if (!x || !score || !index_ok(index) || (ga && (!images || !grad_cache))) return LV_ERR_NULL;
   if (d.C > 1024) return LV_ERR_SHAPE;
+  if (p->block && (!block_weights_ok(p->block) || d.C % 256 != 0))
+    return p->block && d.C % 256 != 0 ? LV_ERR_SHAPE : LV_ERR_NULL;
   if (!ws_ok(ws, ws_bytes, driver_ws_bytes(p, d, pl))) return LV_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   const size_t zy = align_up((size_t)pl.M * d.C * 2, 256);
@@ -300,10 +330,18 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
     rc = launch_merge(xx, d, pl.M, *index, z, st);
     if (rc) return rc;
     if ((rc = mark(LV_EV_MERGE_END))) return rc;
-    rc = launch_attn(z, z, z, y, pl.M, d.heads, scale_of(p), p->attn_dtype, p->qk_norm, op_ws, st,
-                     ev ? ev[LV_EV_ATTN_PACK_END] : nullptr);
-    if (rc) return rc;
-    if ((rc = mark(LV_EV_ATTN_END))) return rc;
+    if (p->block) {
+      rc = launch_global_block(z, pl.M, d.C, d.heads, scale_of(p), p->attn_dtype, p->qk_norm,
+                               *p->block, y, op_ws, st, ev ? ev[LV_EV_ATTN_PACK_END] : nullptr,
+                               ev ? ev[LV_EV_ATTN_END] : nullptr);
+      if (rc) return rc;
+    } else {
+      rc = launch_attn(z, z, z, y, pl.M, d.heads, scale_of(p), p->attn_dtype, p->qk_norm, op_ws, st,
+                       ev ? ev[LV_EV_ATTN_PACK_END] : nullptr);
+      if (rc) return rc;
+      if ((rc = mark(LV_EV_ATTN_END))) return rc;
+    }
+    if ((rc = mark(LV_EV_BLOCK_END))) return rc;
     rc = launch_unmerge(y, d, *index, xx, xx, st);
     if (rc) return rc;
     if ((rc = mark(LV_EV_UNMERGE_END))) return rc;

@@ -1,0 +1,317 @@
+// The transformer block around the global attention core, on the merged sequence (Sec. 3.1:
+// the aggregator's global layers are standard pre-norm attention + MLP blocks; the paper does
+// not restate their details and there are no trained weights here, so the block is the plain
+// one with synthetic weights):
+//   h  = LN(z; g1, b1)                       q|k|v = h Wqkv^T + bqkv
+//   a  = Attn(q, k, v)   (q, k RMS-normalised per head when qk_norm)
+//   u1 = a Wo^T + bo                         h2 = LN(z + u1; g2, b2)
+//   u2 = GELU(h2 W1^T + b1m) W2^T + b2m      delta = u1 + u2        (Block(z) = z + delta)
+// Every intermediate is stored as bf16; the four linear layers run on one tiled MFMA kernel.
+#include "common.h"
+#include "internal.h"
+
+namespace lv {
+
+// ---------------------------------------------------------------------------------------
+// LayerNorm over the channel dimension, one wave per row, statistics in fp32 (two passes over
+// registers: mean, then the centred sum of squares).  `add` (optional) is added to x first.
+// ---------------------------------------------------------------------------------------
+constexpr float kLnEps = 1e-6f;
+
+template <int CPL>
+__global__ __launch_bounds__(256) void k_layernorm(const uint16_t *__restrict__ x,
+                                                   const uint16_t *__restrict__ add,
+                                                   const float *__restrict__ gamma,
+                                                   const float *__restrict__ beta, int64_t M, int C,
+                                                   uint16_t *__restrict__ out) {
+  const int lane = threadIdx.x & 63, nch = C >> 3;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  float v[CPL][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane + 64 * c;
+    u32x4 w = {0u, 0u, 0u, 0u}, a = {0u, 0u, 0u, 0u};
+    if (ch < nch) {
+      w = ((const u32x4 *)(x + (size_t)row * C))[ch];
+      if (add) a = ((const u32x4 *)(add + (size_t)row * C))[ch];
+    }
+    const uint32_t uw[4] = {w.x, w.y, w.z, w.w}, ua[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[c][2 * i] = bf16_lo(uw[i]) + bf16_lo(ua[i]);
+      v[c][2 * i + 1] = bf16_hi(uw[i]) + bf16_hi(ua[i]);
+      sum += v[c][2 * i] + v[c][2 * i + 1];
+    }
+  }
+  const float mean = wave_sum(sum) / (float)C;
+  float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c)
+    if (lane + 64 * c < nch)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ss += (v[c][i] - mean) * (v[c][i] - mean);
+  const float rstd = 1.0f / sqrtf(wave_sum(ss) / (float)C + kLnEps);
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane + 64 * c;
+    if (ch < nch) {
+      const f32x4 g0 = ((const f32x4 *)gamma)[2 * ch], g1 = ((const f32x4 *)gamma)[2 * ch + 1];
+      const f32x4 b0 = ((const f32x4 *)beta)[2 * ch], b1 = ((const f32x4 *)beta)[2 * ch + 1];
+      u32x4 o;
+      o.x = pack_bf16((v[c][0] - mean) * rstd * g0[0] + b0[0], (v[c][1] - mean) * rstd * g0[1] + b0[1]);
+      o.y = pack_bf16((v[c][2] - mean) * rstd * g0[2] + b0[2], (v[c][3] - mean) * rstd * g0[3] + b0[3]);
+      o.z = pack_bf16((v[c][4] - mean) * rstd * g1[0] + b1[0], (v[c][5] - mean) * rstd * g1[1] + b1[1]);
+      o.w = pack_bf16((v[c][6] - mean) * rstd * g1[2] + b1[2], (v[c][7] - mean) * rstd * g1[3] + b1[3]);
+      ((u32x4 *)(out + (size_t)row * C))[ch] = o;
+    }
+  }
+}
+
+static int launch_layernorm(const uint16_t *x, const uint16_t *add, const float *gamma,
+                            const float *beta, int64_t M, int C, uint16_t *out, hipStream_t st) {
+  const int cpl = (C / 8 + 63) / 64;
+  const unsigned grid = (unsigned)((M + 3) / 4);
+#define LV_LN(CPL) \
+  hipLaunchKernelGGL(k_layernorm<CPL>, dim3(grid), dim3(256), 0, st, x, add, gamma, beta, M, C, out)
+  switch (cpl) {
+    case 1: LV_LN(1); break;
+    case 2: LV_LN(2); break;
+    case 3: LV_LN(3); break;
+    case 4: LV_LN(4); break;
+    default: return LV_ERR_SHAPE;
+  }
+#undef LV_LN
+  LV_HIP_CHECK_LAUNCH();
+  return LV_OK;
+}
+
+// out = a + b, bf16, one rounding
+__global__ __launch_bounds__(256) void k_add_bf16(const u32x4 *__restrict__ a,
+                                                  const u32x4 *__restrict__ b, int64_t n16,
+                                                  u32x4 *__restrict__ out) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const u32x4 x = a[i], y = b[i];
+    u32x4 o;
+    o.x = pack_bf16(bf16_lo(x.x) + bf16_lo(y.x), bf16_hi(x.x) + bf16_hi(y.x));
+    o.y = pack_bf16(bf16_lo(x.y) + bf16_lo(y.y), bf16_hi(x.y) + bf16_hi(y.y));
+    o.z = pack_bf16(bf16_lo(x.z) + bf16_lo(y.z), bf16_hi(x.z) + bf16_hi(y.z));
+    o.w = pack_bf16(bf16_lo(x.w) + bf16_lo(y.w), bf16_hi(x.w) + bf16_hi(y.w));
+    out[i] = o;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Y[M, Nout] = A[M, K] W[Nout, K]^T + bias (optionally GELU), bf16 in and out, fp32
+// accumulation.  Same machinery as the similarity kernel of the matching step: 256 x 256
+// output tiles, both operands pre-packed fragment-major, fetched straight into a 4-stage LDS
+// ring (2 k-steps per stage, 3 stages ahead), fragments read by hand one k-step ahead, 8 waves
+// of 64 rows x 128 columns.  The finished tile is converted to bf16, transposed through LDS
+// (the ring is free by then) and written in 16-byte pieces along the rows.
+// `split`: the output is Nout / split row-major blocks of [M, split] one after the other
+// (split = Nout: one plain matrix; split = C for the fused q|k|v projection).
+// ---------------------------------------------------------------------------------------
+constexpr int kTile = 256;
+constexpr int kStages = 4;
+constexpr int kStageU4 = 2 * 2 * 8 * 64;     // [weights|activations][2 k-steps][8 fragments][64 lanes]
+constexpr int kOutPitch = kTile * 2 + 16;    // bytes per row of the transposed tile (+16: rows 4 apart miss each other's banks)
+
+__device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
+
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_bt(
+    const u32x4 *__restrict__ ap, const u32x4 *__restrict__ wp, int64_t M, int Nout, int KS, int nt_n,
+    const float *__restrict__ bias, int gelu, uint16_t *__restrict__ out, int split) {
+  extern __shared__ u32x4 ring[];
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wd = wave & 3, wn = wave >> 2;
+  const int tn = blockIdx.x % nt_n, tm = blockIdx.x / nt_n;
+  const int total = KS >> 1;
+
+  // fetch: this wave moves fragments f = 4*wave .. 4*wave+3 of a stage (f = op*16 + ks*8 + a)
+  const int f_op = wave >> 2, f_ks = (wave >> 1) & 1, f_a0 = (wave & 1) * 4;
+  int pf_g = 0;
+  auto fetch = [&]() {
+    const int s = pf_g < total ? pf_g : total - 1;   // past the end: the last stage again, into a free slot
+    const u32x4 *src = (f_op ? ap + (size_t)(tm * 8 + f_a0) * KS * 64 : wp + (size_t)(tn * 8 + f_a0) * KS * 64) +
+                       (size_t)(s * 2 + f_ks) * 64 + lane;
+    u32x4 *dst = ring + (size_t)(pf_g & (kStages - 1)) * kStageU4 + (size_t)(wave * 4) * 64;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds(src + (size_t)i * KS * 64, dst + i * 64, 16, 0, 0);
+    ++pf_g;
+  };
+  const uint32_t ring_lane = lds_addr(&ring[lane]);
+  const uint32_t b_off = (uint32_t)((wn * 4) * 1024), a_off = (uint32_t)((16 + wd * 2) * 1024);
+  u32x4 fb[2][4], fa[2][2];
+  auto read_frags = [&](int g, int ks, u32x4(&b)[4], u32x4(&a)[2]) {
+    const uint32_t base = ring_lane + (uint32_t)((g & (kStages - 1)) * kStageU4 * 16 + ks * 8 * 1024);
+    lds_read4_async(b, base + b_off);
+    lds_read2_async(a, base + a_off);
+  };
+  auto wait_frags = [&](u32x4(&b)[4], u32x4(&a)[2]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(a[0]), "+v"(a[1])
+                 :
+                 : "memory");
+  };
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+  auto mma = [&](const u32x4(&b)[4], const u32x4(&a)[2]) {
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+      for (int ai = 0; ai < 2; ++ai)
+        acc[ai][bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[ai]),
+                                                             __builtin_bit_cast(bf16x8, b[bi]),
+                                                             acc[ai][bi], 0, 0, 0);
+  };
+
+#pragma unroll
+  for (int i = 0; i < kStages; ++i) fetch();                 // stages 0..3
+  asm volatile("s_waitcnt vmcnt(12)" ::: "memory");          // stage 0 has landed (this wave's part)
+  __builtin_amdgcn_s_barrier();
+  read_frags(0, 0, fb[0], fa[0]);
+  for (int g = 0; g < total; ++g) {
+    __builtin_amdgcn_sched_barrier(0);
+    wait_frags(fb[0], fa[0]);
+    read_frags(g, 1, fb[1], fa[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(fb[0], fa[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_frags(fb[1], fa[1]);
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");         // stage g+1 has landed; g+2, g+3 may be in flight
+    __builtin_amdgcn_s_barrier();
+    fetch();                                                 // stage g+4 -> slot of stage g
+    read_frags(g + 1, 0, fb[0], fa[0]);                      // past the end: a stale slot, never used
+    __builtin_amdgcn_sched_barrier(0);
+    mma(fb[1], fa[1]);
+  }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // nothing may land in LDS any more
+  __syncthreads();
+
+  // bias, activation, bf16, into the transposed tile: row = token, column = output channel
+  char *tile = (char *)ring;
+  const int ncol = wn * 128 + (lane & 31);
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const float bv = bias ? bias[tn * kTile + ncol + 32 * b] : 0.f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int mrow = wd * 64 + a * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+        float v = acc[a][b][r] + bv;
+        if (gelu) v = gelu_erf(v);
+        *(uint16_t *)(tile + (size_t)mrow * kOutPitch + (ncol + 32 * b) * 2) = (uint16_t)pack_bf16(v, 0.f);
+      }
+  }
+  __syncthreads();
+  // 16-byte pieces along the rows: 32 per row, 8192 per tile, 16 per thread
+  const int blk = (tn * kTile) / split, col0 = (tn * kTile) % split;   // a tile never straddles two blocks
+  uint16_t *ob = out + (size_t)blk * M * split + col0;
+#pragma unroll 4
+  for (int i = 0; i < 16; ++i) {
+    const int c = i * 512 + tid, mrow = c >> 5, piece = c & 31;
+    const int64_t m = (int64_t)tm * kTile + mrow;
+    if (m < M)
+      *(u32x4 *)(ob + (size_t)m * split + piece * 8) = *(const u32x4 *)(tile + (size_t)mrow * kOutPitch + piece * 16);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+struct BlockWs {
+  uint16_t *h, *qkv, *a, *u1, *u2, *h3;
+  u32x4 *apack, *wpack;
+  void *attn;
+  size_t bytes;
+  int64_t Mp;
+};
+
+static BlockWs carve_block(int64_t M, int C, int heads, int attn_dtype, char *base) {
+  BlockWs w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char *p = base ? base + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  };
+  w.Mp = (int64_t)align_up((size_t)M, kTile);
+  w.h = (uint16_t *)take((size_t)M * C * 2);
+  w.qkv = (uint16_t *)take((size_t)3 * M * C * 2);
+  w.a = (uint16_t *)take((size_t)M * C * 2);
+  w.u1 = (uint16_t *)take((size_t)M * C * 2);
+  w.u2 = (uint16_t *)take((size_t)M * C * 2);
+  w.h3 = (uint16_t *)take((size_t)M * 4 * C * 2);
+  w.apack = (u32x4 *)take((size_t)w.Mp * 4 * C * 2);
+  w.wpack = (u32x4 *)take((size_t)4 * C * C * 2);
+  w.attn = take(attn_ws_bytes(heads, M, attn_dtype));
+  w.bytes = off;
+  return w;
+}
+
+size_t block_ws_bytes(int64_t M, int C, int heads, int attn_dtype) {
+  return carve_block(M, C, heads, attn_dtype, nullptr).bytes;
+}
+
+// Y = A W^T + bias: packs both operands, then the tiled kernel
+static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W, int Nout,
+                         const float *bias, int gelu, uint16_t *out, int split, BlockWs &w,
+                         hipStream_t st) {
+  if (K % 32 != 0 || Nout % kTile != 0 || split % kTile != 0 || Nout % split != 0) return LV_ERR_SHAPE;
+  int rc;
+  if ((rc = launch_pack_rows(A, M, w.Mp, K, w.apack, st))) return rc;
+  if ((rc = launch_pack_rows(W, Nout, Nout, K, w.wpack, st))) return rc;
+  const size_t lds = (size_t)kTile * kOutPitch > (size_t)kStages * kStageU4 * 16 ? (size_t)kTile * kOutPitch
+                                                                                   : (size_t)kStages * kStageU4 * 16;
+  static bool lds_set = false;
+  if (!lds_set) {
+    if (hipFuncSetAttribute((const void *)k_gemm_bt, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+      return LV_ERR_HIP;
+    lds_set = true;
+  }
+  const int nt_n = Nout / kTile;
+  const int64_t nt_m = w.Mp / kTile;
+  if (nt_m * nt_n >= ((int64_t)1 << 31)) return LV_ERR_SHAPE;
+  hipLaunchKernelGGL(k_gemm_bt, dim3((unsigned)(nt_m * nt_n)), dim3(512), lds, st, w.apack, w.wpack,
+                     M, Nout, K / 16, nt_n, bias, gelu, out, split);
+  LV_HIP_CHECK_LAUNCH();
+  return LV_OK;
+}
+
+int launch_global_block(const uint16_t *z, int64_t M, int C, int heads, float scale, int attn_dtype,
+                        int qk_norm, const litevggt_block_weights &bw, uint16_t *delta, void *ws,
+                        hipStream_t st, hipEvent_t after_pack, hipEvent_t after_attn) {
+  if (C % kTile != 0) return LV_ERR_SHAPE;
+  BlockWs w = carve_block(M, C, heads, attn_dtype, (char *)ws);
+  int rc;
+  if ((rc = launch_layernorm(z, nullptr, bw.ln1_g, bw.ln1_b, M, C, w.h, st))) return rc;
+  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_qkv, 3 * C, bw.b_qkv, 0, w.qkv, C, w, st)))
+    return rc;
+  const uint16_t *q = w.qkv, *k = w.qkv + (size_t)M * C, *v = w.qkv + (size_t)2 * M * C;
+  if ((rc = launch_attn(q, k, v, w.a, M, heads, scale, attn_dtype, qk_norm, w.attn, st, after_pack)))
+    return rc;
+  if (after_attn && hipEventRecord(after_attn, st) != hipSuccess) return LV_ERR_HIP;
+  if ((rc = launch_linear(w.a, M, C, (const uint16_t *)bw.w_o, C, bw.b_o, 0, w.u1, C, w, st))) return rc;
+  if ((rc = launch_layernorm(z, w.u1, bw.ln2_g, bw.ln2_b, M, C, w.h, st))) return rc;
+  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_1, 4 * C, bw.b_1, 1, w.h3, 4 * C, w, st)))
+    return rc;
+  if ((rc = launch_linear(w.h3, M, 4 * C, (const uint16_t *)bw.w_2, C, bw.b_2, 0, w.u2, C, w, st)))
+    return rc;
+  const int64_t n16 = M * C / 8;
+  const unsigned grid = (unsigned)(((n16 + 255) / 256) < 65536 ? ((n16 + 255) / 256) : 65536);
+  hipLaunchKernelGGL(k_add_bf16, dim3(grid), dim3(256), 0, st, (const u32x4 *)w.u1, (const u32x4 *)w.u2,
+                     n16, (u32x4 *)delta);
+  LV_HIP_CHECK_LAUNCH();
+  return LV_OK;
+}
+
+}  // namespace lv

@@ -33,6 +33,20 @@ size_t match_ws_bytes(const Dims &d, const litevggt_plan_t &pl);
 int launch_match(const uint16_t *x, const Dims &d, const litevggt_plan_t &pl,
                  const litevggt_index &ix, float *best_sim, void *ws, hipStream_t st);
 
+// rows 0..n-1 of a row-major [n, C] bf16 matrix -> fragment-major (1 KB per 32 rows x 16
+// channels), padded with zero rows to n_pad
+int launch_pack_rows(const uint16_t *x, int64_t n, int64_t n_pad, int C, void *packed,
+                     hipStream_t st);
+
+// block.hip
+size_t block_ws_bytes(int64_t M, int C, int heads, int attn_dtype);
+// delta = Block(z) - z for M tokens; the two events (optional) are recorded around the
+// attention kernel inside the block
+int launch_global_block(const uint16_t *z, int64_t M, int C, int heads, float scale, int attn_dtype,
+                        int qk_norm, const litevggt_block_weights &bw, uint16_t *delta, void *ws,
+                        hipStream_t st, hipEvent_t after_pack = nullptr,
+                        hipEvent_t after_attn = nullptr);
+
 // merge.hip
 int launch_merge(const uint16_t *x, const Dims &d, int64_t M, const litevggt_index &ix,
                  uint16_t *z, hipStream_t st);

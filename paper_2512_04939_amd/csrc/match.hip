@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void k_inv_norm(const uint16_t *__restrict__ x
 
 // Gather token rows into fragment-major order: fragment (tile t of 32 rows, k-step s of 16
 // channels) is 1 KB contiguous, lane (h*32 + r) holds row r, channels 16s+8h .. 16s+8h+7.
-// Rows beyond n are zero.  inv_out (optional) receives the rows' inverse norms, 0 beyond n;
+// idx_of == NULL packs rows 0..n-1 in place order.  Rows beyond n are zero.  inv_out (optional) receives the rows' inverse norms, 0 beyond n;
 // zero256 (optional) is a 256-word array to clear.
 __global__ __launch_bounds__(256) void k_pack_rows(const uint16_t *__restrict__ x,
                                                    const int32_t *__restrict__ idx_of,
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void k_pack_rows(const uint16_t *__restrict__ 
   u32x4 w = {0u, 0u, 0u, 0u};
   int row = -1;
   if (j < n) {
-    row = idx_of[j];
+    row = idx_of ? idx_of[j] : j;
     w = ((const u32x4 *)(x + (size_t)row * C))[c];
   }
   const int t = j >> 5, r = j & 31, s = c >> 1, h = c & 1;
@@ -74,6 +74,17 @@ __device__ __forceinline__ void top2_insert_any(Top2 &t, float v, int i) {
     t.v2 = v;
     t.i2 = i;
   }
+}
+
+int launch_pack_rows(const uint16_t *x, int64_t n, int64_t n_pad, int C, void *packed, hipStream_t st) {
+  const int64_t pk = n_pad * (C / 8);
+  if (n_pad >= ((int64_t)1 << 31) || (pk + 255) / 256 >= ((int64_t)1 << 31)) return LV_ERR_SHAPE;
+  hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)((pk + 255) / 256)), dim3(256), 0, st, x,
+                     (const int32_t *)nullptr, (const float *)nullptr, (int)n, (int)n_pad, C,
+                     (u32x4 *)packed,
+                     (float *)nullptr, (uint32_t *)nullptr);
+  LV_HIP_CHECK_LAUNCH();
+  return LV_OK;
 }
 
 // ---------------------------------------------------------------------------------

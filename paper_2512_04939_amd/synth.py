@@ -270,3 +270,28 @@ def random_qkv(n_tokens: int, heads: int, head_dim: int, seed: int, scale: float
     rng = _stream(seed, 50)
     return tuple((scale * rng.standard_normal((n_tokens, heads, head_dim), dtype=np.float32))
                  for _ in range(3))
+
+
+# ----------------------------------------------------------------------------
+# synthetic weights of the transformer block around the global attention
+# ----------------------------------------------------------------------------
+def block_weights(dim: int, seed: int = 0) -> dict:
+    """Seeded random weights of one pre-norm block (no trained weights exist here): matrices
+    [out, in] ~ N(0, 1/in) rounded to bf16 (returned as float32 holding bf16 values), the two
+    residual-branch outputs (w_o, w_2) scaled by 0.5 so a stack of blocks grows slowly; biases
+    and LayerNorm offsets ~ N(0, 0.02^2), LayerNorm gains 1 + N(0, 0.1^2); vectors float32."""
+    rng = np.random.Generator(np.random.PCG64([seed, 0xB10C]))
+
+    def mat(o, i, gain=1.0):
+        w = (rng.standard_normal((o, i)) * (gain / np.sqrt(i))).astype(np.float32)
+        return bf16_bits_to_f32(f32_to_bf16_bits(w))
+
+    def vec(n, std, mean=0.0):
+        return (mean + std * rng.standard_normal(n)).astype(np.float32)
+
+    return dict(ln1_g=vec(dim, 0.1, 1.0), ln1_b=vec(dim, 0.02),
+                w_qkv=mat(3 * dim, dim), b_qkv=vec(3 * dim, 0.02),
+                w_o=mat(dim, dim, 0.5), b_o=vec(dim, 0.02),
+                ln2_g=vec(dim, 0.1, 1.0), ln2_b=vec(dim, 0.02),
+                w_1=mat(4 * dim, dim), b_1=vec(4 * dim, 0.02),
+                w_2=mat(dim, 4 * dim, 0.5), b_2=vec(dim, 0.02))

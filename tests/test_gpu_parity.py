@@ -458,6 +458,66 @@ def test_layers_run_fp8_attention(B):
     assert max_rel_err(got, emu) <= 2e-2
 
 
+# ------------------------------------------------- the transformer block around the attention
+def _dev_block_weights(B, w):
+    import torch
+    t = {k: (f32_to_dev_bf16(v) if v.ndim == 2 else torch.from_numpy(v).cuda()) for k, v in w.items()}
+    return t, B.block_weights(t)
+
+
+@pytest.mark.parametrize("n,dim,heads,qk_norm", [(300, 256, 4, 1), (777, 256, 4, 0), (520, 1024, 16, 1)])
+def test_global_block(B, n, dim, heads, qk_norm):
+    """LN -> qkv projection -> attention -> output projection -> LN -> GELU MLP against the
+    oracle; n is ragged against the 256-row tiles, dim 1024 runs 4-16 output tiles per row."""
+    import torch
+    w = synth.block_weights(dim, seed=n)
+    tens, bw = _dev_block_weights(B, w)
+    rng = np.random.default_rng(n)
+    zb = synth.f32_to_bf16_bits((rng.standard_normal((n, dim)) * 1.5).astype(np.float32))
+    z = synth.bf16_bits_to_f32(zb).astype(np.float64)
+    wl = small_workload(frames=1, grid=4, dim=dim, heads=heads)
+    po, ph = oracle_params(wl, qk_norm=bool(qk_norm)), hip_params(wl, qk_norm=qk_norm)
+    want = O.global_block(z, {k: v.astype(np.float64) for k, v in w.items()}, po, _store_bf16)
+    delta = torch.zeros(n, dim, dtype=torch.bfloat16, device="cuda")
+    ws = B.alloc_ws(B.litevggt_global_block_ws_bytes(ph, n))
+    B.litevggt_global_block(ph, n, to_dev_bf16(zb), bw, delta, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(dev_bf16_to_f64(delta), want) <= BF16_TOL
+
+
+def test_layers_run_with_block_and_frame_attention(B):
+    """The faithful stack: merged global block, unmerge, frame attention; teacher-forced."""
+    import torch
+    wl = synth.workload("tiny2")
+    bits, xf, im = stored_inputs(wl)
+    w = synth.block_weights(wl.dim, seed=5)
+    tens, bw = _dev_block_weights(B, w)
+    po = oracle_params(wl, frame_attn=True, block={k: v.astype(np.float64) for k, v in w.items()})
+    ph = hip_params(wl, frame_attn=1, block=bw)
+    pl = B.litevggt_plan(ph)
+    trace = []
+    ref_out, ref_log = O.layers_run(im, xf, po, 2, store=_store_bf16, trace=trace)
+    im_dev = torch.from_numpy(im).cuda()
+    grad = torch.zeros(wl.frames, wl.patches, device="cuda")
+    score = torch.zeros(wl.frames, wl.patches, device="cuda")
+    ws = B.alloc_ws(pl.ws_bytes)
+    p1 = hip_params(wl, frame_attn=1, block=bw, refresh_interval=1)
+    for t in trace:
+        x_dev = f32_to_dev_bf16(t["x_in"].astype(np.float32))
+        ib = B.alloc_index(pl)
+        B.litevggt_layers_run(p1, 1, im_dev, x_dev, ib, grad, score, ws)
+        torch.cuda.synchronize()
+        idx = O.compute_index(im, t["x_in"], po)[0]
+        exp = O.frame_layer(O.global_layer(t["x_in"], idx, po, _store_bf16), po, _store_bf16)
+        assert max_rel_err(dev_bf16_to_f64(x_dev), exp) <= BF16_TOL
+    x_dev = to_dev_bf16(bits)
+    ib = B.alloc_index(pl)
+    log = B.litevggt_layers_run(ph, 2, im_dev, x_dev, ib, grad, score, ws)
+    torch.cuda.synchronize()
+    assert log == ref_log
+    assert max_rel_err(dev_bf16_to_f64(x_dev), ref_out) <= BF16_TOL
+
+
 # ------------------------------------------------------------------------- frame attention
 @pytest.mark.parametrize("qk_norm", [1, 0])
 @pytest.mark.parametrize("frames,grid,heads", [(3, 37, 4), (5, 6, 2), (2, 16, 16)])

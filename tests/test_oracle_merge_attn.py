@@ -277,3 +277,57 @@ def test_frame_layer_is_residual_plus_frame_attention():
     # constant value rows inside a frame: attention returns them, the layer doubles them
     xc = np.repeat(rng.standard_normal((2, 1, 64)), p.tokens_per_frame, axis=0).reshape(-1, 64)
     assert np.abs(O.frame_layer(xc, p) - 2 * xc).max() < 1e-12
+
+
+# ---------------------------------------------------------------------------
+# the transformer block around the global attention
+# ---------------------------------------------------------------------------
+def test_layer_norm_gelu_linear_against_torch():
+    import torch
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((7, 96)) * 3 + 1
+    g, b = rng.standard_normal(96), rng.standard_normal(96)
+    ref = torch.nn.functional.layer_norm(torch.from_numpy(x), (96,), torch.from_numpy(g),
+                                         torch.from_numpy(b), eps=O.LN_EPS).numpy()
+    assert np.abs(O.layer_norm(x, g, b) - ref).max() < 1e-12
+    y = O.layer_norm(x, np.ones(96), np.zeros(96))
+    assert np.abs(y.mean(axis=1)).max() < 1e-12 and np.abs(y.var(axis=1) - 1).max() < 1e-5
+    assert np.abs(O.gelu(x) - torch.nn.functional.gelu(torch.from_numpy(x)).numpy()).max() < 1e-12
+    assert O.gelu(np.array([0.0]))[0] == 0 and abs(O.gelu(np.array([10.0]))[0] - 10) < 1e-12
+    w, bias = rng.standard_normal((5, 96)), rng.standard_normal(5)
+    ref = torch.nn.functional.linear(torch.from_numpy(x), torch.from_numpy(w), torch.from_numpy(bias)).numpy()
+    assert np.abs(O.linear(x, w, bias) - ref).max() < 1e-12
+
+
+def test_global_block_against_a_torch_block():
+    """The block assembled from torch modules with the same weights (float64)."""
+    import torch
+    C, heads, n = 128, 2, 37
+    w = {k: v.astype(np.float64) for k, v in synth.block_weights(C, seed=3).items()}
+    rng = np.random.default_rng(7)
+    z = rng.standard_normal((n, C))
+    p = O.Params(frames=1, grid_h=1, grid_w=1, dim=C, heads=heads)
+    t = {k: torch.from_numpy(v) for k, v in w.items()}
+    zt = torch.from_numpy(z)
+    h = torch.nn.functional.layer_norm(zt, (C,), t["ln1_g"], t["ln1_b"], eps=O.LN_EPS)
+    q, k, v = torch.nn.functional.linear(h, t["w_qkv"], t["b_qkv"]).chunk(3, dim=1)
+    sp = lambda a: a.reshape(n, heads, 64).permute(1, 0, 2)
+    a = torch.nn.functional.scaled_dot_product_attention(sp(q), sp(k), sp(v)).permute(1, 0, 2).reshape(n, C)
+    u1 = torch.nn.functional.linear(a, t["w_o"], t["b_o"])
+    h2 = torch.nn.functional.layer_norm(zt + u1, (C,), t["ln2_g"], t["ln2_b"], eps=O.LN_EPS)
+    u2 = torch.nn.functional.linear(torch.nn.functional.gelu(torch.nn.functional.linear(h2, t["w_1"], t["b_1"])),
+                                    t["w_2"], t["b_2"])
+    assert np.abs(O.global_block(z, w, p) - (u1 + u2).numpy()).max() < 1e-11
+    # q, k normalisation enters only through the attention inputs
+    pn = O.Params(frames=1, grid_h=1, grid_w=1, dim=C, heads=heads, qk_norm=True)
+    assert np.abs(O.global_block(z, w, pn) - O.global_block(z, w, p)).max() > 1e-6
+
+
+def test_block_layer_at_ratio_zero_is_the_block_on_the_unmerged_sequence():
+    wl = synth.workload("tiny2", merge_ratio=0.0)
+    p = O.Params(frames=wl.frames, grid_h=16, grid_w=16, dim=256, heads=4, merge_ratio=0.0,
+                 block={k: v.astype(np.float64) for k, v in synth.block_weights(256, 1).items()})
+    gen = synth.Generator(wl)
+    x, im = synth.stored_to_f32(gen.tokens()).astype(np.float64), gen.images()
+    idx = O.compute_index(im, x, p)[0]
+    assert np.abs(O.global_layer(x, idx, p) - (x + O.global_block(x, p.block, p))).max() < 1e-12
