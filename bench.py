@@ -51,7 +51,7 @@ def parse_args():
     ap.add_argument("--no-unmerged", action="store_true",
                     help="skip the one-launch unmerged attention baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-frames", type=int, default=24,
+    ap.add_argument("--cpu-frames", type=int, default=96,
                     help="frames of the sub-sequence the CPU oracle is timed on")
     return ap.parse_args()
 

@@ -1,0 +1,127 @@
+"""Parity at the benchmark's full size (1000 frames, N = 1,374,000, M = 143,232) in the launch
+configuration bench.py times: every step runs on the whole sequence, the oracle checks
+sampled outputs it can compute one by one, plus structural properties that hold at any size."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+from helpers import hip_params, max_rel_err, oracle_params
+from oracle import litevggt_oracle as O
+from paper_2512_04939_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL = 2e-2
+
+
+def _f64(bits_rows: np.ndarray) -> np.ndarray:
+    return synth.bf16_bits_to_f32(bits_rows).astype(np.float64)
+
+
+def _host_bits(t) -> np.ndarray:
+    import torch
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def test_full_size_steps_against_sampled_oracle():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2512_04939_amd import binding as B
+    wl = synth.workload("f1000")
+    po, ph = oracle_params(wl), hip_params(wl)
+    pl = B.litevggt_plan(ph)
+    F, T, P, S, C, heads = wl.frames, wl.tokens_per_frame, wl.patches, wl.n_special, wl.dim, wl.heads
+    N, M = pl.N, pl.M
+    assert (N, M, pl.n_dst, pl.n_src) == (1374000, 143232, 101269, 1230768)
+    gen = synth.Generator(wl)
+    bits = gen.tokens(threads=16)                        # [N, C] bf16 bit patterns
+    x = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    im = torch.empty(F, 3, wl.img_h, wl.img_w, dtype=torch.float32, device="cuda")
+    for f0 in range(0, F, 50):
+        fr = range(f0, min(F, f0 + 50))
+        im[f0:f0 + len(fr)].copy_(torch.from_numpy(gen.images(fr)))
+    rng = np.random.default_rng(2024)
+
+    # ---- every step of one layer with a refresh, whole sequence
+    ib = B.alloc_index(pl)
+    ws = B.alloc_ws(pl.ws_bytes)
+    grad = torch.zeros(F, P, device="cuda")
+    score = torch.zeros(F, P, device="cuda")
+    z = torch.empty(M, C, dtype=torch.bfloat16, device="cuda")
+    y = torch.empty_like(z)
+    out = torch.empty_like(x)
+    B.litevggt_importance(ph, im, x, grad, True, score, ws)
+    B.litevggt_select_anchors(ph, score, ib)
+    B.litevggt_match(ph, x, ib, None, ws)
+    B.litevggt_merge(ph, x, ib, z)
+    B.litevggt_global_attn(ph, M, z, z, z, y, ws)
+    B.litevggt_unmerge(ph, y, ib, x, out)
+    torch.cuda.synchronize()
+
+    # ---- importance: sampled frames (the map of a frame depends on that frame only)
+    frames = np.array([0, 1, 499, 998, 999])
+    rows = np.concatenate([np.arange(f * T, (f + 1) * T) for f in frames])
+    psub = oracle_params(synth.Workload(**{**wl.__dict__, "frames": len(frames)}))
+    want, _ = O.importance(gen.images(frames), _f64(bits[rows]), psub)
+    got = score[torch.from_numpy(frames).cuda()].cpu().numpy().astype(np.float64)
+    assert np.abs(got - want).max() <= 2e-5
+
+    # ---- partition: the oracle's rule on the GPU's own scores, frame 0 plus sampled frames
+    sel = O.select_anchors(score[torch.from_numpy(frames).cuda()].cpu().numpy(), psub)
+    role = ib.role.cpu().numpy().reshape(F, T)
+    assert np.array_equal(role[frames].ravel(), sel["role"])
+    src_idx = ib.src_idx.cpu().numpy()[:pl.n_src].astype(np.int64)
+    dst_idx = ib.dst_idx.cpu().numpy()[:pl.n_dst].astype(np.int64)
+    kept_idx = ib.kept_idx.cpu().numpy().astype(np.int64)
+    flat = role.ravel()
+    assert np.array_equal(np.flatnonzero(flat == O.ROLE_SRC), src_idx)
+    assert np.array_equal(np.flatnonzero(flat == O.ROLE_DST), dst_idx)
+    assert np.array_equal(np.flatnonzero(flat != O.ROLE_SRC), kept_idx)
+
+    # ---- match: sampled src tokens against all 101,269 dst tokens
+    pick = np.sort(rng.choice(pl.n_src, size=96, replace=False))
+    small = _f64(bits[np.concatenate([dst_idx, src_idx[pick]])])
+    mt = O.match(small, np.arange(pl.n_dst), pl.n_dst + np.arange(len(pick)))
+    want_anchor = dst_idx[mt["anchor"]]
+    anchor_of = ib.anchor_of.cpu().numpy().astype(np.int64)
+    got_anchor = anchor_of[src_idx[pick]]
+    differ = got_anchor != want_anchor
+    assert np.all((mt["best"] - mt["second"])[differ] < 1e-6), "disagreement outside near-ties"
+    assert differ.sum() <= 2
+    assert np.array_equal(anchor_of[kept_idx], kept_idx)
+
+    # ---- index structure at full size
+    slot_of = ib.slot_of.cpu().numpy().astype(np.int64)
+    goff = ib.group_off.cpu().numpy().astype(np.int64)
+    gmem = ib.group_mem.cpu().numpy().astype(np.int64)
+    assert goff[0] == 0 and goff[-1] == N and np.all(np.diff(goff) >= 1)
+    assert np.array_equal(np.sort(gmem), np.arange(N))                 # every token in one group
+    assert np.array_equal(slot_of[gmem], np.repeat(np.arange(M), np.diff(goff)))
+    assert np.array_equal(slot_of[kept_idx], np.arange(M))
+    assert np.array_equal(slot_of, slot_of[anchor_of])
+    inside = np.ones(N, dtype=bool)
+    inside[goff[1:-1]] = False                                          # group starts
+    assert np.all(np.diff(gmem)[inside[1:]] > 0)                        # ascending inside a group
+
+    # ---- merge: the largest group and random slots
+    sizes = np.diff(goff)
+    slots = np.unique(np.concatenate([[int(np.argmax(sizes)), 0, M - 1], rng.choice(M, size=40, replace=False)]))
+    zb = _host_bits(z)
+    want_z = np.stack([_f64(bits[gmem[goff[m]:goff[m + 1]]]).mean(axis=0) for m in slots])
+    assert max_rel_err(_f64(zb[slots]), want_z) <= BF16_TOL
+
+    # ---- attention: sampled query rows of two heads over all M keys (inputs: the GPU's z)
+    qrows = np.sort(rng.choice(M, size=12, replace=False))
+    yb = _host_bits(y)
+    for head in (3, 12):
+        cols = slice(head * 64, (head + 1) * 64)
+        zh = _f64(zb[:, cols]).reshape(M, 1, 64)
+        qk = O.round_bf16(O.qk_normalize(zh))
+        want_y = O.attention(qk, qk, zh, rows=qrows).reshape(len(qrows), 64)
+        assert max_rel_err(_f64(yb[qrows][:, cols]), want_y) <= BF16_TOL
+
+    # ---- unmerge with the fused residual: bit-exact on sampled tokens
+    toks = np.sort(rng.choice(N, size=4096, replace=False))
+    s = synth.bf16_bits_to_f32(bits[toks]) + synth.bf16_bits_to_f32(yb[slot_of[toks]])
+    assert np.array_equal(_host_bits(out[torch.from_numpy(toks).cuda()]), synth.f32_to_bf16_bits(s))
