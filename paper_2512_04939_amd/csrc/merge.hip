@@ -27,30 +27,24 @@ template <int CPL>
 __device__ __forceinline__ void sum_rows(const uint16_t *__restrict__ x,
                                          const int32_t *__restrict__ group_mem, int lo, int hi,
                                          int C, int nch, int lane, float (&a)[CPL][8]) {
-  int j = lo;
-  for (; j + 8 <= hi; j += 8) {
+  // batches of 8 rows; the last batch is masked (lo, hi are wave-uniform), so its loads are
+  // issued together as well instead of one after the other
+  for (int j = lo; j < hi; j += 8) {
     u32x4 w[8][CPL];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const int r = group_mem[j + u];
+      const bool on = j + u < hi;
+      const int r = on ? group_mem[j + u] : 0;
 #pragma unroll
       for (int c = 0; c < CPL; ++c) {
         const int ch = lane + 64 * c;
-        w[u][c] = ch < nch ? ((const u32x4 *)(x + (size_t)r * C))[ch] : u32x4{0u, 0u, 0u, 0u};
+        w[u][c] = (on && ch < nch) ? ((const u32x4 *)(x + (size_t)r * C))[ch] : u32x4{0u, 0u, 0u, 0u};
       }
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u)
 #pragma unroll
       for (int c = 0; c < CPL; ++c) acc8(a[c], w[u][c]);
-  }
-  for (; j < hi; ++j) {
-    const int r = group_mem[j];
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-      const int ch = lane + 64 * c;
-      if (ch < nch) acc8(a[c], ((const u32x4 *)(x + (size_t)r * C))[ch]);
-    }
   }
 }
 
