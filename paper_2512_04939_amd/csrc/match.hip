@@ -190,6 +190,13 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                                                __builtin_bit_cast(bf16x8, b[bi]),
                                                                acc[ai][bi], 0, 0, 0);
     };
+    auto mma_pair = [&](const u32x4(&b)[4], const u32x4(&a)[2], int bi) {   // the two MFMAs of column block bi
+#pragma unroll
+      for (int ai = 0; ai < 2; ++ai)
+        acc[ai][bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[ai]),
+                                                             __builtin_bit_cast(bf16x8, b[bi]),
+                                                             acc[ai][bi], 0, 0, 0);
+    };
     // Fold the eight finished 32x32 tiles into the running top-2 of this lane's four columns.
     // Almost no element beats its column's second best once a few tiles have been seen, but
     // with 64 columns per wave "some lane of the wave has such an element in this tile" is true
@@ -241,15 +248,25 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       __builtin_amdgcn_sched_barrier(0);
       mma(fb[0], fa[0]);
       // k-step 1 of stage g: its fragments are in registers, so the slot of stage g is free once
-      // every wave is here; stage g+1 is published by the same barrier
+      // every wave is here; stage g+1 is published by the same barrier.  The barrier, the
+      // fetch instructions and the fragment reads sit between pairs of MFMAs, so that the MFMA
+      // pipe still has queued work from this wave while it does them.
       __builtin_amdgcn_sched_barrier(0);
       wait_frags(fb[1], fa[1]);
+      mma_pair(fb[1], fa[1], 0);
+      __builtin_amdgcn_sched_barrier(0);
       asm volatile("s_waitcnt vmcnt(8)" ::: "memory");         // stage g+1 has landed; g+2, g+3 may be in flight
       __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      mma_pair(fb[1], fa[1], 1);
+      __builtin_amdgcn_sched_barrier(0);
       fetch();                                                 // stage g+4 -> slot of stage g
+      __builtin_amdgcn_sched_barrier(0);
+      mma_pair(fb[1], fa[1], 2);
+      __builtin_amdgcn_sched_barrier(0);
       read_frags(g + 1, 0, fb[0], fa[0]);                      // past the end: a stale slot, never used
       __builtin_amdgcn_sched_barrier(0);
-      mma(fb[1], fa[1]);
+      mma_pair(fb[1], fa[1], 3);
       if (++sidx == SPT) {
         // Team step: the workgroups of a team finish a dst tile at about the same time and
         // start the next one together, so that what one of them fetches is still in their
