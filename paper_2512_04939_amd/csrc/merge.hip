@@ -22,27 +22,30 @@ __device__ __forceinline__ void acc8(float (&a)[8], const u32x4 w) {
 #endif
 constexpr int kCoopSize = LV_MERGE_COOP;   // groups larger than this are summed by all 4 waves of a workgroup
 
-// acc += rows group_mem[lo..hi) of x, this lane's chunks; 8 member rows in flight per lane.
-template <int CPL>
+// acc += rows group_mem[lo..hi) of x, this lane's chunks; R member rows in flight per lane.
+// Rows are taken in batches of R; the last batch is masked (lo, hi are wave-uniform), so its
+// loads are issued together as well.  The member indices of a batch are fetched while the rows
+// of the batch before it are in flight, so a batch costs one memory round trip, not two.
+template <int CPL, int R>
 __device__ __forceinline__ void sum_rows(const uint16_t *__restrict__ x,
                                          const int32_t *__restrict__ group_mem, int lo, int hi,
                                          int C, int nch, int lane, float (&a)[CPL][8]) {
-  // batches of 8 rows; the last batch is masked (lo, hi are wave-uniform), so its loads are
-  // issued together as well instead of one after the other
-  for (int j = lo; j < hi; j += 8) {
-    u32x4 w[8][CPL];
+  int r[R];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const bool on = j + u < hi;
-      const int r = on ? group_mem[j + u] : 0;
+  for (int u = 0; u < R; ++u) r[u] = lo + u < hi ? group_mem[lo + u] : -1;
+  for (int j = lo; j < hi; j += R) {
+    u32x4 w[R][CPL];
+#pragma unroll
+    for (int u = 0; u < R; ++u)
 #pragma unroll
       for (int c = 0; c < CPL; ++c) {
         const int ch = lane + 64 * c;
-        w[u][c] = (on && ch < nch) ? ((const u32x4 *)(x + (size_t)r * C))[ch] : u32x4{0u, 0u, 0u, 0u};
+        w[u][c] = (r[u] >= 0 && ch < nch) ? ((const u32x4 *)(x + (size_t)r[u] * C))[ch] : u32x4{0u, 0u, 0u, 0u};
       }
-    }
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
+    for (int u = 0; u < R; ++u) r[u] = j + R + u < hi ? group_mem[j + R + u] : -1;
+#pragma unroll
+    for (int u = 0; u < R; ++u)
 #pragma unroll
       for (int c = 0; c < CPL; ++c) acc8(a[c], w[u][c]);
   }
@@ -65,54 +68,63 @@ __device__ __forceinline__ void store_mean(uint16_t *__restrict__ z, int m, int 
   }
 }
 
-// A workgroup (4 waves) owns 4 consecutive merged slots; lane l owns the 16-byte chunks l,
-// l+64, ... of a row.  A slot with at most kCoopSize members is summed by one wave in
-// ascending member order.  Larger groups (a heavy tail: 1 % of the slots hold a third of the
-// tokens) are summed by all 4 waves, each taking a contiguous quarter of the members, and the
-// four partial sums are added in wave order -- the order of additions depends only on the
-// group size, so results are reproducible.
+// Slots with at most kCoopSize members are summed by one wave each, in ascending member
+// order (a workgroup takes 4 consecutive slots).  Larger groups (a heavy tail: a few percent of
+// the slots hold most of the tokens once the features have been through some layers) are
+// summed by all 4 waves of a workgroup, each taking a contiguous quarter of the members, and
+// the four partial sums are added in wave order -- the order of additions depends only on the
+// group size, so results are reproducible.  The large groups are the long jobs, so they are
+// started first: workgroups 0 .. nb0-1 scan kScan slots each (nb0 apart) and sum the large
+// groups among them, workgroups nb0 .. take the small ones behind them.
+constexpr int kScan = 64;
+
 template <int CPL>
 __global__ __launch_bounds__(256) void k_merge(const uint16_t *__restrict__ x,
                                                const int32_t *__restrict__ group_off,
                                                const int32_t *__restrict__ group_mem, int M,
-                                               int C, uint16_t *__restrict__ z) {
+                                               int C, int nb0, uint16_t *__restrict__ z) {
   __shared__ float part[3][CPL * 64 * 8];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nch = C >> 3;
-  const int m0 = blockIdx.x * 4;
-  for (int s = 0; s < 4; ++s) {          // cooperative pass over the workgroup's large groups
-    const int m = m0 + s;
-    if (m >= M) break;
-    const int b = group_off[m], e = group_off[m + 1], n = e - b;
-    if (n <= kCoopSize) continue;
-    const int per = (n + 3) >> 2;
-    const int lo = min(b + wave * per, e), hi = min(lo + per, e);
-    float a[CPL][8];
-#pragma unroll
-    for (int c = 0; c < CPL; ++c)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) a[c][i] = 0.f;
-    sum_rows<CPL>(x, group_mem, lo, hi, C, nch, lane, a);
-    if (wave > 0) {
+  if ((int)blockIdx.x < nb0) {           // cooperative pass over the large groups of kScan slots
+    const int ms = blockIdx.x + lane * nb0;   // strided: neighbouring slots (the all-dst first frame) hold the largest groups
+    const int bl = ms < M ? group_off[ms] : 0, el = ms < M ? group_off[ms + 1] : 0;
+    uint64_t big = __builtin_amdgcn_ballot_w64(el - bl > kCoopSize);   // same in every wave
+    while (big) {
+      const int s = __builtin_ctzll(big);
+      big &= big - 1;
+      const int m = blockIdx.x + s * nb0;
+      const int b = __builtin_amdgcn_readlane(bl, s), e = __builtin_amdgcn_readlane(el, s), n = e - b;
+      const int per = (n + 3) >> 2;
+      const int lo = min(b + wave * per, e), hi = min(lo + per, e);
+      float a[CPL][8];
 #pragma unroll
       for (int c = 0; c < CPL; ++c)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) part[wave - 1][(c * 8 + i) * 64 + lane] = a[c][i];
-    }
-    __syncthreads();
-    if (wave == 0) {
-#pragma unroll
-      for (int w = 0; w < 3; ++w)
+        for (int i = 0; i < 8; ++i) a[c][i] = 0.f;
+      sum_rows<CPL, 16>(x, group_mem, lo, hi, C, nch, lane, a);
+      if (wave > 0) {
 #pragma unroll
         for (int c = 0; c < CPL; ++c)
 #pragma unroll
-          for (int i = 0; i < 8; ++i) a[c][i] += part[w][(c * 8 + i) * 64 + lane];
-      store_mean<CPL>(z, m, C, nch, lane, a, 1.0f / (float)n);
+          for (int i = 0; i < 8; ++i) part[wave - 1][(c * 8 + i) * 64 + lane] = a[c][i];
+      }
+      __syncthreads();
+      if (wave == 0) {
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+#pragma unroll
+          for (int c = 0; c < CPL; ++c)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) a[c][i] += part[w][(c * 8 + i) * 64 + lane];
+        store_mean<CPL>(z, m, C, nch, lane, a, 1.0f / (float)n);
+      }
+      __syncthreads();
     }
-    __syncthreads();
+    return;
   }
-  const int m = m0 + wave;               // own slot, if small
+  const int m = ((int)blockIdx.x - nb0) * 4 + wave;   // own slot, if small
   if (m < M) {
     const int b = group_off[m], e = group_off[m + 1];
     if (e - b <= kCoopSize) {
@@ -121,7 +133,7 @@ __global__ __launch_bounds__(256) void k_merge(const uint16_t *__restrict__ x,
       for (int c = 0; c < CPL; ++c)
 #pragma unroll
         for (int i = 0; i < 8; ++i) a[c][i] = 0.f;
-      sum_rows<CPL>(x, group_mem, b, e, C, nch, lane, a);
+      sum_rows<CPL, 8>(x, group_mem, b, e, C, nch, lane, a);
       store_mean<CPL>(z, m, C, nch, lane, a, 1.0f / (float)(e - b));
     }
   }
@@ -130,10 +142,11 @@ __global__ __launch_bounds__(256) void k_merge(const uint16_t *__restrict__ x,
 int launch_merge(const uint16_t *x, const Dims &d, int64_t M, const litevggt_index &ix,
                  uint16_t *z, hipStream_t st) {
   const int cpl = (d.C / 8 + 63) / 64;
-  const unsigned grid = (unsigned)((M + 3) / 4);
+  const int nb0 = (int)((M + kScan - 1) / kScan);
+  const unsigned grid = (unsigned)(nb0 + (M + 3) / 4);
 #define LV_MERGE(CPL)                                                                       \
   hipLaunchKernelGGL(k_merge<CPL>, dim3(grid), dim3(256), 0, st, x, ix.group_off, ix.group_mem, \
-                     (int)M, d.C, z)
+                     (int)M, d.C, nb0, z)
   switch (cpl) {
     case 1: LV_MERGE(1); break;
     case 2: LV_MERGE(2); break;
