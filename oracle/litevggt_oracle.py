@@ -12,8 +12,9 @@ docstring.  No blocking, fusion or re-ordering beyond what the definition says.
 
 Pins (tests/test_oracle_*.py, all CPU): closed forms for the Sobel/variance maps,
 scipy.ndimage routines for the filters, a sparse averaging matrix for the merge,
-torch's scaled_dot_product_attention for the attention core, pure-Python brute
-force for selection and matching, the paper's recompute-count table for the
+torch's scaled_dot_product_attention for the attention core, torch's float8_e4m3fn
+casts for the FP8 rounding and linear layers, closed forms for the delayed-scaling
+history, pure-Python brute force for selection and matching, the paper's recompute-count table for the
 cache schedule.  The ratio -> (cell size, number of GA tokens) rule is a
 definition of this build, not of the paper: **parity unpinned** for that rule
 beyond its own closed-form counts.
@@ -52,6 +53,9 @@ class Params:
     block: Optional[dict] = None  # layer loop: weights of global_block, or None (projection-free attention)
     qk_norm: bool = False       # layer loop: RMS-normalise q and k per head (see global_layer)
     attn_fp8: bool = False      # layer loop: FP8 E4M3 attention emulation (see attention_fp8)
+    linear_fp8: bool = False    # block: FP8 E4M3 linear layers (see linear_fp8)
+    fp8_history: Optional[list] = None  # block: four Fp8History (inputs of qkv, out-proj, fc1, fc2)
+                                        # = delayed scaling; None = scale from the tensor itself
 
     @property
     def patches(self) -> int:
@@ -486,25 +490,84 @@ def linear(x: np.ndarray, w: np.ndarray, b: np.ndarray) -> np.ndarray:
     return np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T + b
 
 
+FP8_MAX = 448.0
+FP8_HISTORY = 80
+
+
+class Fp8History:
+    """Delayed-scaling state of one quantised tensor (supplementary "FP8 Quantization Details":
+    E4M3, delayed scaling, an amax history of 80 steps reduced with max).  The scale used at a
+    step comes from the largest amax recorded in the previous (up to) 80 steps, not from the
+    tensor being quantised; that tensor's amax is recorded afterwards.  A step is one use of
+    the linear layer.  Before anything is recorded (history all zero) the scale is 1."""
+
+    def __init__(self, length: int = FP8_HISTORY):
+        self.hist = np.zeros(length, dtype=np.float32)
+        self.step = 0
+
+    def amax(self) -> np.float32:
+        return self.hist.max()
+
+    def record(self, amax) -> None:
+        self.hist[self.step % len(self.hist)] = amax
+        self.step += 1
+
+
+def fp8_inv_scale(amax) -> np.float32:
+    """448 / amax in float32 (the kernel's precision: it decides the codes); 1 for amax = 0."""
+    amax = np.float32(amax)
+    return np.float32(FP8_MAX) / amax if amax > 0 else np.float32(1.0)
+
+
+def quantize_e4m3_at(a: np.ndarray, inv_scale: np.float32) -> np.ndarray:
+    """E4M3 values of a * inv_scale: the product in float32, then nearest-even, saturating."""
+    v = np.asarray(a, dtype=np.float32) * np.float32(inv_scale)
+    return round_e4m3(v.astype(np.float64))
+
+
+def linear_fp8(x: np.ndarray, w: np.ndarray, b: np.ndarray,
+               hist: Optional[Fp8History] = None) -> np.ndarray:
+    """x w^T + b with both operands quantised per tensor to FP8 E4M3 and the products
+    accumulated exactly (the paper's FP8 inference: the aggregator's linear modules, E4M3).
+    hist None: "current" scaling, inv_scale = 448 / amax(x).  With a history: delayed scaling
+    (see Fp8History); values beyond the representable range saturate.  The weights are static,
+    so their delayed scale equals the one from their own amax, which is what is used."""
+    amax_x = np.abs(np.asarray(x, dtype=np.float32)).max() if np.size(x) else np.float32(0)
+    if hist is None:
+        inv_x = fp8_inv_scale(amax_x)
+    else:
+        inv_x = fp8_inv_scale(hist.amax())
+        hist.record(amax_x)
+    inv_w = fp8_inv_scale(np.abs(np.asarray(w, dtype=np.float32)).max())
+    x8, w8 = quantize_e4m3_at(x, inv_x), quantize_e4m3_at(w, inv_w)
+    return (x8 @ w8.T) * (1.0 / float(inv_x)) * (1.0 / float(inv_w)) + b
+
+
 def global_block(z: np.ndarray, w: dict, p: Params, store=lambda a: a) -> np.ndarray:
     """delta = Block(z) - z of the pre-norm transformer block around the global attention
     (Sec. 3.1: the aggregator's global layers; the paper does not restate the block and there
     are no trained weights, so this is the plain one with the weights given):
     LN -> q|k|v projection -> attention (q, k normalised per head when p.qk_norm) -> output
     projection u1; LN(z + u1) -> GELU MLP u2; delta = u1 + u2.  ``store`` models the storage
-    rounding of every intermediate the HIP path keeps in bf16."""
+    rounding of every intermediate the HIP path keeps in bf16.  With p.linear_fp8 the four
+    linear layers are linear_fp8 on the stored inputs."""
     C = z.shape[1]
+    if p.linear_fp8:
+        hs = p.fp8_history if p.fp8_history is not None else [None] * 4
+        lin = [lambda x, wt, b, h=h: linear_fp8(x, wt, b, h) for h in hs]
+    else:
+        lin = [linear] * 4
     h = store(layer_norm(z, w["ln1_g"], w["ln1_b"]))
-    qkv = store(linear(h, w["w_qkv"], w["b_qkv"]))
+    qkv = store(lin[0](h, w["w_qkv"], w["b_qkv"]))
     q, k, v = (qkv[:, i * C:(i + 1) * C].reshape(-1, p.heads, p.head_dim) for i in range(3))
     if p.qk_norm:
         q, k = store(qk_normalize(q)), store(qk_normalize(k))
     attn = attention_fp8 if p.attn_fp8 else attention
     a = store(attn(q, k, v).reshape(z.shape))
-    u1 = store(linear(a, w["w_o"], w["b_o"]))
+    u1 = store(lin[1](a, w["w_o"], w["b_o"]))
     h2 = store(layer_norm(z + u1, w["ln2_g"], w["ln2_b"]))
-    h3 = store(gelu(linear(h2, w["w_1"], w["b_1"])))
-    u2 = store(linear(h3, w["w_2"], w["b_2"]))
+    h3 = store(gelu(lin[2](h2, w["w_1"], w["b_1"])))
+    u2 = store(lin[3](h3, w["w_2"], w["b_2"]))
     return store(u1 + u2)
 
 

@@ -172,6 +172,87 @@ def test_round_e4m3_matches_torch():
     assert np.array_equal(O.round_e4m3(a), ref)
 
 
+# ---------------------------------------------------------------------------- FP8 linear layers
+def test_linear_fp8_matches_torch_float8_casts():
+    """Independent rounding (torch's float8_e4m3fn cast) and an independent product."""
+    rng = np.random.default_rng(53)
+    x = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(rng.standard_normal((37, 96)).astype(np.float32) * 3))
+    w = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(rng.standard_normal((24, 96)).astype(np.float32) * 0.1))
+    b = rng.standard_normal(24)
+    ix = np.float32(448.0) / np.abs(x).max()
+    iw = np.float32(448.0) / np.abs(w).max()
+    x8 = (torch.from_numpy(x) * float(ix)).to(torch.float8_e4m3fn).to(torch.float64)
+    w8 = (torch.from_numpy(w) * float(iw)).to(torch.float8_e4m3fn).to(torch.float64)
+    ref = (torch.einsum("nk,ok->no", x8, w8) / float(ix) / float(iw)).numpy() + b
+    got = O.linear_fp8(x, w, b)
+    assert np.allclose(got, ref, rtol=1e-12, atol=1e-12)
+    # and it is a small perturbation of the exact layer (3 mantissa bits on both operands)
+    exact = O.linear(x, w, b)
+    assert 1e-4 < np.abs(got - exact).max() / np.abs(exact).max() < 4e-2
+
+
+def test_linear_fp8_is_exact_on_representable_operands():
+    """Operands on the E4M3 grid with amax 448 (scale 1) lose nothing."""
+    rng = np.random.default_rng(54)
+    grid = np.array([0, 0.25, 1, 1.5, 3, 10, 14, 28, 120, 208, 448], dtype=np.float64)
+    x = rng.choice(grid, size=(9, 32)) * rng.choice([-1, 1], size=(9, 32))
+    w = rng.choice(grid, size=(5, 32)) * rng.choice([-1, 1], size=(5, 32))
+    x[0, 0], w[0, 0] = 448.0, -448.0
+    b = rng.standard_normal(5)
+    assert np.array_equal(O.linear_fp8(x, w, b), O.linear(x, w, b))
+    # a transposed weight or a dropped bias would show
+    assert O.linear_fp8(x, w, b).shape == (9, 5)
+
+
+def test_fp8_delayed_scaling_history():
+    """Scale from the largest amax of the previous <= 80 steps; 1 before anything is recorded."""
+    w = np.array([[448.0]])
+    b = np.zeros(1)
+    h = O.Fp8History()
+    # step 0: empty history -> scale 1: 1000 saturates at 448, 3.2 rounds to 3.25 (step 0.25 in [2, 4))
+    y = O.linear_fp8(np.array([[1000.0], [3.2]]), w, b, h)
+    assert np.array_equal(y.ravel(), [448.0 * 448.0, 3.25 * 448.0])
+    assert h.step == 1 and h.hist[0] == 1000.0
+    # step 1: scale from amax 1000: 1000 would be exact, 500 -> code 224 exactly
+    y = O.linear_fp8(np.array([[500.0]]), w, b, h)
+    inv = np.float32(448.0) / np.float32(1000.0)
+    assert np.isclose(y[0, 0], 224.0 / float(inv) * 448.0, rtol=1e-12)
+    # the window: amax t+1 at steps 1 + t; at step 100 the last 80 recorded amaxes are 20 .. 99
+    h = O.Fp8History()
+    for t in range(100):
+        assert h.amax() == (0 if t == 0 else max(range(max(0, t - 80), t)) + 1)
+        O.linear_fp8(np.array([[float(t + 1)]]), w, b, h)
+    # a large amax is forgotten after 80 further steps, not earlier
+    h = O.Fp8History()
+    O.linear_fp8(np.array([[4480.0]]), w, b, h)
+    for t in range(80):
+        assert h.amax() == 4480.0
+        O.linear_fp8(np.array([[1.0]]), w, b, h)
+    assert h.amax() == 1.0
+    # current scaling ignores all of it
+    assert np.isclose(O.linear_fp8(np.array([[1000.0]]), w, b)[0, 0], 1000.0 * 448.0, rtol=1e-6)
+
+
+def test_global_block_fp8_linear_is_close_to_exact_block():
+    wl = synth.Workload("b8", frames=2, grid_h=4, grid_w=4, dim=256, heads=4, merge_ratio=0.0, seed=71)
+    from helpers import oracle_params
+    wts = {k: (synth.bf16_bits_to_f32(v).astype(np.float64) if v.dtype == np.uint16 else v.astype(np.float64))
+           for k, v in synth.block_weights(wl.dim, seed=3).items()}
+    z = synth.bf16_bits_to_f32(synth.Generator(wl).tokens()).astype(np.float64)
+    exact = O.global_block(z, wts, oracle_params(wl, qk_norm=True))
+    p8 = oracle_params(wl, qk_norm=True)
+    p8.linear_fp8 = True
+    cur = O.global_block(z, wts, p8)
+    err = np.abs(cur - exact).max() / np.abs(exact).max()
+    assert 1e-4 < err < 6e-2
+    # delayed scaling, second step with the same input: the history holds this input's amaxes,
+    # so the result equals current scaling
+    p8.fp8_history = [O.Fp8History() for _ in range(4)]
+    O.global_block(z, wts, p8)
+    assert np.array_equal(O.global_block(z, wts, p8), cur)
+    assert [h.step for h in p8.fp8_history] == [2, 2, 2, 2]
+
+
 # ---------------------------------------------------------------------------- layer driver
 def test_refresh_schedule_matches_paper_table(golden_dir):
     rows = [tuple(int(v) for v in ln.split()) for ln in open(os.path.join(golden_dir, "recompute_counts.txt"))
