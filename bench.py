@@ -46,6 +46,9 @@ def parse_args():
     ap.add_argument("--block", action="store_true",
                     help="global layer = LayerNorm, q|k|v projection, attention, output projection, "
                          "MLP with seeded synthetic weights instead of the projection-free attention")
+    ap.add_argument("--linear-dtype", default="bf16", choices=["bf16", "fp8", "fp8-delayed"],
+                    help="with --block: operand type of its four linear layers (fp8: E4M3 per tensor, "
+                         "scales from the tensors; fp8-delayed: input scales from an 80-step amax history)")
     ap.add_argument("--frame-attn", action="store_true",
                     help="run a frame attention after every global layer (not part of the metric's default)")
     ap.add_argument("--no-unmerged", action="store_true",
@@ -176,7 +179,10 @@ def main():
         w_host = synth.block_weights(wl.dim, seed=wl.seed)
         w_dev = {k: (torch.from_numpy(synth.f32_to_bf16_bits(v).view(np.int16)).cuda().view(torch.bfloat16)
                      if v.ndim == 2 else torch.from_numpy(v).cuda()) for k, v in w_host.items()}
-        bw = B.block_weights(w_dev)
+        fp8_state = torch.zeros(B.FP8_STATE_BYTES, dtype=torch.uint8, device="cuda")
+        bw = B.block_weights(w_dev, linear_dtype=B.LINEAR_BF16 if args.linear_dtype == "bf16" else B.LINEAR_FP8_E4M3,
+                             fp8_recipe=B.FP8_DELAYED if args.linear_dtype == "fp8-delayed" else B.FP8_CURRENT,
+                             fp8_state=fp8_state)
     ph = B.make_params(wl.frames, wl.grid_h, wl.grid_w, wl.dim, wl.heads, n_special=wl.n_special,
                        patch=wl.patch, merge_ratio=wl.merge_ratio,
                        refresh_interval=wl.refresh_interval, qk_norm=1, attn_dtype=attn_dtype,
@@ -282,7 +288,8 @@ def main():
         ops["block_linear"] = dict(ms=avg["attn_pack"] + avg["block_rest"],
                                    tflops=blk_flop / ((avg["attn_pack"] + avg["block_rest"]) * 1e-3) / 1e12,
                                    note="everything of the block except the attention kernel: 2 LayerNorms, "
-                                        "4 linear layers (24 M C^2 flop), operand re-layouts, K/V re-layout")
+                                        "4 linear layers (24 M C^2 flop), operand re-layouts (FP8: amax and "
+                                        "quantisation passes), K/V re-layout")
     if args.frame_attn:
         fa_flop = 4.0 * wl.frames * wl.tokens_per_frame ** 2 * C_
         ops["frame_attn"] = dict(ms=avg["frame_attn"], tflops=fa_flop / (avg["frame_attn"] * 1e-3) / 1e12,
@@ -322,6 +329,7 @@ def main():
                                f"every {wl.refresh_interval}",
                    "token_layers_per_s": L * N / (ms_step * 1e-3),
                    "anchor_policy": args.anchor_policy, "frame_attn": bool(args.frame_attn), "block": bool(args.block),
+                   "linear_dtype": args.linear_dtype if args.block else None,
                    "refresh_log": log, "output_finite": finite,
                    "peak_hbm_alloc_gib": torch.cuda.max_memory_allocated() / 2 ** 30,
                    "input_generation_s": gen_s,

@@ -44,6 +44,14 @@ enum { LV_IMG_F32 = 0, LV_IMG_U8 = 1 };        /* image element type            
 enum { LV_ATTN_BF16 = 0, LV_ATTN_FP8_E4M3 = 1 }; /* attention MFMA operand type   */
 enum { LV_ROLE_PROTECTED = 0, LV_ROLE_DST = 1, LV_ROLE_SRC = 2 };
 enum { LV_POLICY_GA = 0, LV_POLICY_FIXED = 1, LV_POLICY_RANDOM = 2 }; /* what ranks the tokens */
+enum { LV_LINEAR_BF16 = 0, LV_LINEAR_FP8_E4M3 = 1 }; /* MFMA operand type of the block's linear layers */
+enum { LV_FP8_CURRENT = 0, LV_FP8_DELAYED = 1 };     /* where a quantised input's scale comes from */
+
+/* Delayed scaling (supplementary "FP8 Quantization Details": E4M3, delayed scaling, amax
+ * history of 80 steps reduced with max): per quantised input, the last 80 amaxes and a step
+ * counter.  One state block covers the four linear layers of a transformer block. */
+#define LV_FP8_HISTORY 80
+#define LV_FP8_STATE_BYTES (4 * (LV_FP8_HISTORY + 2) * 4)
 
 /* Weights of the transformer block around the global attention (litevggt_global_block):
  * device pointers, matrices bf16 row-major [out features, in features], vectors fp32. */
@@ -58,6 +66,20 @@ typedef struct {
   const float *b_1;             /* [4 dim]      */
   const void  *w_2;             /* [dim, 4 dim] */
   const float *b_2;             /* [dim]        */
+  int32_t linear_dtype;         /* LV_LINEAR_BF16, or LV_LINEAR_FP8_E4M3: the four linear layers
+                                   quantise their input and their weight per tensor to E4M3
+                                   (code = RNE(value * (448 / amax)), saturating, products
+                                   accumulated in fp32 and rescaled); bias, activation and
+                                   every stored intermediate stay as in the bf16 block        */
+  int32_t fp8_recipe;           /* scale of a linear layer's input: LV_FP8_CURRENT takes amax
+                                   from the tensor being quantised; LV_FP8_DELAYED from the
+                                   largest amax of the previous (up to) 80 uses of that layer,
+                                   scale 1 before the first use, and records the tensor's own
+                                   amax afterwards.  Weights always use their own amax.      */
+  void *fp8_state;              /* [device] LV_FP8_STATE_BYTES, read and written by every
+                                   call with LV_FP8_DELAYED: per layer (qkv, out-proj, fc1,
+                                   fc2) 80 fp32 amaxes, a uint32 step counter and a pad word.
+                                   The caller zero-fills it once; may be NULL otherwise.      */
 } litevggt_block_weights;
 
 /* Shape and hyper-parameters (host memory). */
@@ -206,7 +228,8 @@ int litevggt_unmerge(const litevggt_params *p, const void *y, const litevggt_ind
  *   u2 = GELU(h2 w_1^T + b_1) w_2^T + b_2     (GELU with erf)
  *   delta = u1 + u2               the block's output is z + delta
  * Every intermediate (h, q, k, v, a, u1, h2, the MLP hidden layer, u2) is stored as bf16;
- * accumulation is fp32.  dim must be a multiple of 256.
+ * accumulation is fp32.  dim must be a multiple of 256.  weights->linear_dtype selects FP8
+ * E4M3 operands for the four linear layers (see litevggt_block_weights).
  *   z      [device] [n_tokens, dim] bf16
  *   delta  [device] [n_tokens, dim] bf16 out
  *   ws     litevggt_global_block_ws_bytes(p, n_tokens) bytes

@@ -17,6 +17,10 @@ LIB_PATH = os.path.join(HERE, "liblitevggt.so")
 IMG_F32, IMG_U8 = 0, 1
 ATTN_BF16, ATTN_FP8_E4M3 = 0, 1
 POLICY_GA, POLICY_FIXED, POLICY_RANDOM = 0, 1, 2
+LINEAR_BF16, LINEAR_FP8_E4M3 = 0, 1
+FP8_CURRENT, FP8_DELAYED = 0, 1
+FP8_HISTORY = 80
+FP8_STATE_BYTES = 4 * (FP8_HISTORY + 2) * 4
 ROLE_PROTECTED, ROLE_DST, ROLE_SRC = 0, 1, 2
 
 EXPORTS = ["litevggt_strerror", "litevggt_plan", "litevggt_attn_ws_bytes", "litevggt_importance",
@@ -33,7 +37,8 @@ class LiteVGGTError(RuntimeError):
 class BlockWeights(C.Structure):
     """Mirror of ``litevggt_block_weights`` (device pointers)."""
     _fields_ = [(n, C.c_void_p) for n in ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g",
-                                          "ln2_b", "w_1", "b_1", "w_2", "b_2")]
+                                          "ln2_b", "w_1", "b_1", "w_2", "b_2")] + [
+        ("linear_dtype", C.c_int32), ("fp8_recipe", C.c_int32), ("fp8_state", C.c_void_p)]
 
 
 class Params(C.Structure):
@@ -232,9 +237,14 @@ def litevggt_frame_attn(p: Params, q, k, v, residual, o, ws) -> None:
                                      wp, wn, _stream()), "litevggt_frame_attn")
 
 
-def block_weights(tensors: dict) -> BlockWeights:
-    """BlockWeights from a dict of device tensors (keys = field names); keep the dict alive."""
-    return BlockWeights(**{k: tensors[k].data_ptr() for k, _ in BlockWeights._fields_})
+def block_weights(tensors: dict, linear_dtype: int = LINEAR_BF16, fp8_recipe: int = FP8_CURRENT,
+                  fp8_state=None) -> BlockWeights:
+    """BlockWeights from a dict of device tensors (keys = the pointer fields' names); keep the
+    dict alive.  ``fp8_state``: a zero-filled uint8 device tensor of FP8_STATE_BYTES for
+    FP8_DELAYED, kept alive and passed again on later calls."""
+    ptrs = {k: tensors[k].data_ptr() for k, t in BlockWeights._fields_ if t is C.c_void_p and k != "fp8_state"}
+    return BlockWeights(linear_dtype=linear_dtype, fp8_recipe=fp8_recipe,
+                        fp8_state=_ptr(fp8_state) if fp8_state is not None else None, **ptrs)
 
 
 def litevggt_global_block_ws_bytes(p: Params, n_tokens: int) -> int:

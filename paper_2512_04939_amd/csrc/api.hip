@@ -219,9 +219,16 @@ int litevggt_global_attn(const litevggt_params *p, int64_t n_tokens, const void 
                      n_tokens, d.heads, scale_of(p), p->attn_dtype, p->qk_norm, ws, (hipStream_t)stream);
 }
 
-static bool block_weights_ok(const litevggt_block_weights *w) {
-  return w && w->ln1_g && w->ln1_b && w->w_qkv && w->b_qkv && w->w_o && w->b_o && w->ln2_g &&
-         w->ln2_b && w->w_1 && w->b_1 && w->w_2 && w->b_2;
+static int check_block_weights(const litevggt_block_weights *w) {
+  if (!(w && w->ln1_g && w->ln1_b && w->w_qkv && w->b_qkv && w->w_o && w->b_o && w->ln2_g &&
+        w->ln2_b && w->w_1 && w->b_1 && w->w_2 && w->b_2))
+    return LV_ERR_NULL;
+  if (w->linear_dtype != LV_LINEAR_BF16 && w->linear_dtype != LV_LINEAR_FP8_E4M3) return LV_ERR_DTYPE;
+  if (w->linear_dtype == LV_LINEAR_FP8_E4M3) {
+    if (w->fp8_recipe != LV_FP8_CURRENT && w->fp8_recipe != LV_FP8_DELAYED) return LV_ERR_PARAM;
+    if (w->fp8_recipe == LV_FP8_DELAYED && !w->fp8_state) return LV_ERR_NULL;
+  }
+  return LV_OK;
 }
 
 size_t litevggt_global_block_ws_bytes(const litevggt_params *p, int64_t n_tokens) {
@@ -236,7 +243,8 @@ int litevggt_global_block(const litevggt_params *p, int64_t n_tokens, const void
   Dims d;
   int rc = check_params(p, &d);
   if (rc) return rc;
-  if (!z || !delta || !block_weights_ok(weights)) return LV_ERR_NULL;
+  if (!z || !delta) return LV_ERR_NULL;
+  if ((rc = check_block_weights(weights))) return rc;
   if (n_tokens < 1 || n_tokens >= ((int64_t)1 << 31) || d.C % 256 != 0) return LV_ERR_SHAPE;
   if (!ws_ok(ws, ws_bytes, block_ws_bytes(n_tokens, d.C, d.heads, p->attn_dtype))) return LV_ERR_WORKSPACE;
   return launch_global_block((const uint16_t *)z, n_tokens, d.C, d.heads, scale_of(p), p->attn_dtype,
@@ -285,8 +293,10 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
   const bool ga = p->anchor_policy == LV_POLICY_GA;   // the other policies read no image, cache no map
   if (!x || !score || !index_ok(index) || (ga && (!images || !grad_cache))) return LV_ERR_NULL;
   if (d.C > 1024) return LV_ERR_SHAPE;
-  if (p->block && (!block_weights_ok(p->block) || d.C % 256 != 0))
-    return p->block && d.C % 256 != 0 ? LV_ERR_SHAPE : LV_ERR_NULL;
+  if (p->block) {
+    if (d.C % 256 != 0) return LV_ERR_SHAPE;
+    if ((rc = check_block_weights(p->block))) return rc;
+  }
   if (!ws_ok(ws, ws_bytes, driver_ws_bytes(p, d, pl))) return LV_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   const size_t zy = align_up((size_t)pl.M * d.C * 2, 256);

@@ -652,27 +652,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // scale = amax/448 taken in the same call, the softmax weights with a fixed scale 2^8; the
 // MFMAs are v_mfma_f32_32x32x16_fp8_fp8, everything else (scores, max, sums, O) stays fp32.
 // ---------------------------------------------------------------------------------------
-constexpr float kFp8Max = 448.0f;
 constexpr float kFp8PShift = 8.0f;   // weights are stored as 2^8 * p, p <= 1 at the reference
 constexpr float kFp8Raise = 0.75f;   // 2^(8 + 0.75) < 448: the reference follows the maximum closely
 
-__device__ __forceinline__ uint32_t cvt4_fp8(float a, float b, float c, float d) {
-  uint32_t w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0u, false);
-  return __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
-}
-__device__ __forceinline__ float clamp448(float x) { return fminf(fmaxf(x, -kFp8Max), kFp8Max); }
-// 8 bf16 values scaled by r and quantised to 8 fp8 bytes
-__device__ __forceinline__ u32x2 quant8(const u32x4 w, float r) {
-  return u32x2{cvt4_fp8(clamp448(bf16_lo(w.x) * r), clamp448(bf16_hi(w.x) * r),
-                        clamp448(bf16_lo(w.y) * r), clamp448(bf16_hi(w.y) * r)),
-               cvt4_fp8(clamp448(bf16_lo(w.z) * r), clamp448(bf16_hi(w.z) * r),
-                        clamp448(bf16_lo(w.w) * r), clamp448(bf16_hi(w.w) * r))};
-}
-__device__ __forceinline__ float absmax8(const u32x4 w) {
-  const float a = fmaxf(fmaxf(fabsf(bf16_lo(w.x)), fabsf(bf16_hi(w.x))), fmaxf(fabsf(bf16_lo(w.y)), fabsf(bf16_hi(w.y))));
-  const float b = fmaxf(fmaxf(fabsf(bf16_lo(w.z)), fabsf(bf16_hi(w.z))), fmaxf(fabsf(bf16_lo(w.w)), fabsf(bf16_hi(w.w))));
-  return fmaxf(a, b);
-}
 // bf16 values of w scaled by r and rounded to bf16 (the normalised q/k as the bf16 path sees them)
 __device__ __forceinline__ u32x4 norm8(const u32x4 w, float ss_head, int qk_norm) {
   return qk_norm ? scale8(w, 1.0f / sqrtf(ss_head * (1.0f / 64.0f) + kQkEps)) : w;
@@ -720,11 +702,6 @@ __global__ __launch_bounds__(256) void k_attn_amax(const uint16_t *__restrict__ 
                           fmaxf(red[threadIdx.x][2], red[threadIdx.x][3]));
     atomicMax(&amax[threadIdx.x], __float_as_uint(m));   // non-negative floats order like uints
   }
-}
-
-__device__ __forceinline__ float fp8_scale_inv(uint32_t amax_bits) {   // 448 / amax (1 if amax = 0)
-  const float a = __uint_as_float(amax_bits);
-  return a > 0.f ? kFp8Max / a : 1.0f;
 }
 
 // fp8 counterpart of k_attn_pack: same fragment-major orders with 8 bytes per lane.

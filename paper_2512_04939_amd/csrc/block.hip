@@ -6,7 +6,10 @@
 //   a  = Attn(q, k, v)   (q, k RMS-normalised per head when qk_norm)
 //   u1 = a Wo^T + bo                         h2 = LN(z + u1; g2, b2)
 //   u2 = GELU(h2 W1^T + b1m) W2^T + b2m      delta = u1 + u2        (Block(z) = z + delta)
-// Every intermediate is stored as bf16; the four linear layers run on one tiled MFMA kernel.
+// Every intermediate is stored as bf16; the four linear layers run on one tiled MFMA kernel,
+// with bf16 operands or (supplementary "FP8 Quantization Details") with FP8 E4M3 operands
+// quantised per tensor, the input's scale taken from the tensor itself or from an 80-step amax
+// history (delayed scaling).
 #include "common.h"
 #include "internal.h"
 
@@ -104,6 +107,80 @@ __global__ __launch_bounds__(256) void k_add_bf16(const u32x4 *__restrict__ a,
 }
 
 // ---------------------------------------------------------------------------------------
+// FP8 E4M3 operands.  Scalars of one linear layer (device memory, 8 words):
+//   [0] amax of the input (bits of a non-negative float, reduced with atomic max)
+//   [1] amax of the weight     [2] 448 / amax used for the input    [3] the same for the weight
+//   [4] product of the two scales (what the accumulators are multiplied with)
+// ---------------------------------------------------------------------------------------
+constexpr int kFp8Words = 8;
+
+__global__ void k_fp8_zero(uint32_t *sc) {
+  if (threadIdx.x < kFp8Words) sc[threadIdx.x] = 0u;
+}
+
+// amax of a bf16 tensor of n16 16-byte pieces
+__global__ __launch_bounds__(256) void k_amax_bf16(const u32x4 *__restrict__ x, int64_t n16,
+                                                   uint32_t *__restrict__ amax) {
+  __shared__ float red[4];
+  float m = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+       i += (int64_t)gridDim.x * blockDim.x)
+    m = fmaxf(m, absmax8(x[i]));
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    atomicMax(amax, __float_as_uint(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]))));
+}
+
+// One wave: picks the scales of a layer.  state == NULL: both from the tensors' own amax.
+// Otherwise the input's scale comes from the largest of the recorded amaxes (1 while nothing
+// has been recorded), and the input's own amax is recorded afterwards.
+__global__ __launch_bounds__(64) void k_fp8_scales(uint32_t *__restrict__ sc, float *__restrict__ state) {
+  const int lane = threadIdx.x;
+  uint32_t src = sc[0];
+  if (state) {
+    float m = fmaxf(state[lane], lane + 64 < LV_FP8_HISTORY ? state[lane + 64] : 0.f);
+    src = __float_as_uint(wave_max(m));
+  }
+  if (lane == 0) {
+    const float ia = fp8_scale_inv(src), iw = fp8_scale_inv(sc[1]);
+    sc[2] = __float_as_uint(ia);
+    sc[3] = __float_as_uint(iw);
+    sc[4] = __float_as_uint((1.0f / ia) * (1.0f / iw));
+    if (state) {
+      uint32_t *step = (uint32_t *)(state + LV_FP8_HISTORY);
+      state[*step % LV_FP8_HISTORY] = __uint_as_float(sc[0]);
+      *step += 1;
+    }
+  }
+}
+
+// Quantise rows 0..n-1 of a row-major [n, K] bf16 matrix with the scale in *inv and store them
+// fragment-major for the FP8 MFMA: a unit (32 rows x 32 consecutive k, 1 KB) holds, in lane
+// (h*32 + r), the 16 codes k = 32u + 16h .. + 15 of row r; an MFMA operand of 64 k is two
+// units.  (Both operands use the same k order inside an operand, which is all a dot product
+// needs.)  The byte layout equals that of the bf16 packing of a matrix with K/2 columns, so
+// the tiled kernel fetches and reads both types the same way.  Rows n..n_pad-1 are zero.
+__global__ __launch_bounds__(256) void k_quant_pack_fp8(const uint16_t *__restrict__ x, int n, int n_pad,
+                                                        int K, const uint32_t *__restrict__ inv,
+                                                        u32x4 *__restrict__ packed) {
+  const int nch = K >> 4, KS = K >> 5;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)n_pad * nch) return;
+  const int j = (int)(idx / nch), c = (int)(idx % nch);
+  u32x4 o = {0u, 0u, 0u, 0u};
+  if (j < n) {
+    const float r = __uint_as_float(*inv);
+    const u32x4 *src = (const u32x4 *)(x + (size_t)j * K) + 2 * c;
+    const u32x2 lo = quant8(src[0], r), hi = quant8(src[1], r);
+    o = u32x4{lo.x, lo.y, hi.x, hi.y};
+  }
+  const int t = j >> 5, rr = j & 31, s2 = c >> 1, h = c & 1;
+  packed[((size_t)t * KS + s2) * 64 + h * 32 + rr] = o;
+}
+
+// ---------------------------------------------------------------------------------------
 // Y[M, Nout] = A[M, K] W[Nout, K]^T + bias (optionally GELU), bf16 in and out, fp32
 // accumulation.  Same machinery as the similarity kernel of the matching step: 256 x 256
 // output tiles, both operands pre-packed fragment-major, fetched straight into a 4-stage LDS
@@ -112,7 +189,21 @@ __global__ __launch_bounds__(256) void k_add_bf16(const u32x4 *__restrict__ a,
 // (the ring is free by then) and written in 16-byte pieces along the rows.
 // `split`: the output is Nout / split row-major blocks of [M, split] one after the other
 // (split = Nout: one plain matrix; split = C for the fused q|k|v projection).
+// FP8: the same ring and the same byte traffic per stage, but a stage (two 1 KB units per
+// fragment) is one k-step of 64 for v_mfma_f32_32x32x64_f8f6f4, whose operands are the two
+// units of a fragment side by side in 8 registers: per stage a wave issues 8 MFMAs of twice
+// the work.  The activation fragments of the next stage go to a second register set at the
+// start of a stage, the weight fragments replace those of the current stage pair by pair as
+// its MFMAs have been issued.  `alpha` (FP8: the product of the two scales) multiplies the
+// accumulators before the bias.
 // ---------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+__device__ __forceinline__ i32x8 cat8(const u32x4 a, const u32x4 b) {
+  return i32x8{(int)a.x, (int)a.y, (int)a.z, (int)a.w, (int)b.x, (int)b.y, (int)b.z, (int)b.w};
+}
+__device__ __forceinline__ void lds_read1_async(u32x4 &dst, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1" : "=&v"(dst) : "v"(addr) : "memory");
+}
 constexpr int kTile = 256;
 constexpr int kStages = 4;
 constexpr int kStageU4 = 2 * 2 * 8 * 64;     // [weights|activations][2 k-steps][8 fragments][64 lanes]
@@ -120,9 +211,11 @@ constexpr int kOutPitch = kTile * 2 + 16;    // bytes per row of the transposed 
 
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
 
+template <bool FP8>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_bt(
     const u32x4 *__restrict__ ap, const u32x4 *__restrict__ wp, int64_t M, int Nout, int KS, int nt_n,
-    const float *__restrict__ bias, int gelu, uint16_t *__restrict__ out, int split) {
+    const float *__restrict__ bias, int gelu, uint16_t *__restrict__ out, int split,
+    const float *__restrict__ alpha_p) {
   extern __shared__ u32x4 ring[];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -178,27 +271,77 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   for (int i = 0; i < kStages; ++i) fetch();                 // stages 0..3
   asm volatile("s_waitcnt vmcnt(12)" ::: "memory");          // stage 0 has landed (this wave's part)
   __builtin_amdgcn_s_barrier();
-  read_frags(0, 0, fb[0], fa[0]);
-  for (int g = 0; g < total; ++g) {
-    __builtin_amdgcn_sched_barrier(0);
-    wait_frags(fb[0], fa[0]);
-    read_frags(g, 1, fb[1], fa[1]);
-    __builtin_amdgcn_sched_barrier(0);
-    mma(fb[0], fa[0]);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_frags(fb[1], fa[1]);
-    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");         // stage g+1 has landed; g+2, g+3 may be in flight
-    __builtin_amdgcn_s_barrier();
-    fetch();                                                 // stage g+4 -> slot of stage g
-    read_frags(g + 1, 0, fb[0], fa[0]);                      // past the end: a stale slot, never used
-    __builtin_amdgcn_sched_barrier(0);
-    mma(fb[1], fa[1]);
+  if constexpr (!FP8) {
+    read_frags(0, 0, fb[0], fa[0]);
+    for (int g = 0; g < total; ++g) {
+      __builtin_amdgcn_sched_barrier(0);
+      wait_frags(fb[0], fa[0]);
+      read_frags(g, 1, fb[1], fa[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      mma(fb[0], fa[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      wait_frags(fb[1], fa[1]);
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");         // stage g+1 has landed; g+2, g+3 may be in flight
+      __builtin_amdgcn_s_barrier();
+      fetch();                                                 // stage g+4 -> slot of stage g
+      read_frags(g + 1, 0, fb[0], fa[0]);                      // past the end: a stale slot, never used
+      __builtin_amdgcn_sched_barrier(0);
+      mma(fb[1], fa[1]);
+    }
+  } else {
+    // fb[u][bi], fa[set][u][ai]: unit u of a fragment; an operand is (unit 0, unit 1)
+    u32x4 fa2[2][2][2];
+    read_frags(0, 0, fb[0], fa2[0][0]);
+    read_frags(0, 1, fb[1], fa2[0][1]);
+    auto stage = [&](int g, u32x4(&ac)[2][2], u32x4(&an)[2][2]) {
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(fb[0][0]), "+v"(fb[0][1]), "+v"(fb[0][2]), "+v"(fb[0][3]), "+v"(fb[1][0]),
+                     "+v"(fb[1][1]), "+v"(fb[1][2]), "+v"(fb[1][3]), "+v"(ac[0][0]), "+v"(ac[0][1]),
+                     "+v"(ac[1][0]), "+v"(ac[1][1])
+                   :
+                   : "memory");
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");       // stage g+1 has landed; g+2, g+3 may be in flight
+      __builtin_amdgcn_s_barrier();                          // and nobody reads stage g from LDS any more
+      fetch();                                               // stage g+4 -> slot of stage g
+      // past the end these read a stale slot; the values are never used
+      const uint32_t base = ring_lane + (uint32_t)(((g + 1) & (kStages - 1)) * kStageU4 * 16);
+      lds_read2_async(an[0], base + a_off);
+      lds_read2_async(an[1], base + 8 * 1024 + a_off);
+#pragma unroll
+      for (int bi = 0; bi < 4; ++bi) {
+        __builtin_amdgcn_sched_barrier(0);
+        const i32x8 b8 = cat8(fb[0][bi], fb[1][bi]);
+#pragma unroll
+        for (int ai = 0; ai < 2; ++ai)
+          acc[ai][bi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cat8(ac[0][ai], ac[1][ai]), b8,
+                                                                        acc[ai][bi], 0, 0, 0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_read1_async(fb[0][bi], base + b_off + bi * 1024);
+        lds_read1_async(fb[1][bi], base + 8 * 1024 + b_off + bi * 1024);
+      }
+    };
+    int g = 0;
+    for (; g + 1 < total; g += 2) {
+      stage(g, fa2[0], fa2[1]);
+      stage(g + 1, fa2[1], fa2[0]);
+    }
+    if (g < total) stage(g, fa2[0], fa2[1]);
+    // the reads issued by the last stage are waited for below, before their registers die
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(fb[0][0]), "+v"(fb[0][1]), "+v"(fb[0][2]), "+v"(fb[0][3]), "+v"(fb[1][0]),
+                   "+v"(fb[1][1]), "+v"(fb[1][2]), "+v"(fb[1][3]), "+v"(fa2[0][0][0]), "+v"(fa2[0][0][1]),
+                   "+v"(fa2[0][1][0]), "+v"(fa2[0][1][1]), "+v"(fa2[1][0][0]), "+v"(fa2[1][0][1]),
+                   "+v"(fa2[1][1][0]), "+v"(fa2[1][1][1])
+                 :
+                 : "memory");
   }
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // nothing may land in LDS any more
   __syncthreads();
 
   // bias, activation, bf16, into the transposed tile: row = token, column = output channel
   char *tile = (char *)ring;
+  const float alpha = alpha_p ? *alpha_p : 1.0f;
   const int ncol = wn * 128 + (lane & 31);
 #pragma unroll
   for (int b = 0; b < 4; ++b) {
@@ -208,7 +351,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int mrow = wd * 64 + a * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-        float v = acc[a][b][r] + bv;
+        float v = FP8 ? acc[a][b][r] * alpha + bv : acc[a][b][r] + bv;
         if (gelu) v = gelu_erf(v);
         *(uint16_t *)(tile + (size_t)mrow * kOutPitch + (ncol + 32 * b) * 2) = (uint16_t)pack_bf16(v, 0.f);
       }
@@ -230,6 +373,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 struct BlockWs {
   uint16_t *h, *qkv, *a, *u1, *u2, *h3;
   u32x4 *apack, *wpack;
+  uint32_t *fp8sc;
   void *attn;
   size_t bytes;
   int64_t Mp;
@@ -252,6 +396,7 @@ static BlockWs carve_block(int64_t M, int C, int heads, int attn_dtype, char *ba
   w.h3 = (uint16_t *)take((size_t)M * 4 * C * 2);
   w.apack = (u32x4 *)take((size_t)w.Mp * 4 * C * 2);
   w.wpack = (u32x4 *)take((size_t)4 * C * C * 2);
+  w.fp8sc = (uint32_t *)take(kFp8Words * sizeof(uint32_t));
   w.attn = take(attn_ws_bytes(heads, M, attn_dtype));
   w.bytes = off;
   return w;
@@ -261,28 +406,51 @@ size_t block_ws_bytes(int64_t M, int C, int heads, int attn_dtype) {
   return carve_block(M, C, heads, attn_dtype, nullptr).bytes;
 }
 
-// Y = A W^T + bias: packs both operands, then the tiled kernel
+// Y = A W^T + bias: packs both operands (FP8: after taking their amax and quantising them),
+// then the tiled kernel.  fp8_state: the layer's delayed-scaling state, or NULL.
 static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W, int Nout,
                          const float *bias, int gelu, uint16_t *out, int split, BlockWs &w,
-                         hipStream_t st) {
-  if (K % 32 != 0 || Nout % kTile != 0 || split % kTile != 0 || Nout % split != 0) return LV_ERR_SHAPE;
+                         hipStream_t st, bool fp8 = false, float *fp8_state = nullptr) {
+  if (K % 64 != 0 || Nout % kTile != 0 || split % kTile != 0 || Nout % split != 0) return LV_ERR_SHAPE;
   int rc;
-  if ((rc = launch_pack_rows(A, M, w.Mp, K, w.apack, st))) return rc;
-  if ((rc = launch_pack_rows(W, Nout, Nout, K, w.wpack, st))) return rc;
   const size_t lds = (size_t)kTile * kOutPitch > (size_t)kStages * kStageU4 * 16 ? (size_t)kTile * kOutPitch
                                                                                    : (size_t)kStages * kStageU4 * 16;
   static bool lds_set = false;
   if (!lds_set) {
-    if (hipFuncSetAttribute((const void *)k_gemm_bt, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void *)k_gemm_bt<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess ||
+        hipFuncSetAttribute((const void *)k_gemm_bt<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds) != hipSuccess)
       return LV_ERR_HIP;
     lds_set = true;
   }
   const int nt_n = Nout / kTile;
   const int64_t nt_m = w.Mp / kTile;
-  if (nt_m * nt_n >= ((int64_t)1 << 31)) return LV_ERR_SHAPE;
-  hipLaunchKernelGGL(k_gemm_bt, dim3((unsigned)(nt_m * nt_n)), dim3(512), lds, st, w.apack, w.wpack,
-                     M, Nout, K / 16, nt_n, bias, gelu, out, split);
+  if (nt_m * nt_n >= ((int64_t)1 << 31) || w.Mp >= ((int64_t)1 << 31)) return LV_ERR_SHAPE;
+  if (fp8) {
+    auto amax = [&](const uint16_t *t, int64_t n16, uint32_t *dst) {
+      const unsigned g = (unsigned)(((n16 + 255) / 256) < 4096 ? ((n16 + 255) / 256) : 4096);
+      hipLaunchKernelGGL(k_amax_bf16, dim3(g), dim3(256), 0, st, (const u32x4 *)t, n16, dst);
+    };
+    auto quant = [&](const uint16_t *t, int64_t n, int64_t n_pad, const uint32_t *inv, u32x4 *dst) {
+      const int64_t pk = n_pad * (K / 16);
+      hipLaunchKernelGGL(k_quant_pack_fp8, dim3((unsigned)((pk + 255) / 256)), dim3(256), 0, st, t, (int)n,
+                         (int)n_pad, K, inv, dst);
+    };
+    hipLaunchKernelGGL(k_fp8_zero, dim3(1), dim3(64), 0, st, w.fp8sc);
+    amax(A, M * (K / 8), w.fp8sc);
+    amax(W, (int64_t)Nout * (K / 8), w.fp8sc + 1);
+    hipLaunchKernelGGL(k_fp8_scales, dim3(1), dim3(64), 0, st, w.fp8sc, fp8_state);
+    quant(A, M, w.Mp, w.fp8sc + 2, w.apack);
+    quant(W, Nout, Nout, w.fp8sc + 3, w.wpack);
+    hipLaunchKernelGGL(k_gemm_bt<true>, dim3((unsigned)(nt_m * nt_n)), dim3(512), lds, st, w.apack, w.wpack,
+                       M, Nout, K / 32, nt_n, bias, gelu, out, split, (const float *)(w.fp8sc + 4));
+  } else {
+    if ((rc = launch_pack_rows(A, M, w.Mp, K, w.apack, st))) return rc;
+    if ((rc = launch_pack_rows(W, Nout, Nout, K, w.wpack, st))) return rc;
+    hipLaunchKernelGGL(k_gemm_bt<false>, dim3((unsigned)(nt_m * nt_n)), dim3(512), lds, st, w.apack, w.wpack,
+                       M, Nout, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr);
+  }
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;
 }
@@ -293,18 +461,22 @@ int launch_global_block(const uint16_t *z, int64_t M, int C, int heads, float sc
   if (C % kTile != 0) return LV_ERR_SHAPE;
   BlockWs w = carve_block(M, C, heads, attn_dtype, (char *)ws);
   int rc;
+  const bool f8 = bw.linear_dtype == LV_LINEAR_FP8_E4M3;
+  auto state = [&](int layer) -> float * {   // delayed scaling: this layer's history
+    return f8 && bw.fp8_recipe == LV_FP8_DELAYED ? (float *)bw.fp8_state + layer * (LV_FP8_HISTORY + 2) : nullptr;
+  };
   if ((rc = launch_layernorm(z, nullptr, bw.ln1_g, bw.ln1_b, M, C, w.h, st))) return rc;
-  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_qkv, 3 * C, bw.b_qkv, 0, w.qkv, C, w, st)))
+  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_qkv, 3 * C, bw.b_qkv, 0, w.qkv, C, w, st, f8, state(0))))
     return rc;
   const uint16_t *q = w.qkv, *k = w.qkv + (size_t)M * C, *v = w.qkv + (size_t)2 * M * C;
   if ((rc = launch_attn(q, k, v, w.a, M, heads, scale, attn_dtype, qk_norm, w.attn, st, after_pack)))
     return rc;
   if (after_attn && hipEventRecord(after_attn, st) != hipSuccess) return LV_ERR_HIP;
-  if ((rc = launch_linear(w.a, M, C, (const uint16_t *)bw.w_o, C, bw.b_o, 0, w.u1, C, w, st))) return rc;
+  if ((rc = launch_linear(w.a, M, C, (const uint16_t *)bw.w_o, C, bw.b_o, 0, w.u1, C, w, st, f8, state(1)))) return rc;
   if ((rc = launch_layernorm(z, w.u1, bw.ln2_g, bw.ln2_b, M, C, w.h, st))) return rc;
-  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_1, 4 * C, bw.b_1, 1, w.h3, 4 * C, w, st)))
+  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_1, 4 * C, bw.b_1, 1, w.h3, 4 * C, w, st, f8, state(2))))
     return rc;
-  if ((rc = launch_linear(w.h3, M, 4 * C, (const uint16_t *)bw.w_2, C, bw.b_2, 0, w.u2, C, w, st)))
+  if ((rc = launch_linear(w.h3, M, 4 * C, (const uint16_t *)bw.w_2, C, bw.b_2, 0, w.u2, C, w, st, f8, state(3))))
     return rc;
   const int64_t n16 = M * C / 8;
   const unsigned grid = (unsigned)(((n16 + 255) / 256) < 65536 ? ((n16 + 255) / 256) : 65536);

@@ -79,6 +79,31 @@ __device__ __forceinline__ void lds_read2_async(u32x4 (&dst)[2], uint32_t addr) 
                : "memory");
 }
 
+// FP8 E4M3 (OCP "fn": bias 7, largest value 448, no infinities), round to nearest even
+constexpr float kFp8Max = 448.0f;
+
+__device__ __forceinline__ uint32_t cvt4_fp8(float a, float b, float c, float d) {
+  uint32_t w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0u, false);
+  return __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
+}
+__device__ __forceinline__ float clamp448(float x) { return fminf(fmaxf(x, -kFp8Max), kFp8Max); }
+// 8 bf16 values scaled by r and quantised to 8 fp8 bytes
+__device__ __forceinline__ u32x2 quant8(const u32x4 w, float r) {
+  return u32x2{cvt4_fp8(clamp448(bf16_lo(w.x) * r), clamp448(bf16_hi(w.x) * r),
+                        clamp448(bf16_lo(w.y) * r), clamp448(bf16_hi(w.y) * r)),
+               cvt4_fp8(clamp448(bf16_lo(w.z) * r), clamp448(bf16_hi(w.z) * r),
+                        clamp448(bf16_lo(w.w) * r), clamp448(bf16_hi(w.w) * r))};
+}
+__device__ __forceinline__ float absmax8(const u32x4 w) {
+  const float a = fmaxf(fmaxf(fabsf(bf16_lo(w.x)), fabsf(bf16_hi(w.x))), fmaxf(fabsf(bf16_lo(w.y)), fabsf(bf16_hi(w.y))));
+  const float b = fmaxf(fmaxf(fabsf(bf16_lo(w.z)), fabsf(bf16_hi(w.z))), fmaxf(fabsf(bf16_lo(w.w)), fabsf(bf16_hi(w.w))));
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float fp8_scale_inv(uint32_t amax_bits) {   // 448 / amax (1 if amax = 0)
+  const float a = __uint_as_float(amax_bits);
+  return a > 0.f ? kFp8Max / a : 1.0f;
+}
+
 }  // namespace lv
 
 #define LV_HIP_CHECK_LAUNCH()                                  \

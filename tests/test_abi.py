@@ -92,3 +92,18 @@ def test_entry_points_validate_before_launch():
     assert lib.litevggt_layers_run(C.byref(p), 2, fake, fake, C.byref(ix), fake, fake, None, None,
                                    fake, 1 << 30, None) == -1
     assert B.litevggt_attn_ws_bytes(p, 1000) > 0
+    # the block: weights struct is checked before anything is launched
+    bw = B.BlockWeights()                            # all NULL
+    assert lib.litevggt_global_block(C.byref(p), 100, fake, C.byref(bw), fake, fake, 1 << 30, None) == -1
+    for k, t in B.BlockWeights._fields_:
+        if t is C.c_void_p and k != "fp8_state":
+            setattr(bw, k, 0x1000)
+    bw.linear_dtype = 7
+    assert lib.litevggt_global_block(C.byref(p), 100, fake, C.byref(bw), fake, fake, 1 << 30, None) == -5
+    bw.linear_dtype, bw.fp8_recipe = B.LINEAR_FP8_E4M3, 5
+    assert lib.litevggt_global_block(C.byref(p), 100, fake, C.byref(bw), fake, fake, 1 << 30, None) == -3
+    bw.fp8_recipe = B.FP8_DELAYED                    # needs a state block
+    assert lib.litevggt_global_block(C.byref(p), 100, fake, C.byref(bw), fake, fake, 1 << 30, None) == -1
+    bw.fp8_state = 0x1000                            # now only the workspace is wrong
+    assert lib.litevggt_global_block(C.byref(p), 100, fake, C.byref(bw), fake, fake, 16, None) == -4
+    assert C.sizeof(B.BlockWeights) == 12 * 8 + 2 * 4 + 8 and B.FP8_STATE_BYTES == 1312

@@ -375,6 +375,15 @@ def test_global_attn_qk_norm(B):
 
 
 FP8_TOL = 6e-2
+# FP8 linear layers against the oracle with the same quantisation points.  The two sides agree
+# on a stored bf16 intermediate only up to its rounding step: the attention output carries a
+# relative error near 1e-3 (bf16 weights), a quarter of a bf16 step, so about one stored value
+# in four differs by a step (2^-8).  Such a difference crosses an E4M3 rounding boundary (spacing
+# 2^-4) once in 16 times and then moves the code by a whole step: ~1.5 % of a layer's input
+# codes differ by ~6 %, i.e. ~0.7 % rms of the layer's output and, at 4.5 sigma over ~10^5
+# outputs, ~1 % of its largest value; three such layers follow the attention.  That noise adds
+# to the bf16 tolerance: 2e-2 + 2e-2.  (Measured: 2.0e-2 .. 3.0e-2.)
+FP8_EMU_TOL = 4e-2
 
 
 def _fp8_case(B, qs_bits, ks_bits, vs_bits, n, heads, qk_norm):
@@ -483,6 +492,71 @@ def test_global_block(B, n, dim, heads, qk_norm):
     B.litevggt_global_block(ph, n, to_dev_bf16(zb), bw, delta, ws)
     torch.cuda.synchronize()
     assert max_rel_err(dev_bf16_to_f64(delta), want) <= BF16_TOL
+
+
+@pytest.mark.parametrize("n,dim,heads", [(300, 256, 4), (777, 512, 8), (520, 1024, 16)])
+def test_global_block_fp8_linear_current_scaling(B, n, dim, heads):
+    """The four linear layers on FP8 E4M3 MFMAs, scales from the tensors themselves: against
+    the oracle with the same quantisation points, plus a sanity bound against the exact block.  K = 256 .. 4096 gives 4 .. 64 stages per tile, odd and even counts
+    of stage pairs; n is ragged against the 256-row tiles."""
+    import torch
+    w = synth.block_weights(dim, seed=n + 1)
+    tens, _ = _dev_block_weights(B, w)
+    bw = B.block_weights(tens, linear_dtype=B.LINEAR_FP8_E4M3, fp8_recipe=B.FP8_CURRENT)
+    rng = np.random.default_rng(n)
+    zb = synth.f32_to_bf16_bits((rng.standard_normal((n, dim)) * 1.5).astype(np.float32))
+    z = synth.bf16_bits_to_f32(zb).astype(np.float64)
+    wl = small_workload(frames=1, grid=4, dim=dim, heads=heads)
+    ph = hip_params(wl, qk_norm=1)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    emu = O.global_block(z, w64, oracle_params(wl, qk_norm=True, linear_fp8=True), _store_bf16)
+    exact = O.global_block(z, w64, oracle_params(wl, qk_norm=True), _store_bf16)
+    delta = torch.zeros(n, dim, dtype=torch.bfloat16, device="cuda")
+    ws = B.alloc_ws(B.litevggt_global_block_ws_bytes(ph, n))
+    B.litevggt_global_block(ph, n, to_dev_bf16(zb), bw, delta, ws)
+    torch.cuda.synchronize()
+    got = dev_bf16_to_f64(delta)
+    print(f"fp8 block n={n} dim={dim}: vs emulation {max_rel_err(got, emu):.2e}, vs exact {max_rel_err(got, exact):.2e},"
+          f" emulation vs exact {max_rel_err(emu, exact):.2e}")
+    assert max_rel_err(got, emu) <= FP8_EMU_TOL
+    # Distance to the unquantised block: a property of the recipe, not of the kernel (the
+    # oracle's own FP8 block is 5e-2 .. 7e-2 away: per-tensor E4M3 costs about 3.5 % rms per
+    # linear layer and three of them are chained); it bounds gross errors only.
+    assert max_rel_err(got, exact) <= 1e-1
+
+
+def test_global_block_fp8_linear_delayed_scaling(B):
+    """Delayed scaling over four calls with inputs of different range: the scale of a call
+    comes from the amaxes the earlier calls recorded (1 in the first call, where most codes
+    are coarse), and the device state equals the oracle's history."""
+    import torch
+    n, dim, heads = 300, 256, 4
+    w = synth.block_weights(dim, seed=9)
+    tens, _ = _dev_block_weights(B, w)
+    state = torch.zeros(B.FP8_STATE_BYTES, dtype=torch.uint8, device="cuda")
+    bw = B.block_weights(tens, linear_dtype=B.LINEAR_FP8_E4M3, fp8_recipe=B.FP8_DELAYED, fp8_state=state)
+    wl = small_workload(frames=1, grid=4, dim=dim, heads=heads)
+    ph = hip_params(wl, qk_norm=1)
+    hist = [O.Fp8History() for _ in range(4)]
+    po = oracle_params(wl, qk_norm=True, linear_fp8=True, fp8_history=hist)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    ws = B.alloc_ws(B.litevggt_global_block_ws_bytes(ph, n))
+    rng = np.random.default_rng(77)
+    for call, amp in enumerate((1.5, 0.4, 3.0, 1.0)):
+        zb = synth.f32_to_bf16_bits((rng.standard_normal((n, dim)) * amp).astype(np.float32))
+        z = synth.bf16_bits_to_f32(zb).astype(np.float64)
+        want = O.global_block(z, w64, po, _store_bf16)
+        delta = torch.zeros(n, dim, dtype=torch.bfloat16, device="cuda")
+        B.litevggt_global_block(ph, n, to_dev_bf16(zb), bw, delta, ws)
+        torch.cuda.synchronize()
+        assert max_rel_err(dev_bf16_to_f64(delta), want) <= FP8_EMU_TOL, call
+        st = state.cpu().numpy().view(np.float32).reshape(4, B.FP8_HISTORY + 2)
+        for layer in range(4):
+            assert st[layer, B.FP8_HISTORY:].view(np.uint32)[0] == call + 1 == hist[layer].step
+            # LN / attention / GELU outputs differ by bf16 roundings between the two sides
+            assert np.allclose(st[layer, :B.FP8_HISTORY], hist[layer].hist, rtol=2e-2, atol=0)
+    # layer 0's input (LN of the given z) has the same amax on both sides up to one bf16 step
+    assert np.all(st[:, call + 1:B.FP8_HISTORY] == 0)
 
 
 def test_layers_run_with_block_and_frame_attention(B):
