@@ -559,14 +559,21 @@ def test_global_block_fp8_linear_delayed_scaling(B):
     assert np.all(st[:, call + 1:B.FP8_HISTORY] == 0)
 
 
-def test_layers_run_with_block_and_frame_attention(B):
-    """The faithful stack: merged global block, unmerge, frame attention; teacher-forced."""
+@pytest.mark.parametrize("linear", ["bf16", "fp8"])
+def test_layers_run_with_block_and_frame_attention(B, linear):
+    """The faithful stack: merged global block (bf16 or FP8 linear layers, current scaling),
+    unmerge, frame attention; teacher-forced."""
     import torch
     wl = synth.workload("tiny2")
     bits, xf, im = stored_inputs(wl)
     w = synth.block_weights(wl.dim, seed=5)
     tens, bw = _dev_block_weights(B, w)
-    po = oracle_params(wl, frame_attn=True, block={k: v.astype(np.float64) for k, v in w.items()})
+    f8 = linear == "fp8"
+    tol = FP8_EMU_TOL if f8 else BF16_TOL
+    if f8:
+        bw = B.block_weights(tens, linear_dtype=B.LINEAR_FP8_E4M3, fp8_recipe=B.FP8_CURRENT)
+    po = oracle_params(wl, frame_attn=True, linear_fp8=f8,
+                       block={k: v.astype(np.float64) for k, v in w.items()})
     ph = hip_params(wl, frame_attn=1, block=bw)
     pl = B.litevggt_plan(ph)
     trace = []
@@ -583,13 +590,13 @@ def test_layers_run_with_block_and_frame_attention(B):
         torch.cuda.synchronize()
         idx = O.compute_index(im, t["x_in"], po)[0]
         exp = O.frame_layer(O.global_layer(t["x_in"], idx, po, _store_bf16), po, _store_bf16)
-        assert max_rel_err(dev_bf16_to_f64(x_dev), exp) <= BF16_TOL
+        assert max_rel_err(dev_bf16_to_f64(x_dev), exp) <= tol
     x_dev = to_dev_bf16(bits)
     ib = B.alloc_index(pl)
     log = B.litevggt_layers_run(ph, 2, im_dev, x_dev, ib, grad, score, ws)
     torch.cuda.synchronize()
     assert log == ref_log
-    assert max_rel_err(dev_bf16_to_f64(x_dev), ref_out) <= BF16_TOL
+    assert max_rel_err(dev_bf16_to_f64(x_dev), ref_out) <= tol
 
 
 # ------------------------------------------------------------------------- frame attention
@@ -644,13 +651,13 @@ def test_layers_run_with_frame_attention(B):
         torch.cuda.synchronize()
         idx = O.compute_index(im, t["x_in"], po)[0]
         exp = O.frame_layer(O.global_layer(t["x_in"], idx, po, _store_bf16), po, _store_bf16)
-        assert max_rel_err(dev_bf16_to_f64(x_dev), exp) <= BF16_TOL
+        assert max_rel_err(dev_bf16_to_f64(x_dev), exp) <= tol
     x_dev = to_dev_bf16(bits)
     ib = B.alloc_index(pl)
     log = B.litevggt_layers_run(ph, 2, im_dev, x_dev, ib, grad, score, ws)
     torch.cuda.synchronize()
     assert log == ref_log
-    assert max_rel_err(dev_bf16_to_f64(x_dev), ref_out) <= BF16_TOL
+    assert max_rel_err(dev_bf16_to_f64(x_dev), ref_out) <= tol
 
 
 # ------------------------------------------------------------- geometry-blind anchor policies
