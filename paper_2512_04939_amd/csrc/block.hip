@@ -415,15 +415,9 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
   int rc;
   const size_t lds = (size_t)kTile * kOutPitch > (size_t)kStages * kStageU4 * 16 ? (size_t)kTile * kOutPitch
                                                                                    : (size_t)kStages * kStageU4 * 16;
-  static bool lds_set = false;
-  if (!lds_set) {
-    if (hipFuncSetAttribute((const void *)k_gemm_bt<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds) != hipSuccess ||
-        hipFuncSetAttribute((const void *)k_gemm_bt<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds) != hipSuccess)
-      return LV_ERR_HIP;
-    lds_set = true;
-  }
+  static std::atomic<uint64_t> lds_done[2];
+  if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<false>, lds, lds_done[0]))) return rc;
+  if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<true>, lds, lds_done[1]))) return rc;
   const int nt_n = Nout / kTile;
   const int64_t nt_m = w.Mp / kTile;
   if (nt_m * nt_n >= ((int64_t)1 << 31) || w.Mp >= ((int64_t)1 << 31)) return LV_ERR_SHAPE;

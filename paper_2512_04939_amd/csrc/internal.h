@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/litevggt.h"
 
 namespace lv {
@@ -15,6 +17,20 @@ struct Dims {
 };
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Raise a kernel's dynamic LDS limit on the current device.  The attribute is per device, so
+// `done` (one per kernel, zero-initialised) remembers the devices that have it; setting it
+// twice is harmless, which makes concurrent first calls safe.
+inline int allow_dynamic_lds(const void *kernel, size_t bytes, std::atomic<uint64_t> &done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return LV_ERR_HIP;
+  const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t)1 << dev : 0;
+  if (bit && (done.load(std::memory_order_acquire) & bit)) return LV_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+    return LV_ERR_HIP;
+  done.fetch_or(bit, std::memory_order_release);
+  return LV_OK;
+}
 
 // importance.hip
 int launch_grad_map(const void *images, int img_dtype, const Dims &d, int patch, float *psi_g,

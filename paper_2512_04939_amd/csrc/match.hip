@@ -532,13 +532,8 @@ int launch_match(const uint16_t *x, const Dims &d, const litevggt_plan_t &pl,
   if (n_src > 0) {
     if (d.C % 32 != 0 || n_dst <= 0) return LV_ERR_SHAPE;
     const size_t lds = (size_t)kGStages * kGStageU4 * 16;        // 128 KB ring (reused for the final merge)
-    static bool lds_set = false;
-    if (!lds_set) {
-      if (hipFuncSetAttribute((const void *)k_match_sim, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds) != hipSuccess)
-        return LV_ERR_HIP;
-      lds_set = true;
-    }
+    static std::atomic<uint64_t> lds_done{0};
+    if (int rc = allow_dynamic_lds((const void *)k_match_sim, lds, lds_done)) return rc;
     const unsigned rows_grid = (unsigned)(((d.N + 3) / 4) < 16384 ? ((d.N + 3) / 4) : 16384);
     hipLaunchKernelGGL(k_inv_norm, dim3(rows_grid), dim3(256), 0, st, x, d.N, d.C, w.inv);
     const int64_t pkd = (int64_t)w.n_dst_pad * (d.C / 8), pks = (int64_t)w.n_src_pad * (d.C / 8);
