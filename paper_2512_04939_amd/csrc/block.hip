@@ -162,22 +162,32 @@ __global__ __launch_bounds__(64) void k_fp8_scales(uint32_t *__restrict__ sc, fl
 // units.  (Both operands use the same k order inside an operand, which is all a dot product
 // needs.)  The byte layout equals that of the bf16 packing of a matrix with K/2 columns, so
 // the tiled kernel fetches and reads both types the same way.  Rows n..n_pad-1 are zero.
+// A wave writes whole units (1 KB stores) and takes 4 consecutive units of its 32 rows (256
+// bytes of each bf16 row).  Grid: (row tiles, ceil(units / 16)).
 __global__ __launch_bounds__(256) void k_quant_pack_fp8(const uint16_t *__restrict__ x, int n, int n_pad,
                                                         int K, const uint32_t *__restrict__ inv,
                                                         u32x4 *__restrict__ packed) {
-  const int nch = K >> 4, KS = K >> 5;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (int64_t)n_pad * nch) return;
-  const int j = (int)(idx / nch), c = (int)(idx % nch);
-  u32x4 o = {0u, 0u, 0u, 0u};
-  if (j < n) {
-    const float r = __uint_as_float(*inv);
-    const u32x4 *src = (const u32x4 *)(x + (size_t)j * K) + 2 * c;
-    const u32x2 lo = quant8(src[0], r), hi = quant8(src[1], r);
-    o = u32x4{lo.x, lo.y, hi.x, hi.y};
+  const int KS = K >> 5;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = lane >> 5, rr = lane & 31;
+  const int t = blockIdx.x, j = t * 32 + rr;
+  const int s0 = (blockIdx.y * 4 + wave) * 4;
+  const float r = __uint_as_float(*inv);
+  u32x4 src[4][2];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    src[u][0] = src[u][1] = u32x4{0u, 0u, 0u, 0u};
+    if (j < n && s0 + u < KS) {
+      const u32x4 *p = (const u32x4 *)(x + (size_t)j * K) + 2 * ((s0 + u) * 2 + h);
+      src[u][0] = p[0];
+      src[u][1] = p[1];
+    }
   }
-  const int t = j >> 5, rr = j & 31, s2 = c >> 1, h = c & 1;
-  packed[((size_t)t * KS + s2) * 64 + h * 32 + rr] = o;
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (s0 + u < KS) {
+      const u32x2 lo = quant8(src[u][0], r), hi = quant8(src[u][1], r);
+      packed[((size_t)t * KS + s0 + u) * 64 + lane] = u32x4{lo.x, lo.y, hi.x, hi.y};
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -427,8 +437,7 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
       hipLaunchKernelGGL(k_amax_bf16, dim3(g), dim3(256), 0, st, (const u32x4 *)t, n16, dst);
     };
     auto quant = [&](const uint16_t *t, int64_t n, int64_t n_pad, const uint32_t *inv, u32x4 *dst) {
-      const int64_t pk = n_pad * (K / 16);
-      hipLaunchKernelGGL(k_quant_pack_fp8, dim3((unsigned)((pk + 255) / 256)), dim3(256), 0, st, t, (int)n,
+      hipLaunchKernelGGL(k_quant_pack_fp8, dim3((unsigned)(n_pad / 32), (unsigned)((K / 32 + 15) / 16)), dim3(256), 0, st, t, (int)n,
                          (int)n_pad, K, inv, dst);
     };
     hipLaunchKernelGGL(k_fp8_zero, dim3(1), dim3(64), 0, st, w.fp8sc);

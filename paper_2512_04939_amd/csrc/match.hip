@@ -39,28 +39,34 @@ __global__ __launch_bounds__(256) void k_inv_norm(const uint16_t *__restrict__ x
 
 // Gather token rows into fragment-major order: fragment (tile t of 32 rows, k-step s of 16
 // channels) is 1 KB contiguous, lane (h*32 + r) holds row r, channels 16s+8h .. 16s+8h+7.
-// idx_of == NULL packs rows 0..n-1 in place order.  Rows beyond n are zero.  inv_out (optional) receives the rows' inverse norms, 0 beyond n;
-// zero256 (optional) is a 256-word array to clear.
+// idx_of == NULL packs rows 0..n-1 in place order.  Rows beyond n are zero.  inv_out (optional)
+// receives the rows' inverse norms, 0 beyond n; zero256 (optional) is a 256-word array to clear.
+// A wave writes whole fragments (1 KB stores); it takes 4 consecutive k-steps of its 32 rows,
+// so the 128 bytes it needs of a row are one cache line read by 4 back-to-back loads.
+// Grid: (row tiles, ceil(KS / 16)); a workgroup's 4 waves take 4 k-steps each.
 __global__ __launch_bounds__(256) void k_pack_rows(const uint16_t *__restrict__ x,
                                                    const int32_t *__restrict__ idx_of,
                                                    const float *__restrict__ inv, int n, int n_pad,
                                                    int C, u32x4 *__restrict__ packed,
                                                    float *__restrict__ inv_out,
                                                    uint32_t *__restrict__ zero256) {
-  const int nch = C >> 3, KS = C >> 4;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (zero256 && idx < 256) zero256[idx] = 0u;   // the similarity kernel's team counters
-  if (idx >= (int64_t)n_pad * nch) return;
-  const int j = (int)(idx / nch), c = (int)(idx % nch);
-  u32x4 w = {0u, 0u, 0u, 0u};
+  const int KS = C >> 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = lane >> 5, r = lane & 31;
+  const int t = blockIdx.x, j = t * 32 + r;
+  if (zero256 && blockIdx.x == 0 && blockIdx.y == 0) zero256[threadIdx.x] = 0u;   // the similarity kernel's team counters
   int row = -1;
-  if (j < n) {
-    row = idx_of ? idx_of[j] : j;
-    w = ((const u32x4 *)(x + (size_t)row * C))[c];
+  if (j < n) row = idx_of ? idx_of[j] : j;
+  if (inv_out && blockIdx.y == 0 && wave == 0 && h == 0 && j < n_pad) inv_out[j] = row >= 0 ? inv[row] : 0.f;
+  const int s0 = (blockIdx.y * 4 + wave) * 4;
+  u32x4 w[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    w[u] = u32x4{0u, 0u, 0u, 0u};
+    if (row >= 0 && s0 + u < KS) w[u] = ((const u32x4 *)(x + (size_t)row * C))[(s0 + u) * 2 + h];
   }
-  const int t = j >> 5, r = j & 31, s = c >> 1, h = c & 1;
-  packed[((size_t)t * KS + s) * 64 + h * 32 + r] = w;
-  if (inv_out && c == 0) inv_out[j] = row >= 0 ? inv[row] : 0.f;
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (s0 + u < KS) packed[((size_t)t * KS + s0 + u) * 64 + lane] = w[u];
 }
 
 __device__ __forceinline__ void top2_insert_any(Top2 &t, float v, int i) {
@@ -77,9 +83,8 @@ __device__ __forceinline__ void top2_insert_any(Top2 &t, float v, int i) {
 }
 
 int launch_pack_rows(const uint16_t *x, int64_t n, int64_t n_pad, int C, void *packed, hipStream_t st) {
-  const int64_t pk = n_pad * (C / 8);
-  if (n_pad >= ((int64_t)1 << 31) || (pk + 255) / 256 >= ((int64_t)1 << 31)) return LV_ERR_SHAPE;
-  hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)((pk + 255) / 256)), dim3(256), 0, st, x,
+  if (n_pad >= ((int64_t)1 << 31) || n_pad % 32 != 0 || C % 16 != 0) return LV_ERR_SHAPE;
+  hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)(n_pad / 32), (unsigned)((C / 16 + 15) / 16)), dim3(256), 0, st, x,
                      (const int32_t *)nullptr, (const float *)nullptr, (int)n, (int)n_pad, C,
                      (u32x4 *)packed,
                      (float *)nullptr, (uint32_t *)nullptr);
@@ -406,29 +411,41 @@ __global__ __launch_bounds__(64) void k_radix_hist(const uint32_t *__restrict__ 
   for (int d = lane; d < 256; d += 64) hist[(size_t)d * nchunks + blockIdx.x] = h[d];
 }
 
-// exclusive prefix sum over hist[256*nchunks] in place (digit-major), single workgroup
+// exclusive prefix sum over hist[256*nchunks] in place (digit-major), single workgroup: tiles
+// of 4096 elements, 4 consecutive elements per thread, the running total carried from tile to tile
 __global__ __launch_bounds__(1024) void k_radix_scan(uint32_t *__restrict__ hist, int64_t n) {
   __shared__ uint32_t wtot[16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int64_t per = (n + 1023) / 1024;
-  const int64_t b = min((int64_t)tid * per, n), e = min(b + per, n);
-  uint32_t sum = 0;
-  for (int64_t i = b; i < e; ++i) sum += hist[i];
-  uint32_t inc = sum;
+  uint32_t carry = 0;
+  for (int64_t t0 = 0; t0 < n; t0 += 4096) {
+    const int64_t i = t0 + (int64_t)tid * 4;
+    uint32_t v[4];
 #pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    uint32_t v = __shfl_up(inc, o, 64);
-    if (lane >= o) inc += v;
-  }
-  if (lane == 63) wtot[wave] = inc;
-  __syncthreads();
-  uint32_t base = 0;
-  for (int w = 0; w < wave; ++w) base += wtot[w];
-  uint32_t run = base + inc - sum;
-  for (int64_t i = b; i < e; ++i) {
-    uint32_t v = hist[i];
-    hist[i] = run;
-    run += v;
+    for (int u = 0; u < 4; ++u) v[u] = i + u < n ? hist[i + u] : 0u;
+    const uint32_t sum = v[0] + v[1] + v[2] + v[3];
+    uint32_t inc = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t up = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += up;
+    }
+    if (lane == 63) wtot[wave] = inc;
+    __syncthreads();
+    uint32_t base = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+      const uint32_t wt = wtot[w];
+      if (w < wave) base += wt;
+      total += wt;
+    }
+    uint32_t run = carry + base + inc - sum;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (i + u < n) hist[i + u] = run;
+      run += v[u];
+    }
+    carry += total;
+    __syncthreads();   // wtot is rewritten by the next tile
   }
 }
 
@@ -536,10 +553,10 @@ int launch_match(const uint16_t *x, const Dims &d, const litevggt_plan_t &pl,
     if (int rc = allow_dynamic_lds((const void *)k_match_sim, lds, lds_done)) return rc;
     const unsigned rows_grid = (unsigned)(((d.N + 3) / 4) < 16384 ? ((d.N + 3) / 4) : 16384);
     hipLaunchKernelGGL(k_inv_norm, dim3(rows_grid), dim3(256), 0, st, x, d.N, d.C, w.inv);
-    const int64_t pkd = (int64_t)w.n_dst_pad * (d.C / 8), pks = (int64_t)w.n_src_pad * (d.C / 8);
-    hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)((pkd + 255) / 256)), dim3(256), 0, st, x,
+    const unsigned ks_groups = (unsigned)((d.C / 16 + 15) / 16);
+    hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)(w.n_dst_pad / 32), ks_groups), dim3(256), 0, st, x,
                        ix.dst_idx, w.inv, n_dst, w.n_dst_pad, d.C, w.dstp, w.invd, w.team_ctr);
-    hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)((pks + 255) / 256)), dim3(256), 0, st, x,
+    hipLaunchKernelGGL(k_pack_rows, dim3((unsigned)(w.n_src_pad / 32), ks_groups), dim3(256), 0, st, x,
                        ix.src_idx, w.inv, n_src, w.n_src_pad, d.C, w.srcp, (float *)nullptr,
                        (uint32_t *)nullptr);
     // One workgroup per CU, all resident at once; the workgroups the hardware deals to one

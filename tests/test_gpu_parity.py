@@ -651,13 +651,13 @@ def test_layers_run_with_frame_attention(B):
         torch.cuda.synchronize()
         idx = O.compute_index(im, t["x_in"], po)[0]
         exp = O.frame_layer(O.global_layer(t["x_in"], idx, po, _store_bf16), po, _store_bf16)
-        assert max_rel_err(dev_bf16_to_f64(x_dev), exp) <= tol
+        assert max_rel_err(dev_bf16_to_f64(x_dev), exp) <= BF16_TOL
     x_dev = to_dev_bf16(bits)
     ib = B.alloc_index(pl)
     log = B.litevggt_layers_run(ph, 2, im_dev, x_dev, ib, grad, score, ws)
     torch.cuda.synchronize()
     assert log == ref_log
-    assert max_rel_err(dev_bf16_to_f64(x_dev), ref_out) <= tol
+    assert max_rel_err(dev_bf16_to_f64(x_dev), ref_out) <= BF16_TOL
 
 
 # ------------------------------------------------------------- geometry-blind anchor policies
