@@ -1,6 +1,8 @@
-"""Parity at the benchmark's full size (1000 frames, N = 1,374,000, M = 143,232) in the launch
-configuration bench.py times: every step runs on the whole sequence, the oracle checks
-sampled outputs it can compute one by one, plus structural properties that hold at any size."""
+"""Parity at the benchmark configurations' full sizes (32, 100, 500 and 1000 frames of 37 x 37
+patches, dim 1024; 100 frames at merge ratios 0.5, 0.75, 0.9), in the launch configuration
+bench.py times: every step runs on the whole sequence, the oracle checks sampled outputs it can
+compute one by one, plus structural properties that hold at any size.  At 100 frames the
+unmerged attention (the speedup baseline) is sampled as well."""
 from __future__ import annotations
 
 import numpy as np
@@ -24,16 +26,23 @@ def _host_bits(t) -> np.ndarray:
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def test_full_size_steps_against_sampled_oracle():
+CASES = [("f32", {}), ("f100", {"merge_ratio": 0.5}), ("f100", {"merge_ratio": 0.75}), ("f100", {}),
+         ("f500", {}), ("f1000", {})]
+
+
+@pytest.mark.parametrize("name,over", CASES, ids=[n + "".join(f"-r{v}" for v in o.values()) for n, o in CASES])
+def test_full_size_steps_against_sampled_oracle(name, over):
     import torch
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     from paper_2512_04939_amd import binding as B
-    wl = synth.workload("f1000")
+    wl = synth.workload(name, **over)
     po, ph = oracle_params(wl), hip_params(wl)
     pl = B.litevggt_plan(ph)
     F, T, P, S, C, heads = wl.frames, wl.tokens_per_frame, wl.patches, wl.n_special, wl.dim, wl.heads
     N, M = pl.N, pl.M
-    assert (N, M, pl.n_dst, pl.n_src) == (1374000, 143232, 101269, 1230768)
+    if name == "f1000":
+        assert (N, M, pl.n_dst, pl.n_src) == (1374000, 143232, 101269, 1230768)
+    print(f"{name} {over}: N={N} M={M} n_dst={pl.n_dst} n_src={pl.n_src}", flush=True)
     gen = synth.Generator(wl)
     bits = gen.tokens(threads=16)                        # [N, C] bf16 bit patterns
     x = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
@@ -60,7 +69,7 @@ def test_full_size_steps_against_sampled_oracle():
     torch.cuda.synchronize()
 
     # ---- importance: sampled frames (the map of a frame depends on that frame only)
-    frames = np.array([0, 1, 499, 998, 999])
+    frames = np.array([0, 1, F // 2, F - 2, F - 1])
     rows = np.concatenate([np.arange(f * T, (f + 1) * T) for f in frames])
     psub = oracle_params(synth.Workload(**{**wl.__dict__, "frames": len(frames)}))
     want, _ = O.importance(gen.images(frames), _f64(bits[rows]), psub)
@@ -79,7 +88,7 @@ def test_full_size_steps_against_sampled_oracle():
     assert np.array_equal(np.flatnonzero(flat == O.ROLE_DST), dst_idx)
     assert np.array_equal(np.flatnonzero(flat != O.ROLE_SRC), kept_idx)
 
-    # ---- match: sampled src tokens against all 101,269 dst tokens
+    # ---- match: sampled src tokens against all dst tokens
     pick = np.sort(rng.choice(pl.n_src, size=96, replace=False))
     small = _f64(bits[np.concatenate([dst_idx, src_idx[pick]])])
     mt = O.match(small, np.arange(pl.n_dst), pl.n_dst + np.arange(len(pick)))
@@ -125,3 +134,17 @@ def test_full_size_steps_against_sampled_oracle():
     toks = np.sort(rng.choice(N, size=4096, replace=False))
     s = synth.bf16_bits_to_f32(bits[toks]) + synth.bf16_bits_to_f32(yb[slot_of[toks]])
     assert np.array_equal(_host_bits(out[torch.from_numpy(toks).cuda()]), synth.f32_to_bf16_bits(s))
+
+    # ---- the speedup baseline: unmerged attention over all N tokens, sampled rows (100 frames)
+    if name == "f100" and not over:
+        ws_u = B.alloc_ws(B.litevggt_attn_ws_bytes(ph, N))
+        yu = torch.empty_like(x)
+        B.litevggt_global_attn(ph, N, x, x, x, yu, ws_u)
+        torch.cuda.synchronize()
+        yub = _host_bits(yu)
+        qrows = np.sort(rng.choice(N, size=8, replace=False))
+        cols = slice(5 * 64, 6 * 64)
+        xh = _f64(bits[:, cols]).reshape(N, 1, 64)
+        qk = O.round_bf16(O.qk_normalize(xh))
+        want_u = O.attention(qk, qk, xh, rows=qrows).reshape(len(qrows), 64)
+        assert max_rel_err(_f64(yub[qrows][:, cols]), want_u) <= BF16_TOL
