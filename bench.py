@@ -51,6 +51,9 @@ def parse_args():
                          "scales from the tensors; fp8-delayed: input scales from an 80-step amax history)")
     ap.add_argument("--frame-attn", action="store_true",
                     help="run a frame attention after every global layer (not part of the metric's default)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one step into a HIP graph and time its replays "
+                         "(reported as config.graph_replay_ms_per_step; `value` stays the eager run)")
     ap.add_argument("--no-unmerged", action="store_true",
                     help="skip the one-launch unmerged attention baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -244,6 +247,24 @@ def main():
     ms_step = 1e3 * total_s / args.steps
     finite = bool(torch.isfinite(x.float()).all().item())
 
+    graph_ms = None
+    if args.graph:      # the driver only enqueues kernels, so a step can be captured and replayed
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                x.copy_(x0)
+                B.litevggt_layers_run(ph, L, im, x, ib, grad, score, ws)
+        torch.cuda.current_stream().wait_stream(side)
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+
     # per-step durations from the driver's events
     E = B.EVENTS_PER_LAYER
     names = {"importance": (B.EV_LAYER_BEGIN, B.EV_IMPORTANCE_END),
@@ -331,6 +352,7 @@ def main():
                    "anchor_policy": args.anchor_policy, "frame_attn": bool(args.frame_attn), "block": bool(args.block),
                    "linear_dtype": args.linear_dtype if args.block else None,
                    "refresh_log": log, "output_finite": finite,
+                   "graph_replay_ms_per_step": graph_ms,
                    "peak_hbm_alloc_gib": torch.cuda.max_memory_allocated() / 2 ** 30,
                    "input_generation_s": gen_s,
                    "h2d_upload_s": h2d_s, "h2d_upload_gbs": h2d_bytes / h2d_s / 1e9,

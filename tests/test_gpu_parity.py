@@ -793,3 +793,49 @@ def test_runs_are_bit_reproducible(B):
         outs.append((x_dev.clone(), ib.anchor_of.clone(), ib.group_mem.clone()))
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+def test_layer_driver_replays_from_a_hip_graph(B):
+    """The driver only enqueues kernels on the caller's stream (no synchronisation, no memset
+    nodes, scratch cleared by kernels), so a caller may capture it.  Three replays, with eager
+    work and synchronisations of the program between them, each against the eager result."""
+    import torch
+    wl = WORKLOADS["small_r09"]()
+    bits, xf, im = stored_inputs(wl)
+    ph = hip_params(wl, refresh_interval=2)
+    pl = B.litevggt_plan(ph)
+    im_dev = torch.from_numpy(im).cuda()
+    ws = B.alloc_ws(pl.ws_bytes)
+    ib = B.alloc_index(pl)
+    grad = torch.zeros(wl.frames, wl.patches, device="cuda")
+    score = torch.zeros(wl.frames, wl.patches, device="cuda")
+    x_in = to_dev_bf16(bits)
+    x_dev = x_in.clone()
+    B.litevggt_layers_run(ph, 3, im_dev, x_dev, ib, grad, score, ws)      # eager (also warms up)
+    torch.cuda.synchronize()
+    want = (x_dev.clone(), ib.anchor_of.clone(), ib.group_mem.clone())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        x_dev.copy_(x_in)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            B.litevggt_layers_run(ph, 3, im_dev, x_dev, ib, grad, score, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        x_dev.copy_(x_in)                      # the driver updates x in place
+        ib.anchor_of.fill_(-7)
+        ib.group_mem.fill_(-7)
+        ws.random_(0, 255)                     # scratch contents must not matter
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(x_dev, want[0]), rep
+        assert torch.equal(ib.anchor_of, want[1]) and torch.equal(ib.group_mem, want[2]), rep
+        # eager work of the program between the replays
+        y = torch.empty_like(x_dev)
+        B.litevggt_unmerge(ph, torch.zeros(pl.M, wl.dim, dtype=torch.bfloat16, device="cuda"), ib, x_dev, y)
+        torch.cuda.synchronize()
+        assert torch.equal(y, x_dev)
