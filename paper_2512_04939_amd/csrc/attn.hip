@@ -650,7 +650,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // ---------------------------------------------------------------------------------------
 // FP8 (E4M3, OCP "fn": bias 7, max 448) variant: q, k, v are quantised per tensor with
 // scale = amax/448 taken in the same call, the softmax weights with a fixed scale 2^8; the
-// MFMAs are v_mfma_f32_32x32x16_fp8_fp8, everything else (scores, max, sums, O) stays fp32.
+// MFMAs are v_mfma_f32_32x32x64_f8f6f4, everything else (scores, max, sums, O) stays fp32.
 // ---------------------------------------------------------------------------------------
 constexpr float kFp8PShift = 8.0f;   // weights are stored as 2^8 * p, p <= 1 at the reference
 constexpr float kFp8Raise = 0.75f;   // 2^(8 + 0.75) < 448: the reference follows the maximum closely
@@ -737,7 +737,17 @@ __global__ __launch_bounds__(256) void k_attn_pack_fp8(const uint16_t *__restric
   vp[tile + (u * 2 + dt) * kFragU4 + lane] = u32x2{w[0], w[1]};
 }
 
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+// four 8-byte operand pieces side by side: the 32-byte operand of v_mfma_f32_32x32x64_f8f6f4
+__device__ __forceinline__ i32x8 cat_fp8(u32x2 a, u32x2 b, u32x2 c, u32x2 d) {
+  return i32x8{(int)a.x, (int)a.y, (int)b.x, (int)b.y, (int)c.x, (int)c.y, (int)d.x, (int)d.y};
+}
+
 // Same structure as k_attn_bf16 (two phase groups, lazily raised reference) on fp8 operands.
+// Each contraction is one v_mfma_f32_32x32x64_f8f6f4 (contraction length 64: all channels of a
+// head for the scores, all keys of a stage for the output), which runs at twice the rate of the
+// 32x32x16 fp8 form; the order of the 64 contraction indices inside an operand is the same for
+// both operands (piece p of the packed fragments = indices 16p .. 16p+15 in fragment order).
 __global__ __launch_bounds__(512) void k_attn_fp8(
     const uint16_t *__restrict__ q, const u32x2 *__restrict__ kp, const u32x2 *__restrict__ vp,
     uint16_t *__restrict__ o, int64_t n, int heads, int n_kt, int nqb, float c_in, int qk_norm,
@@ -763,7 +773,7 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
   const float c = c_in * (1.0f / inv_sq) * (1.0f / fp8_scale_inv(amax[1]));
   const float out_scale = 1.0f / fp8_scale_inv(amax[2]);
 
-  long qf[2][4];
+  i32x8 qf8[2];
 #pragma unroll
   for (int sub = 0; sub < 2; ++sub) {
     const int64_t row = min(q0 + sub * 32 + ql, n - 1);
@@ -773,9 +783,10 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
     for (int s = 0; s < 4; ++s) w[s] = *(const u32x4 *)(qp + 16 * s);
     float ss = (sumsq8(w[0]) + sumsq8(w[1])) + (sumsq8(w[2]) + sumsq8(w[3]));
     ss += __shfl_xor(ss, 32, 64);
+    u32x2 q8[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      qf[sub][s] = __builtin_bit_cast(long, quant8(norm8(w[s], ss, qk_norm), inv_sq));
+    for (int s = 0; s < 4; ++s) q8[s] = quant8(norm8(w[s], ss, qk_norm), inv_sq);
+    qf8[sub] = cat_fp8(q8[0], q8[1], q8[2], q8[3]);
   }
 
   f32x16 oacc[2][2];
@@ -811,20 +822,17 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
       u32x2 vf[8];
 #pragma unroll
       for (int f = 0; f < 8; ++f) vf[f] = vt[f * kFragU4];
+      // one MFMA per (query block, d tile) over all 64 keys: the operands are the four 16-key
+      // pieces (kt2, u) side by side, in the same order for V and for the weights
 #pragma unroll
-      for (int kt2 = 0; kt2 < 2; ++kt2)
+      for (int dt = 0; dt < 2; ++dt) {
+        const i32x8 a = cat_fp8(vf[0 * 2 + dt], vf[1 * 2 + dt], vf[2 * 2 + dt], vf[3 * 2 + dt]);
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int dt = 0; dt < 2; ++dt) {
-            const long a = __builtin_bit_cast(long, vf[(kt2 * 2 + u) * 2 + dt]);
-            oacc[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(
-                a, __builtin_bit_cast(long, pb[0][kt2][u]), oacc[0][dt], 0, 0, 0);
-            oacc[1][dt] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(
-                a, __builtin_bit_cast(long, pb[1][kt2][u]), oacc[1][dt], 0, 0, 0);
-          }
-      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+        for (int sub = 0; sub < 2; ++sub)
+          oacc[sub][dt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+              a, cat_fp8(pb[sub][0][0], pb[sub][0][1], pb[sub][1][0], pb[sub][1][1]), oacc[sub][dt], 0, 0, 0,
+              0, 0, 0);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
     if (j < nkv) {
@@ -832,21 +840,15 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
       u32x2 kf[8];
 #pragma unroll
       for (int f = 0; f < 8; ++f) kf[f] = kt[f * kFragU4];
+      // one MFMA per (key tile, query block) over all 64 channels: the four k-step pieces side by side
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kt2 = 0; kt2 < 2; ++kt2) {
+        const i32x8 a = cat_fp8(kf[kt2 * 4], kf[kt2 * 4 + 1], kf[kt2 * 4 + 2], kf[kt2 * 4 + 3]);
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[kt2][sub][r] = 0.f;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const long a = __builtin_bit_cast(long, kf[kt2 * 4 + s]);
-          sacc[kt2][0] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, qf[0][s], sacc[kt2][0], 0, 0, 0);
-          sacc[kt2][1] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, qf[1][s], sacc[kt2][1], 0, 0, 0);
-        }
+          sacc[kt2][sub] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, qf8[sub], zero, 0, 0, 0, 0, 0, 0);
       }
-      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
     }
     asm volatile("" : "+v"(sacc[0][0]), "+v"(sacc[0][1]), "+v"(sacc[1][0]), "+v"(sacc[1][1]),
                  "+v"(oacc[0][0]), "+v"(oacc[0][1]), "+v"(oacc[1][0]), "+v"(oacc[1][1]));
