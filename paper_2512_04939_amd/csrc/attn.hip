@@ -660,6 +660,11 @@ __device__ __forceinline__ u32x4 norm8(const u32x4 w, float ss_head, int qk_norm
   return qk_norm ? scale8(w, 1.0f / sqrtf(ss_head * (1.0f / 64.0f) + kQkEps)) : w;
 }
 
+__global__ __launch_bounds__(256) void k_zero_words(uint32_t *p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
 __global__ void k_attn_amax_zero(uint32_t *amax) {
   if (threadIdx.x < 4) amax[threadIdx.x] = 0u;
 }
@@ -709,8 +714,10 @@ __global__ __launch_bounds__(256) void k_attn_pack_fp8(const uint16_t *__restric
                                                        const uint16_t *__restrict__ v, int64_t n,
                                                        int heads, int n_kt, int qk_norm,
                                                        const uint32_t *__restrict__ amax,
+                                                       const uint32_t *__restrict__ gate,
                                                        u32x2 *__restrict__ kp, u32x2 *__restrict__ vp) {
   __shared__ __attribute__((aligned(8))) uint8_t vt[kKT][72];
+  if (gate && *gate == 0u) return;   // second pass with nothing flagged: no one will read the result
   const int kt = blockIdx.x, head = blockIdx.y, t = threadIdx.x;
   const int C = heads * 64;
   const int key = t >> 3, chunk = t & 7;
@@ -737,7 +744,6 @@ __global__ __launch_bounds__(256) void k_attn_pack_fp8(const uint16_t *__restric
   vp[tile + (u * 2 + dt) * kFragU4 + lane] = u32x2{w[0], w[1]};
 }
 
-typedef __attribute__((ext_vector_type(8))) int i32x8;
 // four 8-byte operand pieces side by side: the 32-byte operand of v_mfma_f32_32x32x64_f8f6f4
 __device__ __forceinline__ i32x8 cat_fp8(u32x2 a, u32x2 b, u32x2 c, u32x2 d) {
   return i32x8{(int)a.x, (int)a.y, (int)b.x, (int)b.y, (int)c.x, (int)c.y, (int)d.x, (int)d.y};
@@ -751,7 +757,7 @@ __device__ __forceinline__ i32x8 cat_fp8(u32x2 a, u32x2 b, u32x2 c, u32x2 d) {
 __global__ __launch_bounds__(512) void k_attn_fp8(
     const uint16_t *__restrict__ q, const u32x2 *__restrict__ kp, const u32x2 *__restrict__ vp,
     uint16_t *__restrict__ o, int64_t n, int heads, int n_kt, int nqb, float c_in, int qk_norm,
-    const uint32_t *__restrict__ amax) {
+    const uint32_t *__restrict__ amax, const uint32_t *__restrict__ redo) {
   __shared__ u32x2 ks[kKSlots][8 * kFragU4];
   __shared__ u32x2 vs[kVSlots][8 * kFragU4];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ql = lane & 31;
@@ -767,6 +773,10 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
     head = blockIdx.x / nqb;
     qb = blockIdx.x % nqb;
   }
+  // second pass behind the bounded kernel: only the query blocks it has flagged (one flag per
+  // 256 queries; the whole workgroup takes the same branch, before any barrier)
+  if (redo && redo[(size_t)head * (2 * nqb) + 2 * qb] == 0u && redo[(size_t)head * (2 * nqb) + 2 * qb + 1] == 0u)
+    return;
   const int64_t q0 = (int64_t)qb * kQB + wave * kQW;
   const float inv_sq = fp8_scale_inv(amax[0]);
   // scores come out in units of scale_q*scale_k; fold both into the exponent scale
@@ -966,12 +976,307 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
 }
 
 
+// ---------------------------------------------------------------------------------------
+// Bounded-score FP8 kernel (qk_norm).  With unit-RMS heads a score cannot exceed
+// B = 73 * softmax_scale (Cauchy-Schwarz, with room for the bf16 and E4M3 roundings of the
+// normalised rows), so the weights are exponentiated against the fixed reference B: stored weight =
+// 2^(score - B) * 2^8.75 <= 430, no running maximum, no rescaling, no branches.  E4M3 keeps 3
+// mantissa bits down to 2^-6 and flushes below 2^-10, so a row is served well when the scores
+// that carry its mass are within ~15 binades of B.  The sum L of a row's stored weights
+// tells: rows with L < 1 (the total mass of the row sits more than 8.75 binades below the bound,
+// where single weights lose precision and nothing averages the loss out) are flagged per 256-
+// query block, and k_attn_fp8 (running maximum) recomputes the flagged blocks afterwards.  With
+// q = k (the layer driver) every row has the weight 2^8.75 of its own key and nothing is flagged.
+//
+// Structure as k_attn_bf16_bounded with a 64-key stage in place of a 32-key tile (the FP8 MFMA
+// contracts 64 keys at once): a wave owns two 32-query blocks half a stage apart,
+//   A(t): weights of block 0, stage t   ||  PV of block 1, stage t-1;  scores of block 1, stage t
+//   B(t): weights of block 1, stage t   ||  PV of block 0, stage t;    scores of block 0, stage t+1
+// K and V are packed so that an MFMA operand is two 16-byte pieces per lane:
+//   K piece (stage, kt2, j): lane (h*32+key) holds channels 32j+8h .. +8 and 32j+16+8h .. +8 of
+//                            key 64 stage + 32 kt2 + key
+//   V piece (stage, dt, kt2): lane (h*32+dr) holds column 32dt+dr of the 16 keys of tile
+//                            2 stage + kt2 that the lane's accumulator rows map to (u = 0, 1)
+// ---------------------------------------------------------------------------------------
+constexpr int kF8Stages = 4;          // LDS ring of 64-key stages (4 KB of K, 4 KB of V each)
+constexpr float kF8Bound = 73.0f;     // |q.k| <= 64 (1 + 2^-8)^2 (1 + 2^-4)^2 < 73: unit-RMS rows rounded to bf16,
+                                      // then to E4M3 (every element at most 2^-4 off, all in the same direction)
+constexpr float kF8Top = 8.75f;       // a weight at the bound is stored as 2^8.75
+
+__global__ __launch_bounds__(256) void k_attn_pack_fp8b(const uint16_t *__restrict__ k,
+                                                        const uint16_t *__restrict__ v, int64_t n,
+                                                        int heads, int n_kt,
+                                                        const uint32_t *__restrict__ amax,
+                                                        u32x2 *__restrict__ kp, u32x2 *__restrict__ vp) {
+  __shared__ __attribute__((aligned(8))) uint8_t vt[kKT][72];
+  const int kt = blockIdx.x, head = blockIdx.y, t = threadIdx.x;
+  const int C = heads * 64;
+  const int key = t >> 3, chunk = t & 7;
+  const int64_t row = (int64_t)kt * kKT + key;
+  u32x4 wk = {0u, 0u, 0u, 0u}, wv = {0u, 0u, 0u, 0u};
+  if (row < n) {
+    wk = *(const u32x4 *)(k + (size_t)row * C + head * 64 + chunk * 8);
+    wv = *(const u32x4 *)(v + (size_t)row * C + head * 64 + chunk * 8);
+  }
+  float ss = sumsq8(wk);
+  for (int o = 1; o < 8; o <<= 1) ss += __shfl_xor(ss, o, 64);
+  wk = norm8(wk, ss, 1);
+  const int stage = kt >> 1, kt2 = kt & 1;
+  const size_t base = ((size_t)head * (n_kt >> 1) + stage) * 4 * 64;   // in 16-byte pieces
+  const int s = chunk >> 1, hh = chunk & 1;
+  kp[2 * (base + (size_t)(kt2 * 2 + (s >> 1)) * 64 + hh * 32 + key) + (s & 1)] = quant8(wk, fp8_scale_inv(amax[1]));
+  *(u32x2 *)&vt[key][chunk * 8] = quant8(wv, fp8_scale_inv(amax[2]));
+  __syncthreads();
+  const int u = t >> 7, dt = (t >> 6) & 1, lane = t & 63, h = lane >> 5, dr = lane & 31;
+  uint32_t w[2] = {0u, 0u};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int k0 = 16 * u + 8 * (e >> 2) + 4 * h + (e & 3);
+    w[e >> 2] |= (uint32_t)vt[k0][32 * dt + dr] << (8 * (e & 3));
+  }
+  vp[2 * (base + (size_t)(dt * 2 + kt2) * 64 + lane) + u] = u32x2{w[0], w[1]};
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_fp8_bounded(
+    const uint16_t *__restrict__ q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp,
+    uint16_t *__restrict__ o, int64_t n, int heads, int nkv, int nqb, float c_in,
+    const uint32_t *__restrict__ amax, uint32_t *__restrict__ redo, int redo_stride,
+    uint32_t *__restrict__ redo_any) {
+  __shared__ u32x4 ks[kF8Stages][4 * 64];
+  __shared__ u32x4 vs[kF8Stages][4 * 64];
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ql = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int C = heads * 64;
+  int head, qb;
+  if ((heads & 7) == 0) {
+    const int hp = heads >> 3, xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    head = xcd * hp + local / nqb;
+    qb = local % nqb;
+  } else {
+    head = blockIdx.x / nqb;
+    qb = blockIdx.x % nqb;
+  }
+  const int64_t q0 = (int64_t)qb * kBQB + wave * kQW;
+  const float inv_sq = fp8_scale_inv(amax[0]);
+  const float cs = c_in * (1.0f / inv_sq) * (1.0f / fp8_scale_inv(amax[1]));   // code product -> log2 units
+  const float ref = kF8Bound * c_in - kF8Top;
+  const float out_scale = 1.0f / fp8_scale_inv(amax[2]);
+
+  i32x8 qf8[2];
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) {
+    const int64_t row = min(q0 + sub * 32 + ql, n - 1);
+    const uint16_t *qp = q + (size_t)row * C + head * 64 + 8 * h;
+    u32x4 w[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) w[s] = *(const u32x4 *)(qp + 16 * s);
+    float ss = (sumsq8(w[0]) + sumsq8(w[1])) + (sumsq8(w[2]) + sumsq8(w[3]));
+    ss += __shfl_xor(ss, 32, 64);
+    u32x2 q8[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) q8[s] = quant8(norm8(w[s], ss, 1), inv_sq);
+    qf8[sub] = cat_fp8(q8[0], q8[1], q8[2], q8[3]);
+  }
+
+  f32x16 oacc[2][2];
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[sub][dt][r] = 0.f;
+  // Row sums come from the matrix pipe as well: a V fragment of ones (E4M3 1.0 = 0x38) makes
+  // every accumulator row the sum of the E4M3 weights of the lane's query.  The normaliser is
+  // then the sum of exactly the weights that multiply V: with a fixed reference the largest
+  // weight of a row is not a power of two (as it is relative to a running maximum) and carries
+  // up to 3 % rounding error, which cancels in this ratio and would not against the fp32 sum.
+  f32x16 lacc[2];
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) lacc[sub][r] = 0.f;
+  const int kOne = 0x38383838;
+  const i32x8 ones8 = {kOne, kOne, kOne, kOne, kOne, kOne, kOne, kOne};
+  const f32x16 kZero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  const u32x4 *kh = kp + (size_t)head * nkv * 4 * 64;
+  const u32x4 *vh = vp + (size_t)head * nkv * 4 * 64;
+  // one stage = 256 pieces of K and 256 of V: one direct-to-LDS load of each per thread
+  // (stage `src` goes to the ring slot of stage `as`: past the end the last stage is fetched
+  // again, into a slot nobody reads, so that the loop body has no branches)
+  auto fetch_k = [&](int src, int as) {
+    __builtin_amdgcn_global_load_lds(kh + (size_t)src * 256 + tid, &ks[as & (kF8Stages - 1)][wave * 64], 16, 0, 0);
+  };
+  auto fetch_v = [&](int src, int as) {
+    __builtin_amdgcn_global_load_lds(vh + (size_t)src * 256 + tid, &vs[as & (kF8Stages - 1)][wave * 64], 16, 0, 0);
+  };
+
+  f32x16 sacc[2];      // [32-key half]: the scores in flight (of one query block at a time)
+  i32x8 pb[2];         // [query block]: E4M3 weights of its current stage
+  u32x4 fv[4], fk[4];  // the pieces of one stage of V and of K
+
+  auto load4 = [&](const u32x4 *base, u32x4(&dst)[4]) {
+#pragma unroll
+    for (int f = 0; f < 4; ++f) dst[f] = base[f * 64];
+  };
+  auto mma_s = [&](int sub) {
+#pragma unroll
+    for (int kt2 = 0; kt2 < 2; ++kt2)
+      sacc[kt2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cat8(fk[2 * kt2], fk[2 * kt2 + 1]), qf8[sub],
+                                                                  kZero, 0, 0, 0, 0, 0, 0);
+  };
+  auto mma_pv = [&](int sub) {
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+      oacc[sub][dt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cat8(fv[2 * dt], fv[2 * dt + 1]), pb[sub],
+                                                                      oacc[sub][dt], 0, 0, 0, 0, 0, 0);
+    lacc[sub] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones8, pb[sub], lacc[sub], 0, 0, 0, 0, 0, 0);
+  };
+  auto mask_tail = [&](int t) {   // keys beyond the sequence end
+    if ((int64_t)(t + 1) * kKV > n) {
+#pragma unroll
+      for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int64_t key = (int64_t)t * kKV + kt2 * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+          if (key >= n) sacc[kt2][r] = -INFINITY;
+        }
+    }
+  };
+  // exp2 against the fixed reference, E4M3 pack
+  auto weights = [&](int sub) {
+#pragma unroll
+    for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        float pv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt2][8 * u + e], cs, -ref));
+        pb[sub][(kt2 * 2 + u) * 2] = (int)cvt4_fp8(pv[0], pv[1], pv[2], pv[3]);
+        pb[sub][(kt2 * 2 + u) * 2 + 1] = (int)cvt4_fp8(pv[4], pv[5], pv[6], pv[7]);
+      }
+  };
+  auto wait4 = [&](u32x4(&f)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : : "memory");
+  };
+  // A phase is: the MFMAs that consume what the phase before produced, the fragment read for
+  // the next consumer (by hand, waited for a whole VALU part later), the VALU part (the longer
+  // one: 32 fma, 32 exp2, 16 packs per lane against 3 + 2 MFMAs of 64 cycles), then the score
+  // MFMAs whose results the next phase's VALU part turns into weights.  Scores of only one
+  // query block are alive at a time, and one stage of K and of V.
+  const uint32_t ks_lane = lds_addr(&ks[0][lane]), vs_lane = lds_addr(&vs[0][lane]);
+  auto slot_off = [&](int t) { return (uint32_t)((t & (kF8Stages - 1)) * 4 * 64 * 16); };
+  // B(t): PV(t) of block 0; read K(t+1); weights of block 1 (stage t); scores(t+1) of block 0
+  auto phase_b = [&](int t, bool last) {
+    __builtin_amdgcn_sched_barrier(0);
+    wait4(fv);                                            // V(t), read in A(t)
+    mma_pv(0);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_read4_async(fk, ks_lane + slot_off(t + 1));
+    __builtin_amdgcn_sched_barrier(0);
+    weights(1);
+    __builtin_amdgcn_sched_barrier(0);
+    wait4(fk);
+    mma_s(0);
+    if (last) mask_tail(t + 1);
+  };
+  // A(t): PV(t-1) of block 1; read V(t); weights of block 0 (stage t); scores(t) of block 1
+  auto phase_a = [&](int t, bool last) {
+    __builtin_amdgcn_sched_barrier(0);
+    mma_pv(1);                                            // V(t-1): waited for in B(t-1)
+    __builtin_amdgcn_sched_barrier(0);
+    lds_read4_async(fv, vs_lane + slot_off(t));
+    __builtin_amdgcn_sched_barrier(0);
+    weights(0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_s(1);                                             // K(t): waited for in B(t-1)
+    if (last) mask_tail(t);
+  };
+
+  // stages 0, 1 complete and stage 2 in flight before the loop; iteration t fetches stage t+3
+  // into the slot of stage t-1, which nobody reads any more
+  fetch_k(0, 0);
+  fetch_v(0, 0);
+  fetch_k(min(1, nkv - 1), 1);
+  fetch_v(min(1, nkv - 1), 1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  fetch_k(min(2, nkv - 1), 2);
+  fetch_v(min(2, nkv - 1), 2);
+  // A(0) without a PV
+  load4(&ks[0][lane], fk);
+  mma_s(0);
+  if (nkv == 1) mask_tail(0);
+  weights(0);
+  mma_s(1);
+  if (nkv == 1) mask_tail(0);
+  load4(&vs[0][lane], fv);
+  // steady state: B(t), A(t+1) for t <= nkv-3: the stages they touch (t+1) are complete ones
+  for (int t = 0; t < nkv - 2; ++t) {
+    // this wave's parts of stage t+1 have landed (the two newest loads, of stage t+2, may be in
+    // flight); after the barrier all of stage t+1 is readable
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    const int fs = min(t + 3, nkv - 1);
+    fetch_k(fs, t + 3);
+    fetch_v(fs, t + 3);
+    phase_b(t, false);
+    phase_a(t + 1, false);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // nothing may land after the workgroup ends
+  __syncthreads();
+  if (nkv >= 2) {                                         // enters the last stage, which may be ragged
+    phase_b(nkv - 2, true);
+    phase_a(nkv - 1, true);
+  }
+  // B(nkv-1) without scores of a next stage, and the last PV of block 1
+  __builtin_amdgcn_sched_barrier(0);
+  wait4(fv);
+  mma_pv(0);
+  weights(1);
+  mma_pv(1);
+
+  bool low = false;
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) {
+    const float l = lacc[sub][0];   // every row of the accumulator holds the lane's query's sum
+    const float inv = out_scale / l;
+    const int64_t row = q0 + sub * 32 + ql;
+    if (row < n) {
+      low |= !(l >= 1.0f);
+      uint16_t *op = o + (size_t)row * C + head * 64 + 4 * h;
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const u32x2 w = {pack_bf16(oacc[sub][dt][4 * g] * inv, oacc[sub][dt][4 * g + 1] * inv),
+                           pack_bf16(oacc[sub][dt][4 * g + 2] * inv, oacc[sub][dt][4 * g + 3] * inv)};
+          *(u32x2 *)(op + 32 * dt + 8 * g) = w;
+        }
+    }
+  }
+  if (redo && __builtin_amdgcn_ballot_w64(low) != 0 && lane == 0) {
+    atomicOr(&redo[(size_t)head * redo_stride + qb], 1u);
+    atomicOr(redo_any, 1u);
+  }
+}
+
 static int n_key_tiles(int64_t n) { return (int)(2 * ((n + kKV - 1) / kKV)); }
+
+// flags of the bounded FP8 kernel: one word per (head, 256-query block), rows padded to two per
+// 512-query block of the second pass
+static size_t fp8_flag_words(int heads, int64_t n) { return (size_t)heads * 2 * ((n + kQB - 1) / kQB); }
 
 size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype, int n_seq) {
   const size_t elem = attn_dtype == LV_ATTN_FP8_E4M3 ? sizeof(u32x2) : sizeof(u32x4);
   const size_t per = (size_t)heads * n_seq * n_key_tiles(n_tokens) * 4 * kFragU4 * elem;
-  return 256 + 2 * align_up(per, 256);   // [amax block][K fragments][V fragments]
+  // [amax block][K fragments][V fragments]; FP8: a second pair of K/V arrays in the layout of
+  // the second-pass kernel, and the flags
+  size_t total = 256 + 2 * align_up(per, 256);
+  if (attn_dtype == LV_ATTN_FP8_E4M3) total += 2 * align_up(per, 256) + align_up(fp8_flag_words(heads, n_tokens) * 4, 256);
+  return total;
 }
 
 // n_seq independent sequences of n tokens each, stored one after the other (n_seq = 1: the
@@ -996,11 +1301,29 @@ int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_
     const unsigned ag = (unsigned)(((nchunks + 255) / 256) < 4096 ? ((nchunks + 255) / 256) : 4096);
     hipLaunchKernelGGL(k_attn_amax_zero, dim3(1), dim3(64), 0, st, amax);
     hipLaunchKernelGGL(k_attn_amax, dim3(ag), dim3(256), 0, st, q, k, v, n, C, qk_norm, amax);
+    // bounded scores (unit-RMS heads, exponent range checked like for bf16): the branch-free
+    // kernel against the fixed reference first, then the running-maximum kernel on the query
+    // blocks the first one flagged (normally none: its workgroups return at once)
+    const bool bounded = qk_norm && kF8Bound * c <= 64.0f;
+    uint32_t *redo = nullptr;
+    if (bounded) {
+      u32x2 *kpb = (u32x2 *)(frag + 2 * per), *vpb = (u32x2 *)(frag + 3 * per);
+      redo = (uint32_t *)(frag + 4 * per);
+      const size_t words = fp8_flag_words(heads, n);
+      hipLaunchKernelGGL(k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, redo, words);
+      hipLaunchKernelGGL(k_attn_pack_fp8b, dim3((unsigned)n_kt, (unsigned)heads), dim3(256), 0, st, k, v, n,
+                         heads, n_kt, amax, kpb, vpb);
+      if (after_pack && hipEventRecord(after_pack, st) != hipSuccess) return LV_ERR_HIP;
+      const int nqb2 = (int)((n + kBQB - 1) / kBQB);
+      hipLaunchKernelGGL(k_attn_fp8_bounded, dim3((unsigned)(nqb2 * heads)), dim3(256), 0, st, q,
+                         (const u32x4 *)kpb, (const u32x4 *)vpb, o, n, heads, n_kt / 2, nqb2, c, amax, redo,
+                         2 * nqb, amax + 3);
+    }
     hipLaunchKernelGGL(k_attn_pack_fp8, dim3((unsigned)n_kt, (unsigned)heads), dim3(256), 0, st, k,
-                       v, n, heads, n_kt, qk_norm, amax, kp, vp);
-    if (after_pack && hipEventRecord(after_pack, st) != hipSuccess) return LV_ERR_HIP;
+                       v, n, heads, n_kt, qk_norm, amax, bounded ? amax + 3 : (const uint32_t *)nullptr, kp, vp);
+    if (!bounded && after_pack && hipEventRecord(after_pack, st) != hipSuccess) return LV_ERR_HIP;
     hipLaunchKernelGGL(k_attn_fp8, dim3((unsigned)(nqb * heads)), dim3(512), 0, st, q, kp, vp, o, n,
-                       heads, n_kt, nqb, c, qk_norm, amax);
+                       heads, n_kt, nqb, c, qk_norm, amax, redo);
     LV_HIP_CHECK_LAUNCH();
     return LV_OK;
   }

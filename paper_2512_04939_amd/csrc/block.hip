@@ -207,10 +207,6 @@ __global__ __launch_bounds__(256) void k_quant_pack_fp8(const uint16_t *__restri
 // its MFMAs have been issued.  `alpha` (FP8: the product of the two scales) multiplies the
 // accumulators before the bias.
 // ---------------------------------------------------------------------------------------
-typedef __attribute__((ext_vector_type(8))) int i32x8;
-__device__ __forceinline__ i32x8 cat8(const u32x4 a, const u32x4 b) {
-  return i32x8{(int)a.x, (int)a.y, (int)a.z, (int)a.w, (int)b.x, (int)b.y, (int)b.z, (int)b.w};
-}
 __device__ __forceinline__ void lds_read1_async(u32x4 &dst, uint32_t addr) {
   asm volatile("ds_read_b128 %0, %1" : "=&v"(dst) : "v"(addr) : "memory");
 }

@@ -13,6 +13,7 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 constexpr int kWave = 64;
 constexpr int kXcd = 8;      // MI355X: 8 XCDs, workgroups are dealt to them round-robin
@@ -77,6 +78,11 @@ __device__ __forceinline__ void lds_read2_async(u32x4 (&dst)[2], uint32_t addr) 
                : "=&v"(dst[0]), "=&v"(dst[1])
                : "v"(addr)
                : "memory");
+}
+
+// two 16-byte pieces side by side: an 8-register MFMA operand
+__device__ __forceinline__ i32x8 cat8(const u32x4 a, const u32x4 b) {
+  return i32x8{(int)a.x, (int)a.y, (int)a.z, (int)a.w, (int)b.x, (int)b.y, (int)b.z, (int)b.w};
 }
 
 // FP8 E4M3 (OCP "fn": bias 7, largest value 448, no infinities), round to nearest even

@@ -421,16 +421,57 @@ def test_global_attn_fp8_random(B, n, heads, qk_norm):
     exact = O.attention(qs, ks, vs)
     assert max_rel_err(got, emu) <= 5e-2
     assert max_rel_err(got, exact) <= 1e-1 and max_rel_err(emu, exact) <= 1e-1
-    # decode the first K fragment tile from the workspace: [head 0][tile 0][s][lane] 8 bytes,
-    # lane (h*32+key) holds d = 16s + 8h .. +8
+    # decode the first 32-key tile of K from the workspace
     base = (ws.data_ptr() + 255) // 256 * 256 - ws.data_ptr() + 256
-    raw = ws[base:base + 4 * 64 * 8].cpu().numpy().reshape(4, 2, 32, 8)
-    codes = torch.from_numpy(raw.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
     k8, _ = O.quantize_e4m3(ks)
     keys = min(32, n)
-    for s_ in range(4):
-        for hh in range(2):
-            assert np.array_equal(codes[s_, hh, :keys], k8[:keys, 0, 16 * s_ + 8 * hh:16 * s_ + 8 * hh + 8])
+    if qk_norm:
+        # bounded-score kernel: its arrays follow the second-pass kernel's two; [head 0][stage 0]
+        # [half 0][piece j][lane] 16 bytes, lane (h*32+key) holds d = 32j + 8h .. +8 and 32j + 16 + 8h .. +8
+        n_kt = 2 * ((n + 63) // 64)
+        per = (heads * n_kt * 4 * 64 * 8 + 255) // 256 * 256
+        raw = ws[base + 2 * per:base + 2 * per + 2 * 64 * 16].cpu().numpy().reshape(2, 2, 32, 2, 8)
+        codes = torch.from_numpy(raw.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+        for j in range(2):
+            for hh in range(2):
+                for half in range(2):
+                    d0 = 32 * j + 16 * half + 8 * hh
+                    assert np.array_equal(codes[j, hh, :keys, half], k8[:keys, 0, d0:d0 + 8])
+    else:
+        # running-maximum kernel: [head 0][tile 0][s][lane] 8 bytes, lane (h*32+key) holds d = 16s + 8h .. +8
+        raw = ws[base:base + 4 * 64 * 8].cpu().numpy().reshape(4, 2, 32, 8)
+        codes = torch.from_numpy(raw.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+        for s_ in range(4):
+            for hh in range(2):
+                assert np.array_equal(codes[s_, hh, :keys], k8[:keys, 0, 16 * s_ + 8 * hh:16 * s_ + 8 * hh + 8])
+
+
+def test_global_attn_fp8_rows_far_below_the_score_bound(B):
+    """The bounded-score FP8 kernel exponentiates against the largest score unit-RMS heads can
+    reach.  Rows whose scores all sit far below it (queries opposite to every key) cannot be
+    served from E4M3 weights relative to that reference: they must be flagged and recomputed
+    by the running-maximum kernel, while the other rows of the same call are not."""
+    import torch
+    n, heads = 1100, 2
+    rng = np.random.default_rng(88)
+    u = rng.standard_normal((1, heads, 64))
+    k = u + 0.15 * rng.standard_normal((n, heads, 64))
+    q = np.where((np.arange(n) < 400)[:, None, None], -u, u) + 0.15 * rng.standard_normal((n, heads, 64))
+    v = rng.standard_normal((n, heads, 64))
+    bits = [synth.f32_to_bf16_bits(a.reshape(n, heads * 64).astype(np.float32)) for a in (q, k, v)]
+    got, qs, ks, vs, ws = _fp8_case(B, *bits, n, heads, 1)
+    exact = O.attention(qs, ks, vs)
+    assert max_rel_err(got[:400], exact[:400]) <= 1e-1      # near-uniform attention, see the test above
+    assert max_rel_err(got[400:], exact[400:]) <= 1e-1
+    assert max_rel_err(got, O.attention_fp8(qs, ks, vs)) <= 5e-2
+    # flags: one word per (head, 256-query block), rows of 2 * ceil(n / 512) words; blocks 0, 1
+    # hold the opposite queries (block 1 has both kinds), blocks 2 .. 4 none
+    base = (ws.data_ptr() + 255) // 256 * 256 - ws.data_ptr() + 256
+    n_kt = 2 * ((n + 63) // 64)
+    per = (heads * n_kt * 4 * 64 * 8 + 255) // 256 * 256
+    stride = 2 * ((n + 511) // 512)
+    flags = ws[base + 4 * per:base + 4 * per + heads * stride * 4].cpu().numpy().view(np.uint32).reshape(heads, stride)
+    assert np.array_equal(flags[:, :5] != 0, np.array([[True, True, False, False, False]] * heads))
 
 
 @pytest.mark.parametrize("qk_norm", [0, 1])
