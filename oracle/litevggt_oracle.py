@@ -52,7 +52,8 @@ class Params:
     frame_attn: bool = False    # layer loop: a frame attention after every global layer (frame_layer)
     block: Optional[dict] = None  # layer loop: weights of global_block, or None (projection-free attention)
     qk_norm: bool = False       # layer loop: RMS-normalise q and k per head (see global_layer)
-    attn_fp8: bool = False      # layer loop: FP8 E4M3 attention emulation (see attention_fp8)
+    attn_fp8: bool = False      # layer loop: FP8 E4M3 attention emulation (attention_fp8; with qk_norm
+                                # attention_fp8_bounded)
     linear_fp8: bool = False    # block: FP8 E4M3 linear layers (see linear_fp8)
     fp8_history: Optional[list] = None  # block: four Fp8History (inputs of qkv, out-proj, fc1, fc2)
                                         # = delayed scaling; None = scale from the tensor itself
@@ -446,6 +447,45 @@ def attention_fp8(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: Optional[f
     return out
 
 
+FP8_SCORE_BOUND = 73.0   # |q.k| for unit-RMS 64-vectors rounded to bf16, then to E4M3: 64 (1+2^-8)^2 (1+2^-4)^2 < 73
+FP8_WEIGHT_TOP = 8.75    # a weight at the bound is stored as 2^8.75 (E4M3 ends at 448 = 2^8.8)
+
+
+def attention_fp8_bounded(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: Optional[float] = None,
+                          block: int = 1024) -> np.ndarray:
+    """Emulation of the FP8 attention variant for RMS-normalised q and k, where the quantisation
+    points can be fixed without looking at the scores (a design of this build; the paper applies
+    FP8 to linear modules only, see attention_fp8): the weights are exponentiated against the
+    largest score such q and k can reach, w = E4M3(2^(s c - (73 c - 8.75))) with c = scale
+    log2(e); the normaliser is the sum of those E4M3 weights, so that the weights that multiply
+    V sum to one exactly; q is quantised with a scale of at most 448 / amax(q) chosen such that
+    c / (scale_q scale_k) is a power of two (same relative precision, up to one binade less
+    range).  Rows whose weights sum to less than 1 (all scores more than 8.75 binades below the
+    bound) are not served by this scheme: they follow attention_fp8."""
+    d = q.shape[-1]
+    c = np.float32((1.0 / np.sqrt(d) if scale is None else float(scale)) * np.log2(np.e))
+    inv_k = fp8_inv_scale(np.abs(np.asarray(k, dtype=np.float32)).max())
+    inv_q0 = fp8_inv_scale(np.abs(np.asarray(q, dtype=np.float32)).max())
+    e = np.ceil(np.log2(c / (inv_q0 * inv_k)))
+    inv_q = np.float32(c / (inv_k * np.exp2(e)))
+    q8, k8 = quantize_e4m3_at(q, inv_q), quantize_e4m3_at(k, inv_k)
+    v8, sv = quantize_e4m3(v)
+    ref = FP8_SCORE_BOUND * float(c) - FP8_WEIGHT_TOP
+    out = np.empty(q8.shape, dtype=np.float64)
+    low = np.zeros(q8.shape[:2], dtype=bool)
+    for hh in range(q8.shape[1]):
+        for b0 in range(0, q8.shape[0], block):
+            s = (q8[b0:b0 + block, hh, :] @ k8[:, hh, :].T) * np.exp2(e)
+            w8 = round_e4m3(np.exp2(s - ref))
+            tot = w8.sum(axis=1, keepdims=True)
+            low[b0:b0 + block, hh] = tot[:, 0] < 1.0
+            out[b0:b0 + block, hh, :] = (w8 @ v8[:, hh, :]) * sv / np.where(tot > 0, tot, 1.0)
+    if low.any():
+        alt = attention_fp8(q, k, v, scale, block=block)
+        out[low] = alt[low]
+    return out
+
+
 # ---------------------------------------------------------------------------
 # cached-index layer driver  (Sec. 3.4: indices recomputed every refresh_interval layers)
 # ---------------------------------------------------------------------------
@@ -562,7 +602,7 @@ def global_block(z: np.ndarray, w: dict, p: Params, store=lambda a: a) -> np.nda
     q, k, v = (qkv[:, i * C:(i + 1) * C].reshape(-1, p.heads, p.head_dim) for i in range(3))
     if p.qk_norm:
         q, k = store(qk_normalize(q)), store(qk_normalize(k))
-    attn = attention_fp8 if p.attn_fp8 else attention
+    attn = (attention_fp8_bounded if p.qk_norm else attention_fp8) if p.attn_fp8 else attention
     a = store(attn(q, k, v).reshape(z.shape))
     u1 = store(lin[1](a, w["w_o"], w["b_o"]))
     h2 = store(layer_norm(z + u1, w["ln2_g"], w["ln2_b"]))
@@ -582,7 +622,7 @@ def global_layer(x: np.ndarray, idx: Dict[str, np.ndarray], p: Params,
         return store(unmerge(global_block(z, p.block, p, store), idx["slot_of"], residual=x))
     zz = z.reshape(z.shape[0], p.heads, p.head_dim)
     qk = store(qk_normalize(zz)) if p.qk_norm else zz
-    attn = attention_fp8 if p.attn_fp8 else attention
+    attn = (attention_fp8_bounded if p.qk_norm else attention_fp8) if p.attn_fp8 else attention
     y = store(attn(qk, qk, zz).reshape(z.shape))
     return store(unmerge(y, idx["slot_of"], residual=x))
 

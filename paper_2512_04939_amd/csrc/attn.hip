@@ -1057,8 +1057,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     qb = blockIdx.x % nqb;
   }
   const int64_t q0 = (int64_t)qb * kBQB + wave * kQW;
-  const float inv_sq = fp8_scale_inv(amax[0]);
-  const float cs = c_in * (1.0f / inv_sq) * (1.0f / fp8_scale_inv(amax[1]));   // code product -> log2 units
+  // The score MFMA delivers log2-domain scores minus the reference directly: its accumulator
+  // starts at -ref, and the factor between a product of codes and a log2-domain score, c / (scale
+  // of q * scale of k), is made a power of two 2^e by quantising q with a scale up to 2x smaller
+  // than 448 / amax (same relative precision, floating point); 2^e is the MFMA's block scale.
+  const float inv_sk = fp8_scale_inv(amax[1]);
+  const float e_f = fminf(fmaxf(ceilf(log2f(c_in / (fp8_scale_inv(amax[0]) * inv_sk))), -100.f), 100.f);
+  const float inv_sq = c_in / (inv_sk * exp2f(e_f));
+  const int scale_k = 127 + (int)e_f;       // E8M0: 2^(scale_k - 127), applied to the K operand
   const float ref = kF8Bound * c_in - kF8Top;
   const float out_scale = 1.0f / fp8_scale_inv(amax[2]);
 
@@ -1097,7 +1103,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int r = 0; r < 16; ++r) lacc[sub][r] = 0.f;
   const int kOne = 0x38383838;
   const i32x8 ones8 = {kOne, kOne, kOne, kOne, kOne, kOne, kOne, kOne};
-  const f32x16 kZero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const float nr = -ref;
+  const f32x16 kStart = {nr, nr, nr, nr, nr, nr, nr, nr, nr, nr, nr, nr, nr, nr, nr, nr};
 
   const u32x4 *kh = kp + (size_t)head * nkv * 4 * 64;
   const u32x4 *vh = vp + (size_t)head * nkv * 4 * 64;
@@ -1123,7 +1130,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int kt2 = 0; kt2 < 2; ++kt2)
       sacc[kt2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cat8(fk[2 * kt2], fk[2 * kt2 + 1]), qf8[sub],
-                                                                  kZero, 0, 0, 0, 0, 0, 0);
+                                                                  kStart, 0, 0, 0, scale_k, 0, 127);
   };
   auto mma_pv = [&](int sub) {
 #pragma unroll
@@ -1151,7 +1158,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int u = 0; u < 2; ++u) {
         float pv[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt2][8 * u + e], cs, -ref));
+        for (int e = 0; e < 8; ++e) pv[e] = __builtin_amdgcn_exp2f(sacc[kt2][8 * u + e]);
         pb[sub][(kt2 * 2 + u) * 2] = (int)cvt4_fp8(pv[0], pv[1], pv[2], pv[3]);
         pb[sub][(kt2 * 2 + u) * 2 + 1] = (int)cvt4_fp8(pv[4], pv[5], pv[6], pv[7]);
       }
@@ -1161,7 +1168,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   };
   // A phase is: the MFMAs that consume what the phase before produced, the fragment read for
   // the next consumer (by hand, waited for a whole VALU part later), the VALU part (the longer
-  // one: 32 fma, 32 exp2, 16 packs per lane against 3 + 2 MFMAs of 64 cycles), then the score
+  // one: 32 exp2, 16 packs per lane against 3 + 2 MFMAs of 64 cycles), then the score
   // MFMAs whose results the next phase's VALU part turns into weights.  Scores of only one
   // query block are alive at a time, and one stage of K and of V.
   const uint32_t ks_lane = lds_addr(&ks[0][lane]), vs_lane = lds_addr(&vs[0][lane]);

@@ -405,10 +405,11 @@ def _fp8_case(B, qs_bits, ks_bits, vs_bits, n, heads, qk_norm):
 @pytest.mark.parametrize("n,heads,qk_norm", [(257, 2, 0), (1000, 4, 1), (2049, 1, 1)])
 def test_global_attn_fp8_random(B, n, heads, qk_norm):
     """FP8 E4M3 variant on i.i.d. Gaussian q, k, v.  The kernel must store exactly the
-    oracle's E4M3 codes for K and agree with the oracle's emulation up to the placement of
-    the weights' quantisation points (the kernel rounds each weight relative to its running
-    softmax reference, the emulation relative to the final row maximum: same noise level,
-    different noise, 5e-2 here).  Against exact
+    oracle's E4M3 codes for K and agree with the oracle's emulation: without qk_norm up to the
+    placement of the weights' quantisation points (the kernel rounds each weight relative to
+    its running softmax reference, the emulation relative to the final row maximum: same noise
+    level, different noise, 5e-2 here); with qk_norm both sides use the same fixed reference
+    and differ only where a score rounds differently in fp32 and float64 (2e-2).  Against exact
     attention this input is the worst case for E4M3 weights: attention is nearly uniform, the
     output is a small mean of many values (cancellation) while the 2^-4 relative rounding of
     every weight does not cancel; kernel and emulation both land at 6-8e-2 here, so the bound
@@ -417,9 +418,10 @@ def test_global_attn_fp8_random(B, n, heads, qk_norm):
     q, k, v = synth.random_qkv(n, heads, 64, seed=300 + n, scale=1.3)
     bits = [synth.f32_to_bf16_bits(a.reshape(n, heads * 64)) for a in (q, k, v)]
     got, qs, ks, vs, ws = _fp8_case(B, *bits, n, heads, qk_norm)
-    emu = O.attention_fp8(qs, ks, vs)
+    emu = O.attention_fp8_bounded(qs, ks, vs) if qk_norm else O.attention_fp8(qs, ks, vs)
     exact = O.attention(qs, ks, vs)
-    assert max_rel_err(got, emu) <= 5e-2
+    print(f"fp8 random n={n}: vs emulation {max_rel_err(got, emu):.2e}, vs exact {max_rel_err(got, exact):.2e}")
+    assert max_rel_err(got, emu) <= (2e-2 if qk_norm else 5e-2)
     assert max_rel_err(got, exact) <= 1e-1 and max_rel_err(emu, exact) <= 1e-1
     # decode the first 32-key tile of K from the workspace
     base = (ws.data_ptr() + 255) // 256 * 256 - ws.data_ptr() + 256
@@ -463,7 +465,9 @@ def test_global_attn_fp8_rows_far_below_the_score_bound(B):
     exact = O.attention(qs, ks, vs)
     assert max_rel_err(got[:400], exact[:400]) <= 1e-1      # near-uniform attention, see the test above
     assert max_rel_err(got[400:], exact[400:]) <= 1e-1
-    assert max_rel_err(got, O.attention_fp8(qs, ks, vs)) <= 5e-2
+    # rows 0 .. 399 are recomputed (with them the rest of their 256-row blocks, rows 400 .. 511)
+    assert max_rel_err(got[:400], O.attention_fp8(qs, ks, vs)[:400]) <= 5e-2
+    assert max_rel_err(got[512:], O.attention_fp8_bounded(qs, ks, vs)[512:]) <= 2e-2
     # flags: one word per (head, 256-query block), rows of 2 * ceil(n / 512) words; blocks 0, 1
     # hold the opposite queries (block 1 has both kinds), blocks 2 .. 4 none
     base = (ws.data_ptr() + 255) // 256 * 256 - ws.data_ptr() + 256
@@ -483,7 +487,8 @@ def test_global_attn_fp8_workload_features(B, qk_norm):
     n = wl.n_tokens
     got, qs, ks, vs, _ = _fp8_case(B, bits, bits, bits, n, 4, qk_norm)
     assert max_rel_err(got, O.attention(qs, ks, vs)) <= FP8_TOL
-    assert max_rel_err(got, O.attention_fp8(qs, ks, vs)) <= 2e-2
+    emu = O.attention_fp8_bounded(qs, ks, vs) if qk_norm else O.attention_fp8(qs, ks, vs)
+    assert max_rel_err(got, emu) <= 2e-2
 
 
 def test_layers_run_fp8_attention(B):

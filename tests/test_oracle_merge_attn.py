@@ -162,6 +162,32 @@ def test_round_bf16_matches_torch():
     assert np.array_equal(synth.bf16_bits_to_f32(bits).astype(np.float64), ref)
 
 
+def test_attention_fp8_bounded_emulation_properties():
+    """Fixed-reference FP8 emulation: weights sum to one exactly (constant V comes back up to its
+    own quantisation, whatever the scores), close to exact attention on peaked rows, and rows
+    whose scores all sit far below the bound fall back to the running-maximum emulation."""
+    rng = np.random.default_rng(61)
+    n, h = 300, 2
+    q = O.round_bf16(O.qk_normalize(rng.standard_normal((n, h, 64))))
+    k = O.round_bf16(O.qk_normalize(q + 0.3 * rng.standard_normal((n, h, 64))))
+    v = rng.standard_normal((n, h, 64))
+    const = np.broadcast_to(rng.standard_normal((1, h, 64)), (n, h, 64))
+    c8, sc = O.quantize_e4m3(const)
+    assert np.allclose(O.attention_fp8_bounded(q, k, const), c8 * sc, rtol=1e-12, atol=1e-12)
+    got, exact = O.attention_fp8_bounded(q, k, v), O.attention(q, k, v)
+    assert 1e-4 < np.abs(got - exact).max() / np.abs(exact).max() < 6e-2
+    # every key near one direction and the queries opposite to it: every score near -64 * scale,
+    # 2^-24 of the reference: nothing is representable and all rows take the other emulation
+    u = rng.standard_normal((1, h, 64))
+    kk = O.round_bf16(O.qk_normalize(u + 0.1 * rng.standard_normal((n, h, 64))))
+    qq = O.round_bf16(O.qk_normalize(-u + 0.1 * rng.standard_normal((n, h, 64))))
+    assert np.array_equal(O.attention_fp8_bounded(qq, kk, v), O.attention_fp8(qq, kk, v))
+    assert not np.array_equal(O.attention_fp8_bounded(q, k, v), O.attention_fp8(q, k, v))
+    # the bound itself: unit-RMS rows rounded to bf16 and then to E4M3 cannot exceed it
+    worst = 64.0 * (1 + 2.0 ** -8) ** 2 * (1 + 2.0 ** -4) ** 2
+    assert worst < O.FP8_SCORE_BOUND and 2.0 ** O.FP8_WEIGHT_TOP < 448.0
+
+
 def test_round_e4m3_matches_torch():
     rng = np.random.default_rng(52)
     a = np.concatenate([rng.standard_normal(5000) * 10 ** rng.uniform(-4, 2.5, 5000),
