@@ -205,8 +205,13 @@ int litevggt_merge(const litevggt_params *p, const void *x, const litevggt_index
  * With qk_norm the scores use the per-head RMS-normalised q and k (see litevggt_params);
  * v is used as given.  Scores are exponentiated as exp2(s*c - max*c) with one fused
  * multiply-add: accurate while |score * softmax_scale| stays below about 2^16.
- * attn_dtype LV_ATTN_FP8_E4M3 quantises q,k,v per tensor (scale = amax/448) and the
- * softmax weights to e4m3 for the MFMAs; accumulation and softmax stay fp32.
+ * attn_dtype LV_ATTN_FP8_E4M3 quantises q,k,v per tensor (scale = amax/448, amax taken in
+ * this call) and the softmax weights to e4m3 for the MFMAs; accumulation and softmax stay
+ * fp32.  Without qk_norm the weights are rounded relative to a running row maximum and
+ * normalised by their fp32 sum.  With qk_norm they are rounded relative to the largest score
+ * unit-RMS heads can reach and normalised by the sum of the e4m3 weights themselves (they
+ * sum to one exactly), and q's scale may be up to 2x smaller than 448/amax; rows whose
+ * scores all lie more than 8.75 binades below that bound are recomputed the first way.
  */
 int litevggt_global_attn(const litevggt_params *p, int64_t n_tokens, const void *q,
                          const void *k, const void *v, void *o,
