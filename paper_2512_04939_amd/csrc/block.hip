@@ -164,7 +164,7 @@ __global__ __launch_bounds__(64) void k_fp8_scales(uint32_t *__restrict__ sc, fl
 // the tiled kernel fetches and reads both types the same way.  Rows n..n_pad-1 are zero.
 // A wave writes whole units (1 KB stores) and takes 4 consecutive units of its 32 rows (256
 // bytes of each bf16 row).  Grid: (row tiles, ceil(units / 16)).
-__global__ __launch_bounds__(256) void k_quant_pack_fp8(const uint16_t *__restrict__ x, int n, int n_pad,
+__global__ __launch_bounds__(256) void k_quant_pack_fp8(const uint16_t *__restrict__ x, int n,
                                                         int K, const uint32_t *__restrict__ inv,
                                                         u32x4 *__restrict__ packed) {
   const int KS = K >> 5;
@@ -219,7 +219,7 @@ __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + e
 
 template <bool FP8>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_bt(
-    const u32x4 *__restrict__ ap, const u32x4 *__restrict__ wp, int64_t M, int Nout, int KS, int nt_n,
+    const u32x4 *__restrict__ ap, const u32x4 *__restrict__ wp, int64_t M, int KS, int nt_n,
     const float *__restrict__ bias, int gelu, uint16_t *__restrict__ out, int split,
     const float *__restrict__ alpha_p) {
   extern __shared__ u32x4 ring[];
@@ -434,7 +434,7 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
     };
     auto quant = [&](const uint16_t *t, int64_t n, int64_t n_pad, const uint32_t *inv, u32x4 *dst) {
       hipLaunchKernelGGL(k_quant_pack_fp8, dim3((unsigned)(n_pad / 32), (unsigned)((K / 32 + 15) / 16)), dim3(256), 0, st, t, (int)n,
-                         (int)n_pad, K, inv, dst);
+                         K, inv, dst);
     };
     hipLaunchKernelGGL(k_fp8_zero, dim3(1), dim3(64), 0, st, w.fp8sc);
     amax(A, M * (K / 8), w.fp8sc);
@@ -443,12 +443,12 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
     quant(A, M, w.Mp, w.fp8sc + 2, w.apack);
     quant(W, Nout, Nout, w.fp8sc + 3, w.wpack);
     hipLaunchKernelGGL(k_gemm_bt<true>, dim3((unsigned)(nt_m * nt_n)), dim3(512), lds, st, w.apack, w.wpack,
-                       M, Nout, K / 32, nt_n, bias, gelu, out, split, (const float *)(w.fp8sc + 4));
+                       M, K / 32, nt_n, bias, gelu, out, split, (const float *)(w.fp8sc + 4));
   } else {
     if ((rc = launch_pack_rows(A, M, w.Mp, K, w.apack, st))) return rc;
     if ((rc = launch_pack_rows(W, Nout, Nout, K, w.wpack, st))) return rc;
     hipLaunchKernelGGL(k_gemm_bt<false>, dim3((unsigned)(nt_m * nt_n)), dim3(512), lds, st, w.apack, w.wpack,
-                       M, Nout, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr);
+                       M, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr);
   }
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;
