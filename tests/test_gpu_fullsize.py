@@ -130,6 +130,22 @@ def test_full_size_steps_against_sampled_oracle(name, over):
         want_y = O.attention(qk, qk, zh, rows=qrows).reshape(len(qrows), 64)
         assert max_rel_err(_f64(yb[qrows][:, cols]), want_y) <= BF16_TOL
 
+    # ---- FP8 attention at the largest size: the same sampled rows against exact attention
+    if name == "f1000":
+        p8 = hip_params(wl, attn_dtype=B.ATTN_FP8_E4M3)
+        y8 = torch.empty_like(z)
+        ws8 = B.alloc_ws(B.litevggt_attn_ws_bytes(p8, M))
+        B.litevggt_global_attn(p8, M, z, z, z, y8, ws8)
+        torch.cuda.synchronize()
+        y8b = _host_bits(y8)
+        for head in (3, 12):
+            cols = slice(head * 64, (head + 1) * 64)
+            zh = _f64(zb[:, cols]).reshape(M, 1, 64)
+            qk = O.round_bf16(O.qk_normalize(zh))
+            want_y = O.attention(qk, qk, zh, rows=qrows).reshape(len(qrows), 64)
+            assert max_rel_err(_f64(y8b[qrows][:, cols]), want_y) <= 6e-2
+        del y8, ws8
+
     # ---- unmerge with the fused residual: bit-exact on sampled tokens
     toks = np.sort(rng.choice(N, size=4096, replace=False))
     s = synth.bf16_bits_to_f32(bits[toks]) + synth.bf16_bits_to_f32(yb[slot_of[toks]])
