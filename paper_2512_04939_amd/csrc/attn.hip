@@ -405,6 +405,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   if (res) res += (size_t)seq * n * C;
   const int64_t q0 = (int64_t)qb * kBQB + wave * kQW;
 
+  const int nkv = n_kt >> 1, nkt = n_kt;
+  const u32x4 *kh = kp + (size_t)sh * n_kt * 4 * kFragU4;
+  const u32x4 *vh = vp + (size_t)sh * n_kt * 4 * kFragU4;
+  // Stage `stage` of this head's packed K and V (64 keys, 8 KB each) goes from global memory
+  // straight into its ring slot, 1 KB per wave and instruction (global_load_lds_dwordx4: lane l
+  // of a wave lands at the wave's LDS base + 16 l).  No registers are staged, so a stage can be
+  // fetched three iterations before its first use.  Completion is per wave (vmcnt) and is
+  // published to the workgroup by the barrier of the steady-state loop.
+  auto fetch = [&](int stage) {
+    const int slot = stage & (kBStages - 1);
+    const size_t off = (size_t)stage * 8 * kFragU4 + tid;
+    __builtin_amdgcn_global_load_lds(kh + off, &ks[slot][wave * 64], 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(kh + off + 256, &ks[slot][256 + wave * 64], 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(vh + off, &vs[slot][wave * 64], 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(vh + off + 256, &vs[slot][256 + wave * 64], 16, 0, 0);
+  };
+  // the first two stages are requested before q is loaded and normalised: one memory round
+  // trip for both (short sequences, e.g. frame attention, have few stages to hide it behind)
+  fetch(0);
+  fetch(min(1, nkv - 1));
+
   // Q^T fragments, RMS-normalised per head with the softmax scale (log2 units) folded in
   bf16x8 qf[2][4];
 #pragma unroll
@@ -430,23 +451,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int r = 0; r < 16; ++r) oacc[sub][dt][r] = 0.f;
   float lrow[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
   const f32x16 kZero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-
-  const int nkv = n_kt >> 1, nkt = n_kt;
-  const u32x4 *kh = kp + (size_t)sh * n_kt * 4 * kFragU4;
-  const u32x4 *vh = vp + (size_t)sh * n_kt * 4 * kFragU4;
-  // Stage `stage` of this head's packed K and V (64 keys, 8 KB each) goes from global memory
-  // straight into its ring slot, 1 KB per wave and instruction (global_load_lds_dwordx4: lane l
-  // of a wave lands at the wave's LDS base + 16 l).  No registers are staged, so a stage can be
-  // fetched three iterations before its first use.  Completion is per wave (vmcnt) and is
-  // published to the workgroup by the barrier of the steady-state loop.
-  auto fetch = [&](int stage) {
-    const int slot = stage & (kBStages - 1);
-    const size_t off = (size_t)stage * 8 * kFragU4 + tid;
-    __builtin_amdgcn_global_load_lds(kh + off, &ks[slot][wave * 64], 16, 0, 0);
-    __builtin_amdgcn_global_load_lds(kh + off + 256, &ks[slot][256 + wave * 64], 16, 0, 0);
-    __builtin_amdgcn_global_load_lds(vh + off, &vs[slot][wave * 64], 16, 0, 0);
-    __builtin_amdgcn_global_load_lds(vh + off + 256, &vs[slot][256 + wave * 64], 16, 0, 0);
-  };
 
   f32x16 sacc[2];      // [query block]: scores of its current 32-key tile
   u32x4 pb[2][2];      // [query block][u]: bf16 weights of its current 32-key tile
@@ -566,8 +570,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     recipe();
   };
 
-  fetch(0);
-  fetch(min(1, nkv - 1));
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   fetch(min(2, nkv - 1));                  // in flight during the prologue and the first iteration
