@@ -282,6 +282,45 @@ def test_merge_one_giant_group(B):
     assert torch.equal(z, z2)                              # reproducible
 
 
+@pytest.mark.parametrize("seed,dim", [(1, 64), (2, 256), (3, 1024)])
+def test_merge_heavy_tailed_groups(B, seed, dim):
+    """Group sizes from a heavy-tailed distribution with the large groups (65 .. 900 members:
+    the cooperative path) clustered at the first slots, scattered, and at the very last slots of
+    an M that is not a multiple of 64; the kernel reads nothing of the index but the CSR."""
+    import torch
+    wl = synth.Workload("h", frames=30, grid_h=21, grid_w=19, dim=dim, heads=dim // 64, merge_ratio=0.8,
+                        canvas=32, seed=30 + seed)
+    ph = hip_params(wl)
+    pl = B.litevggt_plan(ph)
+    N, M = pl.N, pl.M
+    assert M % 64 != 0
+    rng = np.random.default_rng(seed)
+    sizes = np.ones(M, dtype=np.int64)
+    big = np.concatenate([np.arange(12), M - 1 - np.arange(5), rng.choice(np.arange(12, M - 5), 6, replace=False)])
+    extra = N - M
+    want_big = rng.integers(64, 900, size=len(big))
+    want_big = (want_big * min(1.0, 0.7 * extra / want_big.sum())).astype(np.int64)
+    sizes[big] += want_big
+    rest = N - sizes.sum()
+    assert rest >= 0
+    np.add.at(sizes, rng.integers(0, M, size=rest), 1)          # the remaining members, at random
+    assert sizes.sum() == N and (sizes > 64).sum() >= 15 and sizes.max() > 256
+    group_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    perm = rng.permutation(N)
+    group_mem = np.concatenate([np.sort(perm[group_off[m]:group_off[m + 1]]) for m in range(M)]).astype(np.int32)
+    x = O.round_bf16(rng.standard_normal((N, dim)) * np.exp(rng.standard_normal((N, 1))))
+    ib = B.alloc_index(pl)
+    ib.group_off.copy_(torch.from_numpy(group_off))
+    ib.group_mem.copy_(torch.from_numpy(group_mem))
+    z = torch.zeros(M, dim, dtype=torch.bfloat16, device="cuda")
+    B.litevggt_merge(ph, f32_to_dev_bf16(x.astype(np.float32)), ib, z)
+    torch.cuda.synchronize()
+    ref = O.merge(x, group_off, group_mem)
+    got = dev_bf16_to_f64(z)
+    assert np.abs(got - ref).max() <= 2.0 ** -8 * np.abs(ref).max()
+    assert max_rel_err(got, ref) <= BF16_TOL
+
+
 def test_merge_unmerge_identity_at_ratio_zero(B):
     import torch
     wl = small_workload(frames=2, grid=6, dim=128, heads=2, r=0.0, seed=2)
