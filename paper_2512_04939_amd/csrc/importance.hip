@@ -64,16 +64,19 @@ int launch_grad_map(const void *images, int img_dtype, const Dims &d, int patch,
 }
 
 // ---------------------------------------------------------------------------------
-// Psi_v.  One workgroup per (frame, grid row); thread t owns channels 4t..4t+3 (+1024k).
-// For every grid column the K x K neighbourhood (clipped) is loaded into registers,
-// mean and mean squared deviation are taken per channel, summed over channels.
-// Workgroups of consecutive grid rows are placed on the same XCD so the two
-// neighbouring rows they share are found in that XCD's L2.
+// Psi_v.  One workgroup (2 waves) per (frame, grid row); thread t owns channels 8t..8t+7 (+1024k).
+// The workgroup slides along the row: for every grid column it loads the K tokens of that
+// column (rows i-R..i+R, clipped) once and keeps their per-channel sum and sum of squares
+// for the last K columns in registers; the window of an output column is the sum of those K
+// column partials, its variance E[x^2] - E[x]^2 in fp32 (inputs are bf16 and a window has at
+// most 25 cells: the cancellation costs ~1e-7 of E[x^2], far below the map's tolerance).
+// Workgroups of consecutive grid rows are placed on the same XCD so the two neighbouring rows
+// they share are found in that XCD's L2.
 // ---------------------------------------------------------------------------------
 template <int K>
-__global__ __launch_bounds__(256) void k_var_map(const uint16_t *__restrict__ x, int F, int H,
+__global__ __launch_bounds__(128) void k_var_map(const uint16_t *__restrict__ x, int F, int H,
                                                  int W, int S, int C, float *__restrict__ psi_v) {
-  extern __shared__ float part[];            // [W][4 waves]
+  extern __shared__ float part[];            // [W][2 waves]
   const uint32_t nblk = (uint32_t)F * H;
   const uint32_t lb = xcd_contiguous(blockIdx.x, nblk);
   if (lb >= nblk) return;
@@ -83,70 +86,89 @@ __global__ __launch_bounds__(256) void k_var_map(const uint16_t *__restrict__ x,
   const uint16_t *frame = x + ((size_t)f * T + S) * C;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int i0 = max(i - R, 0), i1 = min(i + R, H - 1);
-  for (int j = 0; j < W; ++j) {
-    const int j0 = max(j - R, 0), j1 = min(j + R, W - 1);
-    const float inv_cnt = 1.0f / (float)((i1 - i0 + 1) * (j1 - j0 + 1));
-    float tot = 0.f;
-    for (int c0 = threadIdx.x * 4; c0 < C; c0 += 1024) {
-      float v[K * K][4];
-      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  const int nrow = i1 - i0 + 1;
+  for (int c0 = threadIdx.x * 8, pass = 0; c0 < (C + 1023) / 1024 * 1024; c0 += 1024, ++pass) {
+    const bool on = c0 < C;                  // every thread walks every pass: part[] is per wave
+    float s1[K][8], s2[K][8];                // column partials of the last K columns; slot = column % K
 #pragma unroll
-      for (int a = 0; a < K; ++a) {
+    for (int u = 0; u < K; ++u)
 #pragma unroll
-        for (int b = 0; b < K; ++b) {
-          int ii = i - R + a, jj = j - R + b;
-          bool ok = ii >= i0 && ii <= i1 && jj >= j0 && jj <= j1;
-          u32x2 w = {0u, 0u};
-          if (ok) w = *(const u32x2 *)(frame + ((size_t)ii * W + jj) * C + c0);
-          // cells outside the grid hold 0 and are excluded from the deviation pass below
-          v[a * K + b][0] = bf16_lo(w.x);
-          v[a * K + b][1] = bf16_hi(w.x);
-          v[a * K + b][2] = bf16_lo(w.y);
-          v[a * K + b][3] = bf16_hi(w.y);
-          s0 += v[a * K + b][0];
-          s1 += v[a * K + b][1];
-          s2 += v[a * K + b][2];
-          s3 += v[a * K + b][3];
+      for (int e = 0; e < 8; ++e) s1[u][e] = s2[u][e] = 0.f;
+    // the K tokens of a column are requested one column ahead of their use
+    auto load_col = [&](int jj, u32x4(&w)[K]) {
+#pragma unroll
+      for (int a = 0; a < K; ++a) {          // rows outside the grid read as zeros: they add nothing
+        const int ii = i - R + a;
+        w[a] = u32x4{0u, 0u, 0u, 0u};
+        if (on && jj < W && ii >= i0 && ii <= i1) w[a] = *(const u32x4 *)(frame + ((size_t)ii * W + jj) * C + c0);
+      }
+    };
+    u32x4 wcur[K], wnext[K];
+    load_col(0, wcur);
+    for (int jb = 0; jb < W + R; jb += K) {
+#pragma unroll
+      for (int u = 0; u < K; ++u) {
+        const int jj = jb + u;               // column entering the window; output column is jj - R
+        load_col(jj + 1, wnext);
+        float a1[8], a2[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a1[e] = a2[e] = 0.f;
+#pragma unroll
+        for (int a = 0; a < K; ++a) {        // (zeros beyond the row end)
+          const float v[8] = {bf16_lo(wcur[a].x), bf16_hi(wcur[a].x), bf16_lo(wcur[a].y), bf16_hi(wcur[a].y),
+                              bf16_lo(wcur[a].z), bf16_hi(wcur[a].z), bf16_lo(wcur[a].w), bf16_hi(wcur[a].w)};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            a1[e] += v[e];
+            a2[e] = __builtin_fmaf(v[e], v[e], a2[e]);
+          }
+        }
+#pragma unroll
+        for (int a = 0; a < K; ++a) wcur[a] = wnext[a];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {        // columns beyond the row end enter as zeros
+          s1[u][e] = a1[e];
+          s2[u][e] = a2[e];
+        }
+        const int j = jj - R;
+        if (j >= 0 && j < W) {
+          const int j0 = max(j - R, 0), j1 = min(j + R, W - 1);
+          const float inv_cnt = 1.0f / (float)(nrow * (j1 - j0 + 1));
+          float tot = 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            float t1 = 0.f, t2 = 0.f;
+#pragma unroll
+            for (int q = 0; q < K; ++q) {
+              t1 += s1[q][e];
+              t2 += s2[q][e];
+            }
+            const float m = t1 * inv_cnt;
+            tot += __builtin_fmaf(-m, m, t2 * inv_cnt);
+          }
+          tot = wave_sum(tot);
+          if (lane == 0) part[j * 2 + wave] = (pass ? part[j * 2 + wave] : 0.f) + tot;
         }
       }
-      const float m0 = s0 * inv_cnt, m1 = s1 * inv_cnt, m2 = s2 * inv_cnt, m3 = s3 * inv_cnt;
-      float q = 0.f;
-#pragma unroll
-      for (int a = 0; a < K; ++a) {
-#pragma unroll
-        for (int b = 0; b < K; ++b) {
-          int ii = i - R + a, jj = j - R + b;
-          bool ok = ii >= i0 && ii <= i1 && jj >= j0 && jj <= j1;
-          float d0 = v[a * K + b][0] - m0, d1 = v[a * K + b][1] - m1;
-          float d2 = v[a * K + b][2] - m2, d3 = v[a * K + b][3] - m3;
-          float e = d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
-          q += ok ? e : 0.f;
-        }
-      }
-      tot += q * inv_cnt;
     }
-    tot = wave_sum(tot);
-    if (lane == 0) part[j * 4 + wave] = tot;
   }
   __syncthreads();
-  for (int j = threadIdx.x; j < W; j += blockDim.x) {
-    float t = ((part[j * 4] + part[j * 4 + 1]) + part[j * 4 + 2]) + part[j * 4 + 3];
-    psi_v[((size_t)f * H + i) * W + j] = t / (float)C;
-  }
+  for (int j = threadIdx.x; j < W; j += blockDim.x)
+    psi_v[((size_t)f * H + i) * W + j] = (part[j * 2] + part[j * 2 + 1]) / (float)C;
 }
 
 int launch_var_map(const uint16_t *x, const Dims &d, int pool, float *psi_v, hipStream_t st) {
   dim3 grid((unsigned)(align_up((size_t)d.F * d.H, kXcd)));
-  size_t lds = (size_t)d.W * 4 * sizeof(float);
+  size_t lds = (size_t)d.W * 2 * sizeof(float);
   switch (pool) {
     case 1:
-      hipLaunchKernelGGL(k_var_map<1>, grid, dim3(256), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
+      hipLaunchKernelGGL(k_var_map<1>, grid, dim3(128), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
       break;
     case 3:
-      hipLaunchKernelGGL(k_var_map<3>, grid, dim3(256), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
+      hipLaunchKernelGGL(k_var_map<3>, grid, dim3(128), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
       break;
     case 5:
-      hipLaunchKernelGGL(k_var_map<5>, grid, dim3(256), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
+      hipLaunchKernelGGL(k_var_map<5>, grid, dim3(128), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
       break;
     default:
       return LV_ERR_PARAM;
