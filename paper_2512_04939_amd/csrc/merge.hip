@@ -88,13 +88,14 @@ __global__ __launch_bounds__(256) void k_merge(const uint16_t *__restrict__ x,
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nch = C >> 3;
   if ((int)blockIdx.x < nb0) {           // cooperative pass over the large groups of kScan slots
-    const int ms = blockIdx.x + lane * nb0;   // strided: neighbouring slots (the all-dst first frame) hold the largest groups
+    // strided: neighbouring slots (the all-dst first frame) hold the largest groups
+    const int64_t ms = (int64_t)blockIdx.x + (int64_t)lane * nb0;
     const int bl = ms < M ? group_off[ms] : 0, el = ms < M ? group_off[ms + 1] : 0;
     uint64_t big = __builtin_amdgcn_ballot_w64(el - bl > kCoopSize);   // same in every wave
     while (big) {
       const int s = __builtin_ctzll(big);
       big &= big - 1;
-      const int m = blockIdx.x + s * nb0;
+      const int m = (int)(blockIdx.x + (int64_t)s * nb0);   // < M: its lane passed the range check
       const int b = __builtin_amdgcn_readlane(bl, s), e = __builtin_amdgcn_readlane(el, s), n = e - b;
       const int per = (n + 3) >> 2;
       const int lo = min(b + wave * per, e), hi = min(lo + per, e);
