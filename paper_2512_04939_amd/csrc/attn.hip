@@ -58,7 +58,8 @@ __global__ __launch_bounds__(256) void k_attn_pack(const uint16_t *__restrict__ 
                                                    const uint16_t *__restrict__ v, int64_t n,
                                                    int heads, int n_kt, int qk_norm,
                                                    u32x4 *__restrict__ kp,
-                                                   u32x4 *__restrict__ vp) {
+                                                   u32x4 *__restrict__ vp,
+                                                   uint32_t *__restrict__ kmax) {
   __shared__ __attribute__((aligned(16))) uint16_t vt[kKT][72];
   const int kt = blockIdx.x, t = threadIdx.x;
   const int seq = blockIdx.y / heads, head = blockIdx.y - seq * heads;
@@ -73,6 +74,12 @@ __global__ __launch_bounds__(256) void k_attn_pack(const uint16_t *__restrict__ 
     wv = *(const u32x4 *)(v + (size_t)row * C + head * 64 + chunk * 8);
   }
   if (qk_norm) wk = rms_scale8(wk, 3);   // the 8 lanes that share a key hold its 64 values
+  if (kmax) {                            // largest |k| of this (sequence, head): bits of a float >= 0
+    float ss = sumsq8(wk);
+    for (int o2 = 1; o2 < 8; o2 <<= 1) ss += __shfl_xor(ss, o2, 64);
+    ss = wave_max(ss);
+    if ((t & 63) == 0) atomicMax(&kmax[blockIdx.y], __float_as_uint(sqrtf(ss)));
+  }
   const size_t tile = ((size_t)blockIdx.y * n_kt + kt) * 4 * kFragU4;
   kp[tile + (chunk >> 1) * kFragU4 + (chunk & 1) * 32 + key] = wk;
   *(u32x4 *)&vt[key][chunk * 8] = wv;
@@ -101,7 +108,7 @@ constexpr int kVSlots = 3;           // LDS ring slots of 64-key V tiles
 __global__ __launch_bounds__(512) void k_attn_bf16(
     const uint16_t *q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp, uint16_t *o,
     const uint16_t *res, int64_t n, int heads, int n_seq, int n_kt, int nqb, float c,
-    int qk_norm) {
+    int qk_norm, const uint32_t *__restrict__ redo) {
   __shared__ u32x4 ks[kKSlots][8 * kFragU4];
   __shared__ u32x4 vs[kVSlots][8 * kFragU4];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ql = lane & 31;
@@ -117,6 +124,9 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
     sh = blockIdx.x / nqb;
     qb = blockIdx.x % nqb;
   }
+  // second pass behind the per-row-reference kernel: only the query blocks it left undone (one
+  // flag per 256 queries; the whole workgroup takes the same branch, before any barrier)
+  if (redo && redo[(size_t)sh * (2 * nqb) + 2 * qb] == 0u && redo[(size_t)sh * (2 * nqb) + 2 * qb + 1] == 0u) return;
   const int seq = sh / heads, head = sh - seq * heads;
   q += (size_t)seq * n * C;
   o += (size_t)seq * n * C;
@@ -333,12 +343,15 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
   }
 
   // ---- normalise and store: lane holds query column ql, rows d = 32dt + 8g + 4h + i
+  // second pass: the 256-query half that the first pass completed keeps its rows (with a fused
+  // residual in place they already hold the sum)
+  const bool mine = !redo || redo[(size_t)sh * (2 * nqb) + 2 * qb + grp] != 0u;
 #pragma unroll
   for (int sub = 0; sub < 2; ++sub) {
     const float l = lrow[sub] + __shfl_xor(lrow[sub], 32, 64);
     const float inv = 1.0f / l;
     const int64_t row = q0 + sub * 32 + ql;
-    if (row < n) {
+    if (row < n && mine) {
       uint16_t *op = o + (size_t)row * C + head * 64 + 4 * h;
 #pragma unroll
       for (int dt = 0; dt < 2; ++dt)
@@ -382,9 +395,11 @@ constexpr int kBQB = 256;            // queries per workgroup (4 waves)
 constexpr int kBStages = 4;          // LDS ring of 64-key K/V stages
 
 
+template <bool REF>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_bf16_bounded(
     const uint16_t *q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp, uint16_t *o,
-    const uint16_t *res, int64_t n, int heads, int n_seq, int n_kt, int nqb, float c) {
+    const uint16_t *res, int64_t n, int heads, int n_seq, int n_kt, int nqb, float c,
+    const uint32_t *__restrict__ kmax, uint32_t *__restrict__ redo, int redo_stride) {
   __shared__ u32x4 ks[kBStages][8 * kFragU4];
   __shared__ u32x4 vs[kBStages][8 * kFragU4];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ql = lane & 31;
@@ -426,8 +441,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   fetch(0);
   fetch(min(1, nkv - 1));
 
-  // Q^T fragments, RMS-normalised per head with the softmax scale (log2 units) folded in
+  // Q^T fragments, RMS-normalised per head with the softmax scale (log2 units) folded in.
+  // REF (q, k as given): only the scale is folded in, and the wave's 64 queries share the
+  // reference scale * max |q| * max |k| * (1 + 2^-7) >= any of their scores (Cauchy-Schwarz; the
+  // factor covers the bf16 rounding of the scaled q), which the scores start from.
   bf16x8 qf[2][4];
+  float rf[2] = {0.f, 0.f};
 #pragma unroll
   for (int sub = 0; sub < 2; ++sub) {
     const int64_t row = min(q0 + sub * 32 + ql, n - 1);
@@ -437,7 +456,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int s = 0; s < 4; ++s) w[s] = *(const u32x4 *)(qp + 16 * s);
     float ss = (sumsq8(w[0]) + sumsq8(w[1])) + (sumsq8(w[2]) + sumsq8(w[3]));
     ss += __shfl_xor(ss, 32, 64);
-    const float r = c / sqrtf(ss * (1.0f / 64.0f) + kQkEps);
+    const float r = REF ? c : c / sqrtf(ss * (1.0f / 64.0f) + kQkEps);
+    if (REF) rf[sub] = sqrtf(ss);
 #pragma unroll
     for (int s = 0; s < 4; ++s) qf[sub][s] = __builtin_bit_cast(bf16x8, scale8(w[s], r));
   }
@@ -450,7 +470,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[sub][dt][r] = 0.f;
   float lrow[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
-  const f32x16 kZero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // what the score accumulators start from: 0, or minus the reference of the wave's longest
+  // query (16 registers that stay live through the loop; one per query block would not fit, a
+  // subtraction per score would cost a fifth of the kernel's VALU time)
+  f32x16 s_start = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (REF) {
+    const float ref = c * wave_max(fmaxf(rf[0], rf[1])) * __uint_as_float(kmax[sh]) * (1.0f + 0.0078125f);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_start[r] = -ref;
+  }
 
   f32x16 sacc[2];      // [query block]: scores of its current 32-key tile
   u32x4 pb[2][2];      // [query block][u]: bf16 weights of its current 32-key tile
@@ -469,7 +497,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int f = 0; f < 4; ++f) dst[f] = kt[f * kFragU4];
   };
   auto mma_s = [&](int sub, const u32x4(&kf)[4]) {
-    f32x16 acc = kZero;
+    f32x16 acc = s_start;
 #pragma unroll
     for (int s = 0; s < 4; ++s)
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[s]), qf[sub][s],
@@ -621,10 +649,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   mma_pv(0, fv[1]);
   mma_pv(1, fv[1]);
 
+  float lsub[2];
 #pragma unroll
   for (int sub = 0; sub < 2; ++sub) {
     const float lsum = lrow[sub][0] + lrow[sub][1];
-    const float l = lsum + __shfl_xor(lsum, 32, 64);
+    lsub[sub] = lsum + __shfl_xor(lsum, 32, 64);
+  }
+  if (REF) {
+    // A row whose scores all lie ~60 binades or more below its reference (the bound is loose when
+    // no key is both long and aligned with the query) has lost its weights to underflow: the whole
+    // 256-query block is left to the running-maximum kernel, and nothing of it is written here
+    // (the output may alias the residual).
+    bool low = false;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) low |= q0 + sub * 32 + ql < n && !(lsub[sub] >= 8.67e-19f);   // 2^-60
+    if (__syncthreads_or(low)) {
+      if (tid == 0) redo[(size_t)sh * redo_stride + qb] = 1u;
+      return;
+    }
+  }
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) {
+    const float l = lsub[sub];
     const float inv = 1.0f / l;
     const int64_t row = q0 + sub * 32 + ql;
     if (row < n) {
@@ -1285,6 +1331,8 @@ size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype, int n_seq) {
   // the second-pass kernel, and the flags
   size_t total = 256 + 2 * align_up(per, 256);
   if (attn_dtype == LV_ATTN_FP8_E4M3) total += 2 * align_up(per, 256) + align_up(fp8_flag_words(heads, n_tokens) * 4, 256);
+  // bf16 without qk_norm: per (sequence, head) the largest |k|, then the flags of the first pass
+  else total += align_up(((size_t)heads * n_seq + fp8_flag_words(heads * n_seq, n_tokens)) * 4, 256);
   return total;
 }
 
@@ -1340,20 +1388,32 @@ int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_
   const size_t per = align_up((size_t)heads * n_seq * n_kt * 4 * kFragU4 * sizeof(u32x4), 256);
   u32x4 *kp = (u32x4 *)frag;
   u32x4 *vp = (u32x4 *)(frag + per);
-  hipLaunchKernelGGL(k_attn_pack, dim3((unsigned)n_kt, (unsigned)(heads * n_seq)), dim3(256), 0, st,
-                     k, v, n, heads, n_kt, qk_norm, kp, vp);
-  if (after_pack && hipEventRecord(after_pack, st) != hipSuccess) return LV_ERR_HIP;
-  // |q.k| <= 64 * (1 + 2^-8) for unit-RMS heads rounded to bf16; exp2 of the scaled score must
-  // stay well inside fp32 range even summed over the sequence
+  // three ways: q, k normalised with exponents that stay in range: the branch-free kernel;
+  // q, k as given: the same kernel with a per-query reference from |q| and the head's largest
+  // |k|, then the running-maximum kernel on the blocks where that bound was too loose (normally
+  // none: its workgroups return at once); otherwise the running-maximum kernel alone
   const bool bounded = qk_norm && 64.25f * c <= 64.0f;
-  if (bounded) {
-    const int nqb2 = (int)((n + kBQB - 1) / kBQB);
-    hipLaunchKernelGGL(k_attn_bf16_bounded, dim3((unsigned)(nqb2 * heads * n_seq)), dim3(256), 0,
-                       st, q, kp, vp, o, res, n, heads, n_seq, n_kt, nqb2, c);
-  } else {
-    hipLaunchKernelGGL(k_attn_bf16, dim3((unsigned)(nqb * heads * n_seq)), dim3(512), 0, st, q, kp,
-                       vp, o, res, n, heads, n_seq, n_kt, nqb, c, qk_norm);
+  const bool by_ref = !qk_norm;
+  uint32_t *kmax = (uint32_t *)(frag + 2 * per);
+  uint32_t *redo = kmax + (size_t)heads * n_seq;
+  if (by_ref) {
+    const size_t words = (size_t)heads * n_seq + fp8_flag_words(heads * n_seq, n);
+    hipLaunchKernelGGL(k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, kmax, words);
   }
+  hipLaunchKernelGGL(k_attn_pack, dim3((unsigned)n_kt, (unsigned)(heads * n_seq)), dim3(256), 0, st,
+                     k, v, n, heads, n_kt, qk_norm, kp, vp, by_ref ? kmax : (uint32_t *)nullptr);
+  if (after_pack && hipEventRecord(after_pack, st) != hipSuccess) return LV_ERR_HIP;
+  const int nqb2 = (int)((n + kBQB - 1) / kBQB);
+  if (bounded)
+    hipLaunchKernelGGL(k_attn_bf16_bounded<false>, dim3((unsigned)(nqb2 * heads * n_seq)), dim3(256), 0,
+                       st, q, kp, vp, o, res, n, heads, n_seq, n_kt, nqb2, c, (const uint32_t *)nullptr,
+                       (uint32_t *)nullptr, 0);
+  if (by_ref)
+    hipLaunchKernelGGL(k_attn_bf16_bounded<true>, dim3((unsigned)(nqb2 * heads * n_seq)), dim3(256), 0,
+                       st, q, kp, vp, o, res, n, heads, n_seq, n_kt, nqb2, c, kmax, redo, 2 * nqb);
+  if (!bounded)
+    hipLaunchKernelGGL(k_attn_bf16, dim3((unsigned)(nqb * heads * n_seq)), dim3(512), 0, st, q, kp,
+                       vp, o, res, n, heads, n_seq, n_kt, nqb, c, qk_norm, by_ref ? redo : (const uint32_t *)nullptr);
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;
 }

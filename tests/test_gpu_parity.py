@@ -413,6 +413,71 @@ def test_global_attn_qk_norm(B):
     assert max_rel_err(ref_plain, ref) > 0.1
 
 
+def _loose_bound_rows(rng, n_seq, n, heads):
+    """q = k rows (per sequence) for which the per-query score bound |q| max|k| used without
+    qk_norm is tight for some 256-query blocks and useless for others: one key per sequence is
+    40 times longer than the rest, the queries of block 1 (rows 256 .. 511) are 50 times shorter."""
+    x = rng.standard_normal((n_seq, n, heads, 64))
+    x[:, 7] *= 40.0
+    x[:, 256:512] *= 0.02
+    return x.reshape(n_seq * n, heads * 64).astype(np.float32)
+
+
+@pytest.mark.parametrize("scale", [1.0, 4.0])
+def test_global_attn_plain_qk_loose_score_bound(B, scale):
+    """Without qk_norm the kernel exponentiates every query against scale |q| max|k|.  Blocks in
+    which some row's scores all sit more than ~60 binades below that are recomputed with a running
+    maximum; scale 4 puts every block there, scale 1 only the blocks with ordinary queries next
+    to the long key.  Either way the result is the softmax of the definition."""
+    import torch
+    n, heads = 1374, 3
+    rng = np.random.default_rng(int(scale * 10))
+    qb = synth.f32_to_bf16_bits(scale * _loose_bound_rows(rng, 1, n, heads))
+    vb = synth.f32_to_bf16_bits(rng.standard_normal((n, heads * 64)).astype(np.float32))
+    ph = B.make_params(1, 1, 1, heads * 64, heads, n_special=0)
+    ws = B.alloc_ws(B.litevggt_attn_ws_bytes(ph, n))
+    o = torch.zeros(n, heads * 64, dtype=torch.bfloat16, device="cuda")
+    B.litevggt_global_attn(ph, n, to_dev_bf16(qb), to_dev_bf16(qb), to_dev_bf16(vb), o, ws)
+    torch.cuda.synchronize()
+    qs, vs = (synth.bf16_bits_to_f32(b).reshape(n, heads, 64) for b in (qb, vb))
+    ref = O.attention(qs, qs, vs)
+    got = dev_bf16_to_f64(o).reshape(n, heads, 64)
+    assert np.all(np.isfinite(got))
+    assert max_rel_err(got, ref) <= BF16_TOL
+    if scale == 1.0:
+        # flags of the first pass: one word per (head, 256-query block), rows of 2 * ceil(n / 512)
+        # words, behind the per-head largest |k|; block 1 (short queries) is the one not redone
+        base = (ws.data_ptr() + 255) // 256 * 256 - ws.data_ptr() + 256
+        per = (heads * 2 * ((n + 63) // 64) * 4 * 64 * 16 + 255) // 256 * 256
+        stride = 2 * ((n + 511) // 512)
+        words = ws[base + 2 * per:base + 2 * per + (heads + heads * stride) * 4].cpu().numpy().view(np.uint32)
+        kmax = words[:heads].view(np.float32)
+        assert np.allclose(kmax, np.sqrt((qs.astype(np.float64) ** 2).sum(-1)).max(0), rtol=1e-5)
+        flags = words[heads:].reshape(heads, stride)[:, :6] != 0
+        assert np.array_equal(flags, np.array([[True, False, True, True, True, True]] * heads))
+
+
+def test_frame_attn_plain_qk_loose_score_bound_residual_in_place(B):
+    """Same data per frame, with the fused residual in place: a 512-query block of the second
+    pass has one half already finished by the first pass (rows 256 .. 511), which must keep the
+    sum it holds and not get the attention added twice."""
+    import torch
+    frames, grid, heads = 2, 37, 4
+    wl = small_workload(frames=frames, grid=grid, dim=64 * heads, heads=heads, r=0.5)
+    po, ph = oracle_params(wl, qk_norm=False), hip_params(wl, qk_norm=0)
+    rng = np.random.default_rng(5)
+    N, C, T = wl.n_tokens, wl.dim, wl.n_tokens // frames
+    qb = synth.f32_to_bf16_bits(_loose_bound_rows(rng, frames, T, heads))
+    vb, rb = (synth.f32_to_bf16_bits(rng.standard_normal((N, C)).astype(np.float32)) for _ in range(2))
+    q, v, r = (synth.bf16_bits_to_f32(a).astype(np.float64) for a in (qb, vb, rb))
+    want = r + O.frame_attention(q.reshape(N, heads, 64), q.reshape(N, heads, 64), v.reshape(N, heads, 64), po).reshape(N, C)
+    ws = B.alloc_ws(B.litevggt_frame_attn_ws_bytes(ph))
+    x = to_dev_bf16(rb)
+    B.litevggt_frame_attn(ph, to_dev_bf16(qb), to_dev_bf16(qb), to_dev_bf16(vb), x, x, ws)
+    torch.cuda.synchronize()
+    assert max_rel_err(dev_bf16_to_f64(x), want) <= BF16_TOL
+
+
 FP8_TOL = 6e-2
 # FP8 linear layers against the oracle with the same quantisation points.  The two sides agree
 # on a stored bf16 intermediate only up to its rounding step: the attention output carries a
