@@ -57,6 +57,8 @@ def parse_args():
     ap.add_argument("--no-unmerged", action="store_true",
                     help="skip the one-launch unmerged attention baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true",
+                    help="skip the probes of what this box sustains (pure MFMA loops, plain copy)")
     ap.add_argument("--cpu-frames", type=int, default=96,
                     help="frames of the sub-sequence the CPU oracle is timed on")
     return ap.parse_args()
@@ -154,6 +156,41 @@ def cpu_baseline(wl, pl_full, n_frames):
                         f"{sum(t.values()):.1f} s measured; each step scaled to the full "
                         f"sequence by its operation count (extrapolated step: {full:.0f} s)"),
                 measured_s={k: round(v, 3) for k, v in t.items()})
+
+
+def sustained_peaks(B, torch):
+    """What this machine gives the simplest possible kernels (the library's probes): loops of
+    independent MFMAs on data loaded once, a plain 16-byte-per-lane copy and read of 2 GiB.
+    Run after the timed steps; context for the fractions of the published peaks."""
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / reps
+    out = torch.empty(2048 * 512, dtype=torch.float32, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(1)
+    vals = torch.randn(65536, device="cuda", generator=g)
+    res = {}
+    for name, dt, ops, iters in (("mfma_bf16_tflops", B.ATTN_BF16, vals.to(torch.bfloat16), 40000),
+                                 ("mfma_fp8_tflops", B.ATTN_FP8_E4M3,
+                                  torch.cat([vals, vals.flip(0)]).to(torch.float8_e4m3fn), 20000)):
+        assert ops.numel() * ops.element_size() == 128 * 1024
+        t = timed(lambda: B.litevggt_probe_mfma(dt, ops, iters, out), 2)
+        res[name] = B.litevggt_probe_mfma_flop(dt, iters) / t / 1e12
+    nbytes = 2 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").random_(0, 256, generator=g)
+    dst = torch.empty_like(src)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    res["copy_gbs"] = 2 * nbytes / timed(lambda: B.litevggt_probe_stream(src, dst, nbytes, sink), 10) / 1e9
+    res["read_gbs"] = nbytes / timed(lambda: B.litevggt_probe_stream(src, None, nbytes, sink), 10) / 1e9
+    res["note"] = ("litevggt_probe_mfma / litevggt_probe_stream: 2048 x 8 waves of independent 32x32 MFMAs on "
+                   "operands loaded once; copy = bytes read + written of a 2 GiB buffer")
+    return res
 
 
 def main():
@@ -368,6 +405,8 @@ def main():
     }
     if unmerged:
         out["speedup_vs_unmerged_stack"] = unmerged["ms_stack_extrapolated"] / ms_step
+    if not args.no_peaks:
+        out["sustained_peaks"] = sustained_peaks(B, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, pl, min(args.cpu_frames, wl.frames))
     print(json.dumps(out))

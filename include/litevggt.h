@@ -297,6 +297,27 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
                         int32_t *refresh_log, void **events, void *ws, size_t ws_bytes,
                         void *stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Measurement aids (no part of the method): what this GPU sustains on the two resources the
+ * kernels' rooflines are quoted against, with nothing else in the way.  A benchmark runs them
+ * next to the hot path and times them with events on `stream`.
+ *
+ * litevggt_probe_mfma: 2048 workgroups of 8 waves, each wave `iters` times 8 independent
+ *   32x32 MFMAs (dtype LV_ATTN_BF16: 32x32x16 bf16; LV_ATTN_FP8_E4M3: 32x32x64 E4M3) on operands
+ *   it loads once.  litevggt_probe_mfma_flop returns the flop of one such call (0 for bad
+ *   arguments).
+ *     operands [device] 128 KiB of operand bits (any finite bf16 / E4M3 values), read only
+ *     out      [device] 2048*512 fp32, written (keeps the result alive; no meaning)
+ *   errors: NULL -> LV_ERR_NULL, iters outside 1 .. 2^20 -> LV_ERR_SHAPE, other dtype ->
+ *   LV_ERR_DTYPE.
+ * litevggt_probe_stream: dst != NULL: copies `bytes` from src to dst (bytes read + bytes
+ *   written = 2*bytes of HBM traffic); dst == NULL: reads src only.  16 B per lane and access.
+ *     src, dst [device] 16-byte aligned, bytes a positive multiple of 16; sink [device] 4 bytes
+ */
+double litevggt_probe_mfma_flop(int dtype, int iters);
+int litevggt_probe_mfma(int dtype, const void *operands, int iters, float *out, void *stream);
+int litevggt_probe_stream(const void *src, void *dst, size_t bytes, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,8 @@ EXPORTS = ["litevggt_strerror", "litevggt_plan", "litevggt_attn_ws_bytes", "lite
            "litevggt_select_anchors", "litevggt_match", "litevggt_merge", "litevggt_global_attn",
            "litevggt_unmerge", "litevggt_frame_attn_ws_bytes", "litevggt_frame_attn",
            "litevggt_global_block_ws_bytes", "litevggt_global_block",
-           "litevggt_layers_run"]
+           "litevggt_layers_run", "litevggt_probe_mfma", "litevggt_probe_stream",
+           "litevggt_probe_mfma_flop"]
 
 
 class LiteVGGTError(RuntimeError):
@@ -111,9 +112,13 @@ def lib() -> C.CDLL:
         L.litevggt_frame_attn.argtypes = [PP, vp, vp, vp, vp, vp, vp, sz, vp]
         L.litevggt_layers_run.argtypes = [PP, i32, vp, vp, C.POINTER(Index), vp, vp,
                                           C.POINTER(C.c_int32), C.POINTER(C.c_void_p), vp, sz, vp]
+        L.litevggt_probe_mfma.argtypes = [i32, vp, i32, vp, vp]
+        L.litevggt_probe_stream.argtypes = [vp, vp, sz, vp, vp]
+        L.litevggt_probe_mfma_flop.argtypes = [i32, i32]
         for name in EXPORTS[1:]:
             if not name.endswith("_ws_bytes"):
                 getattr(L, name).restype = i32
+        L.litevggt_probe_mfma_flop.restype = C.c_double
         _lib = L
     return _lib
 
@@ -273,3 +278,17 @@ def litevggt_layers_run(p: Params, n_layers: int, images, x, index: IndexBuffers
                                      _stream()),
            "litevggt_layers_run")
     return list(log)[:n_layers]
+
+
+# ------------------------------------------------------------------ measurement aids
+def litevggt_probe_mfma_flop(dtype: int, iters: int) -> float:
+    return float(lib().litevggt_probe_mfma_flop(dtype, iters))
+
+
+def litevggt_probe_mfma(dtype: int, operands, iters: int, out) -> None:
+    _check(lib().litevggt_probe_mfma(dtype, _ptr(operands), iters, _ptr(out), _stream()), "litevggt_probe_mfma")
+
+
+def litevggt_probe_stream(src, dst, nbytes: int, sink) -> None:
+    _check(lib().litevggt_probe_stream(_ptr(src), _ptr(dst), nbytes, _ptr(sink), _stream()),
+           "litevggt_probe_stream")

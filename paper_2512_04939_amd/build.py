@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblitevggt.so")
 SOURCES = ["api.hip", "importance.hip", "select.hip", "match.hip", "merge.hip", "attn.hip",
-           "block.hip"]
+           "block.hip", "probe.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms are kept out of the generated code on this target
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

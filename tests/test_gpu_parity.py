@@ -1004,3 +1004,34 @@ def test_layer_driver_replays_from_a_hip_graph(B):
         B.litevggt_unmerge(ph, torch.zeros(pl.M, wl.dim, dtype=torch.bfloat16, device="cuda"), ib, x_dev, y)
         torch.cuda.synchronize()
         assert torch.equal(y, x_dev)
+
+
+# ------------------------------------------------------------------------- measurement aids
+def test_probes(B):
+    """The probes the benchmark reads sustained rates from: the copy copies, the read-only form
+    leaves the destination alone, the MFMA loops run and report the flop they do."""
+    import torch
+    n = (1 << 20) + 48
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.litevggt_probe_stream(src, None, n, sink)
+    torch.cuda.synchronize()
+    assert int(dst.max()) == 0
+    B.litevggt_probe_stream(src, dst, n, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    with pytest.raises(B.LiteVGGTError):
+        B.litevggt_probe_stream(src, dst, n - 1, sink)
+    out = torch.zeros(2048 * 512, device="cuda")
+    ones = torch.ones(65536, dtype=torch.bfloat16, device="cuda")
+    B.litevggt_probe_mfma(B.ATTN_BF16, ones, 3, out)
+    torch.cuda.synchronize()
+    # 8 tiles x 16 accumulator entries per lane, each 3 iterations x 16 products of 1 x 1
+    assert float(out.min()) == float(out.max()) == 8 * 16 * 3 * 16
+    ones8 = torch.ones(131072, device="cuda").to(torch.float8_e4m3fn)
+    B.litevggt_probe_mfma(B.ATTN_FP8_E4M3, ones8, 2, out)
+    torch.cuda.synchronize()
+    assert float(out.min()) == float(out.max()) == 8 * 16 * 2 * 64
+    assert B.litevggt_probe_mfma_flop(B.ATTN_BF16, 10) == 2048 * 8 * 10 * 8 * 2 * 32 * 32 * 16
+    assert B.litevggt_probe_mfma_flop(B.ATTN_FP8_E4M3, 10) == 4 * B.litevggt_probe_mfma_flop(B.ATTN_BF16, 10)
