@@ -114,6 +114,7 @@ constexpr int kGTile = 256;          // src and dst rows per workgroup tile
 constexpr int kGStages = 4;          // LDS ring depth
 constexpr int kGStageU4 = 2 * 2 * 8 * 64;   // u32x4 per stage: [src|dst][2 k-steps][8 fragments][64 lanes]
 constexpr int kTeamSpin = 512;       // polls of the team counter before a workgroup goes on alone
+constexpr int kInvBufs = 8;          // per-wave LDS buffers of 64 inverse dst norms
 constexpr int kGLanes = 4;           // dst tiles are dealt to this many workgroups per src tile
 
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_match_sim(
@@ -146,7 +147,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // fetch: this wave moves fragments f = 4*wave .. 4*wave+3 of a stage (f = op*16 + ks*8 + a)
     const int f_op = wave >> 2, f_ks = (wave >> 1) & 1, f_a0 = (wave & 1) * 4;
     int pf_tile = dl, pf_s = 0, pf_g = 0;      // next stage to fetch: dst tile, stage in tile, flat index
+    int pf_t = 0;                              // tiles whose first stage has been requested
+    // the inverse norms of this wave's 64 dst rows travel with the first stage of their tile
+    // into a wave-private LDS buffer, so the fold at the end of the tile has them without a
+    // memory round trip.  kInvBufs buffers in turn: stages are requested up to kGStages ahead,
+    // which with one stage per tile (C = 32) is that many tiles not yet folded.
+    float *inv_lds = (float *)(ring + (size_t)kGStages * kGStageU4) + wave * (kInvBufs * 64);
     auto fetch = [&]() {
+      if (pf_s == 0 && pf_g < total) {
+        __builtin_amdgcn_global_load_lds(invd + (size_t)pf_tile * kGTile + wd * 64 + lane,
+                                         inv_lds + (pf_t & (kInvBufs - 1)) * 64, 4, 0, 0);
+        ++pf_t;
+      }
       const int tile = f_op ? pf_tile : st;
       const u32x4 *src = (f_op ? dstp : srcp) +
                          ((size_t)(tile * 8 + f_a0) * KS + (size_t)(pf_s * 2 + f_ks)) * 64 + lane;
@@ -195,6 +207,15 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                                                __builtin_bit_cast(bf16x8, b[bi]),
                                                                acc[ai][bi], 0, 0, 0);
     };
+    auto mma_first = [&](const u32x4(&b)[4], const u32x4(&a)[2]) {   // first k-step of a tile: starts from zero
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+        for (int ai = 0; ai < 2; ++ai)
+          acc[ai][bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[ai]),
+                                                               __builtin_bit_cast(bf16x8, b[bi]), zero, 0, 0, 0);
+    };
     auto mma_pair = [&](const u32x4(&b)[4], const u32x4(&a)[2], int bi) {   // the two MFMAs of column block bi
 #pragma unroll
       for (int ai = 0; ai < 2; ++ai)
@@ -207,11 +228,32 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // with 64 columns per wave "some lane of the wave has such an element in this tile" is true
     // nearly always, so the test is made per element: a compare per element and one branch per
     // tile in the common case, the insertion code only for the elements that need it.
-    auto fold = [&](int tile) {
+    //
+    // A column's rows are spread over eight running pairs (four waves, two lane halves), each
+    // of which alone would let through about 2 ln(rows / 8) elements.  The test is therefore
+    // made against thr >= the largest second best any of the eight had at the end of the
+    // previous tile (exchanged through LDS once per tile): an element at or below it cannot be
+    // one of the column's two best, and with equal values it has the higher row index, because
+    // earlier tiles hold lower rows.  Two buffers by tile parity: a wave that is already done
+    // with this tile writes the other one (bounds from this tile's rows could tie with a lower
+    // row that a slower wave has yet to see), and nobody is more than one tile-end barrier apart.
+    float *share = (float *)(ring + (size_t)kGStages * kGStageU4) + 8 * kInvBufs * 64;   // [parity][wsrc][b][wd][column]
+    float thr[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {   // before the first barrier of the super-row
+      share[((wsrc * 4 + b) * 4 + wd) * 32 + (lane & 31)] = -INFINITY;
+      share[1024 + ((wsrc * 4 + b) * 4 + wd) * 32 + (lane & 31)] = -INFINITY;
+    }
+    auto fold = [&](int tile, int buf, int parity) {
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          thr[b] = fmaxf(thr[b], share[parity * 1024 + ((wsrc * 4 + b) * 4 + w) * 32 + (lane & 31)]);
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
         const int row0 = tile * kGTile + wd * 64 + a * 32 + h * 4;
-        const f32x4 *ip = (const f32x4 *)(invd + row0);
+        const f32x4 *ip = (const f32x4 *)(inv_lds + buf * 64 + a * 32 + h * 4);
         f32x4 iv[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) iv[g] = ip[2 * g];
@@ -222,7 +264,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             v[r] = acc[a][b][r] * iv[r >> 2][r & 3];
-            hit[r] = __builtin_amdgcn_ballot_w64(v[r] > best[b].v2);
+            hit[r] = __builtin_amdgcn_ballot_w64(v[r] > thr[b]);
             any |= hit[r];
           }
           if (any != 0) {
@@ -233,8 +275,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 if (j2 < n_dst) top2_insert_any(best[b], v[r], j2);
               }
             }
+            thr[b] = fmaxf(thr[b], best[b].v2);
           }
         }
+      }
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        thr[b] = fmaxf(thr[b], __shfl_xor(thr[b], 32, 64));   // the other half of the wave has the same column
+        share[(parity ^ 1) * 1024 + ((wsrc * 4 + b) * 4 + wd) * 32 + (lane & 31)] = thr[b];
       }
     };
 
@@ -251,7 +299,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       wait_frags(fb[0], fa[0]);
       read_frags(g, 1, fb[1], fa[1]);
       __builtin_amdgcn_sched_barrier(0);
-      mma(fb[0], fa[0]);
+      if (sidx == 0) mma_first(fb[0], fa[0]);
+      else mma(fb[0], fa[0]);
       // k-step 1 of stage g: its fragments are in registers, so the slot of stage g is free once
       // every wave is here; stage g+1 is published by the same barrier.  The barrier, the
       // fetch instructions and the fragment reads sit between pairs of MFMAs, so that the MFMA
@@ -278,8 +327,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         // XCD's L2 when the others ask for it.  The wait is advisory: it is bounded, and no
         // result depends on it.
         if (tid == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        fold(tile);
-        clear_acc();
+        fold(tile, steps & (kInvBufs - 1), steps & 1);
         sidx = 0;
         tile += n_lanes;
         ++steps;
@@ -548,7 +596,9 @@ int launch_match(const uint16_t *x, const Dims &d, const litevggt_plan_t &pl,
   const int n_src = (int)pl.n_src, n_dst = (int)pl.n_dst;
   if (n_src > 0) {
     if (d.C % 32 != 0 || n_dst <= 0) return LV_ERR_SHAPE;
-    const size_t lds = (size_t)kGStages * kGStageU4 * 16;        // 128 KB ring (reused for the final merge)
+    // 128 KB ring (reused for the final merge) + per wave kInvBufs buffers of 64 inverse norms
+    // and two buffers of 8 x 4 x 32 second-best bounds the waves of a column exchange
+    const size_t lds = (size_t)kGStages * kGStageU4 * 16 + 8 * kInvBufs * 64 * sizeof(float) + 2 * 1024 * sizeof(float);
     static std::atomic<uint64_t> lds_done{0};
     if (int rc = allow_dynamic_lds((const void *)k_match_sim, lds, lds_done)) return rc;
     const unsigned rows_grid = (unsigned)(((d.N + 3) / 4) < 16384 ? ((d.N + 3) / 4) : 16384);
