@@ -321,6 +321,10 @@ def main():
                     continue
                 dur[k].append(ev.ms(l * E + a, l * E + b))
     avg = {k: (sum(v) / len(v) if v else 0.0) for k, v in dur.items()}
+    # each step on the device's clock: first to last event of its driver call
+    last_ev = (L - 1) * E + B.EV_FRAME_ATTN_END
+    step_ms = sorted(ev.ms(B.EV_LAYER_BEGIN, last_ev) for ev in evs)
+    step_median = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
     for ev in evs:
         ev.close()
 
@@ -394,7 +398,9 @@ def main():
                    "input_generation_s": gen_s,
                    "h2d_upload_s": h2d_s, "h2d_upload_gbs": h2d_bytes / h2d_s / 1e9,
                    "tokens_per_s_with_upload": N / (ms_step * 1e-3 + h2d_s),
-                   "calibration_copy_bytes": CALIBRATION_COPY_BYTES},
+                   "calibration_copy_bytes": CALIBRATION_COPY_BYTES,
+                   "device_ms_per_step_median": step_median, "device_ms_per_step_min": step_ms[0],
+                   "device_ms_per_step_max": step_ms[-1]},
         "roofline": {"kernel": ("k_attn_fp8" if args.attn_dtype == "fp8" else "k_attn_bf16_bounded" if wl_qk_norm else "k_attn_bf16"), "bound": "mfma", "achieved": attn_tf, "peak": peak_tf,
                      "unit": "TFLOP/s", "frac": attn_tf / peak_tf,
                      "traffic": measured_traffic(wl.name, args.attn_dtype),
