@@ -200,6 +200,25 @@ def test_match_exact_duplicates_pick_lowest_index(B):
     assert _check_match(B, case_like) == 0
 
 
+def test_match_exact_duplicates_across_dst_tiles(B):
+    """Noise-free frames with enough dst tokens that every sweep of the similarity kernel visits
+    several 256-row dst tiles: exact ties between dst rows of different tiles (lower rows are
+    seen first and must win), with the waves' second-best bounds exchanged between the tiles."""
+    import torch
+    wl = small_workload(frames=16, grid=24, dim=64, heads=1, r=0.25, seed=5)
+    gen = synth.Generator(wl, noise_std=0.0)
+    bits = synth.f32_to_bf16_bits(gen.tokens())
+    xf = synth.bf16_bits_to_f32(bits)
+    po, ph = oracle_params(wl), hip_params(wl)
+    pl = B.litevggt_plan(ph)
+    assert pl.n_dst > 8 * 256
+    idx, _, _, mt = O.compute_index(gen.images(), xf, po)
+    tied = mt["best"] - mt["second"] == 0
+    assert tied.sum() > 100
+    case_like = dict(pl=pl, idx=idx, mt=mt, ph=ph, xf=xf, x_dev=to_dev_bf16(bits))
+    assert _check_match(B, case_like) == 0
+
+
 def test_match_constant_features_one_giant_group(B):
     """All tokens identical: every src ties on every dst and must pick the first dst."""
     import torch
