@@ -56,6 +56,9 @@ def parse_args():
                          "(reported as config.graph_replay_ms_per_step; `value` stays the eager run)")
     ap.add_argument("--no-unmerged", action="store_true",
                     help="skip the one-launch unmerged attention baseline")
+    ap.add_argument("--qk-norm", type=int, default=1, choices=[0, 1],
+                    help="1 (default): q and k RMS-normalised per head as in the model; 0: as given "
+                         "(per-wave score bound, running-maximum second pass where it is loose)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peaks", action="store_true",
                     help="skip the probes of what this box sustains (pure MFMA loops, plain copy)")
@@ -225,7 +228,7 @@ def main():
                              fp8_state=fp8_state)
     ph = B.make_params(wl.frames, wl.grid_h, wl.grid_w, wl.dim, wl.heads, n_special=wl.n_special,
                        patch=wl.patch, merge_ratio=wl.merge_ratio,
-                       refresh_interval=wl.refresh_interval, qk_norm=1, attn_dtype=attn_dtype,
+                       refresh_interval=wl.refresh_interval, qk_norm=args.qk_norm, attn_dtype=attn_dtype,
                        anchor_policy=dict(ga=B.POLICY_GA, fixed=B.POLICY_FIXED,
                                           random=B.POLICY_RANDOM)[args.anchor_policy],
                        frame_attn=1 if args.frame_attn else 0, block=bw)
@@ -390,7 +393,7 @@ def main():
                                f"{wl.merge_ratio} (M={M}), {L} global layers, index refreshed "
                                f"every {wl.refresh_interval}",
                    "token_layers_per_s": L * N / (ms_step * 1e-3),
-                   "anchor_policy": args.anchor_policy, "frame_attn": bool(args.frame_attn), "block": bool(args.block),
+                   "qk_norm": bool(args.qk_norm), "anchor_policy": args.anchor_policy, "frame_attn": bool(args.frame_attn), "block": bool(args.block),
                    "linear_dtype": args.linear_dtype if args.block else None,
                    "refresh_log": log, "output_finite": finite,
                    "graph_replay_ms_per_step": graph_ms,
@@ -401,7 +404,7 @@ def main():
                    "calibration_copy_bytes": CALIBRATION_COPY_BYTES,
                    "device_ms_per_step_median": step_median, "device_ms_per_step_min": step_ms[0],
                    "device_ms_per_step_max": step_ms[-1]},
-        "roofline": {"kernel": ("k_attn_fp8" if args.attn_dtype == "fp8" else "k_attn_bf16_bounded" if wl_qk_norm else "k_attn_bf16"), "bound": "mfma", "achieved": attn_tf, "peak": peak_tf,
+        "roofline": {"kernel": ("k_attn_fp8_bounded" if args.attn_dtype == "fp8" and wl_qk_norm else "k_attn_fp8" if args.attn_dtype == "fp8" else "k_attn_bf16_bounded"), "bound": "mfma", "achieved": attn_tf, "peak": peak_tf,
                      "unit": "TFLOP/s", "frac": attn_tf / peak_tf,
                      "traffic": measured_traffic(wl.name, args.attn_dtype),
                      "flop_per_launch": attn_flop, "avg_launch_ms": avg["attn"],

@@ -160,7 +160,7 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[sub][dt][r] = 0.f;
-  float mref[2] = {-INFINITY, -INFINITY}, mc[2] = {0.f, 0.f}, lrow[2] = {0.f, 0.f};
+  float mref[2] = {-INFINITY, -INFINITY}, lrow[2] = {0.f, 0.f};
   const bf16x2 kOnes = {(__bf16)1.0f, (__bf16)1.0f};
 
   const int nkv = n_kt >> 1;           // 64-key tiles
@@ -266,7 +266,6 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
           const float mnew = fmaxf(mref[sub], mx);
           const float alpha = __builtin_amdgcn_exp2f((mref[sub] - mnew) * c);
           mref[sub] = mnew;
-          mc[sub] = mnew * c;
           lrow[sub] *= alpha;
 #pragma unroll
           for (int dt = 0; dt < 2; ++dt)
@@ -283,8 +282,10 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float s0 = sacc[kt2][sub][8 * u + 2 * e], s1 = sacc[kt2][sub][8 * u + 2 * e + 1];
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0, c, -mc[sub]));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1, c, -mc[sub]));
+            // the difference first: scores are of any size here, and c * s - c * mref with the
+            // second product rounded is off by 2^-24 of it, i.e. by thousands once scores reach 1e11
+            const float p0 = __builtin_amdgcn_exp2f((s0 - mref[sub]) * c);
+            const float p1 = __builtin_amdgcn_exp2f((s1 - mref[sub]) * c);
             w[e] = pack_bf16(p0, p1);
             // row sum of the bf16-rounded weights (what the second MFMA really multiplies)
             ls = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e]), kOnes, ls, false);
@@ -392,6 +393,7 @@ __device__ __forceinline__ void lds_wait(u32x4 (&a)[4], u32x4 (&b)[4]) {
 }
 
 constexpr int kBQB = 256;            // queries per workgroup (4 waves)
+constexpr float kRefUseful = 256.0f; // largest per-wave score bound (log2 units) the first pass is tried with
 constexpr int kBStages = 4;          // LDS ring of 64-key K/V stages
 
 
@@ -478,6 +480,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const float ref = c * wave_max(fmaxf(rf[0], rf[1])) * __uint_as_float(kmax[sh]) * (1.0f + 0.0078125f);
 #pragma unroll
     for (int r = 0; r < 16; ++r) s_start[r] = -ref;
+    // Scores have to come within 60 of the bound for it to serve; when it is this large they
+    // almost never do (and not finite means they cannot), so the block goes to the second pass
+    // without being computed here first.
+    if (__syncthreads_or(!(ref <= kRefUseful))) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the two stages already requested land before the workgroup ends
+      if (tid == 0) redo[(size_t)sh * redo_stride + qb] = 1u;
+      return;
+    }
   }
 
   f32x16 sacc[2];      // [query block]: scores of its current 32-key tile
@@ -854,7 +864,7 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[sub][dt][r] = 0.f;
-  float mref[2] = {-INFINITY, -INFINITY}, mc[2] = {0.f, 0.f}, lrow[2] = {0.f, 0.f};
+  float mref[2] = {-INFINITY, -INFINITY}, lrow[2] = {0.f, 0.f};
 
   const int nkv = n_kt >> 1;
   const u32x2 *kh = kp + (size_t)head * n_kt * 4 * kFragU4;
@@ -941,7 +951,6 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
         const float mnew = fmaxf(mref[sub], mx);
         const float alpha = __builtin_amdgcn_exp2f((mref[sub] - mnew) * c);
         mref[sub] = mnew;
-        mc[sub] = mnew * c - kFp8PShift;
         lrow[sub] *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
@@ -949,18 +958,37 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
           for (int r = 0; r < 16; ++r) oacc[sub][dt][r] *= alpha;
       }
       float ls = lrow[sub];
+      // exp2(c (s - mref) + shift).  As one fma on c * mref - shift while that product is small
+      // enough to be exact to 2^-10 (this kernel is bound by its VALU instructions); beyond that
+      // (scores of any size come in here) the difference is taken first.
+      const float mc = mref[sub] * c - kFp8PShift;
+      if (__builtin_amdgcn_ballot_w64(!(fabsf(mc) < 16384.0f)) == 0) {
 #pragma unroll
-      for (int kt2 = 0; kt2 < 2; ++kt2)
+        for (int kt2 = 0; kt2 < 2; ++kt2)
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          float pv[8];
+          for (int u = 0; u < 2; ++u) {
+            float pv[8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt2][sub][8 * u + e], c, -mc[sub]));
-            ls += pv[e];   // row sum of the fp32 weights, before the cast
+            for (int e = 0; e < 8; ++e) {
+              pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt2][sub][8 * u + e], c, -mc));
+              ls += pv[e];   // row sum of the fp32 weights, before the cast
+            }
+            pb[sub][kt2][u] = u32x2{cvt4_fp8(pv[0], pv[1], pv[2], pv[3]), cvt4_fp8(pv[4], pv[5], pv[6], pv[7])};
           }
-          pb[sub][kt2][u] = u32x2{cvt4_fp8(pv[0], pv[1], pv[2], pv[3]), cvt4_fp8(pv[4], pv[5], pv[6], pv[7])};
-        }
+      } else {
+#pragma unroll
+        for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            float pv[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt2][sub][8 * u + e] - mref[sub], c, kFp8PShift));
+              ls += pv[e];
+            }
+            pb[sub][kt2][u] = u32x2{cvt4_fp8(pv[0], pv[1], pv[2], pv[3]), cvt4_fp8(pv[4], pv[5], pv[6], pv[7])};
+          }
+      }
       lrow[sub] = ls;
     }
     asm volatile("" : "+v"(pb[0][0][0]), "+v"(pb[0][0][1]), "+v"(pb[0][1][0]), "+v"(pb[0][1][1]),

@@ -476,6 +476,36 @@ def test_global_attn_plain_qk_loose_score_bound(B, scale):
         assert np.array_equal(flags, np.array([[True, False, True, True, True, True]] * heads))
 
 
+@pytest.mark.parametrize("attn", ["bf16", "fp8"])
+def test_global_attn_plain_qk_huge_scores(B, attn):
+    """q, k as given and 3e4 times larger than unit scale: scores near 1e10, where c * s and
+    c * reference each carry rounding errors in the thousands.  The weights must come from the
+    difference of the two: finite outputs, rows that still sum to one (v = 1 gives 1), and the
+    softmax is one-hot on the largest score, here each row's own key or a longer one."""
+    import torch
+    n, heads = 700, 2
+    rng = np.random.default_rng(31)
+    x = (rng.standard_normal((n, heads * 64)) * 3e4).astype(np.float32)
+    xb = synth.f32_to_bf16_bits(x)
+    ph = B.make_params(1, 1, 1, heads * 64, heads, n_special=0,
+                       attn_dtype=B.ATTN_FP8_E4M3 if attn == "fp8" else B.ATTN_BF16)
+    ws = B.alloc_ws(B.litevggt_attn_ws_bytes(ph, n))
+    o = torch.zeros(n, heads * 64, dtype=torch.bfloat16, device="cuda")
+    ones = torch.ones(n, heads * 64, dtype=torch.bfloat16, device="cuda")
+    xd = to_dev_bf16(xb)
+    B.litevggt_global_attn(ph, n, xd, xd, ones, o, ws)
+    torch.cuda.synchronize()
+    got = dev_bf16_to_f64(o)
+    assert np.all(np.isfinite(got))
+    assert np.abs(got - 1.0).max() <= (6e-2 if attn == "fp8" else 2.0 ** -7)
+    if attn == "bf16":
+        B.litevggt_global_attn(ph, n, xd, xd, xd, o, ws)
+        torch.cuda.synchronize()
+        xs = synth.bf16_bits_to_f32(xb).reshape(n, heads, 64)
+        ref = O.attention(xs, xs, xs)
+        assert max_rel_err(dev_bf16_to_f64(o).reshape(n, heads, 64), ref) <= BF16_TOL
+
+
 def test_frame_attn_plain_qk_loose_score_bound_residual_in_place(B):
     """Same data per frame, with the fused residual in place: a 512-query block of the second
     pass has one half already finished by the first pass (rows 256 .. 511), which must keep the
