@@ -68,8 +68,8 @@ int launch_grad_map(const void *images, int img_dtype, const Dims &d, int patch,
 // The workgroup slides along the row: for every grid column it loads the K tokens of that
 // column (rows i-R..i+R, clipped) once and keeps their per-channel sum and sum of squares
 // for the last K columns in registers; the window of an output column is the sum of those K
-// column partials, its variance E[x^2] - E[x]^2 in fp32 (inputs are bf16 and a window has at
-// most 25 cells: the cancellation costs ~1e-7 of E[x^2], far below the map's tolerance).
+// column partials, its variance E[d^2] - E[d]^2 in fp32 with d = x - (the frame's first patch
+// token), so that the cancellation costs ~1e-7 of the spread and not of a channel's offset.
 // Workgroups of consecutive grid rows are placed on the same XCD so the two neighbouring rows
 // they share are found in that XCD's L2.
 // ---------------------------------------------------------------------------------
@@ -94,12 +94,18 @@ __global__ __launch_bounds__(128) void k_var_map(const uint16_t *__restrict__ x,
     for (int u = 0; u < K; ++u)
 #pragma unroll
       for (int e = 0; e < 8; ++e) s1[u][e] = s2[u][e] = 0.f;
+    // Sums are taken of x - pivot, the pivot being the frame's first patch token: the variance
+    // does not change, and a channel that sits at a large offset (mean >> spread) no longer loses
+    // its spread in the rounding of E[x^2] - E[x]^2.
+    const u32x4 pbits = on ? *(const u32x4 *)(frame + c0) : u32x4{0u, 0u, 0u, 0u};
+    const float pv[8] = {bf16_lo(pbits.x), bf16_hi(pbits.x), bf16_lo(pbits.y), bf16_hi(pbits.y),
+                         bf16_lo(pbits.z), bf16_hi(pbits.z), bf16_lo(pbits.w), bf16_hi(pbits.w)};
     // the K tokens of a column are requested one column ahead of their use
     auto load_col = [&](int jj, u32x4(&w)[K]) {
 #pragma unroll
-      for (int a = 0; a < K; ++a) {          // rows outside the grid read as zeros: they add nothing
+      for (int a = 0; a < K; ++a) {          // rows outside the grid read as the pivot: they add nothing
         const int ii = i - R + a;
-        w[a] = u32x4{0u, 0u, 0u, 0u};
+        w[a] = pbits;
         if (on && jj < W && ii >= i0 && ii <= i1) w[a] = *(const u32x4 *)(frame + ((size_t)ii * W + jj) * C + c0);
       }
     };
@@ -114,19 +120,20 @@ __global__ __launch_bounds__(128) void k_var_map(const uint16_t *__restrict__ x,
 #pragma unroll
         for (int e = 0; e < 8; ++e) a1[e] = a2[e] = 0.f;
 #pragma unroll
-        for (int a = 0; a < K; ++a) {        // (zeros beyond the row end)
+        for (int a = 0; a < K; ++a) {        // (the pivot beyond the row end)
           const float v[8] = {bf16_lo(wcur[a].x), bf16_hi(wcur[a].x), bf16_lo(wcur[a].y), bf16_hi(wcur[a].y),
                               bf16_lo(wcur[a].z), bf16_hi(wcur[a].z), bf16_lo(wcur[a].w), bf16_hi(wcur[a].w)};
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            a1[e] += v[e];
-            a2[e] = __builtin_fmaf(v[e], v[e], a2[e]);
+            const float dlt = v[e] - pv[e];
+            a1[e] += dlt;
+            a2[e] = __builtin_fmaf(dlt, dlt, a2[e]);
           }
         }
 #pragma unroll
         for (int a = 0; a < K; ++a) wcur[a] = wnext[a];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {        // columns beyond the row end enter as zeros
+        for (int e = 0; e < 8; ++e) {        // columns beyond the row end enter as zeros of x - pivot
           s1[u][e] = a1[e];
           s2[u][e] = a2[e];
         }

@@ -94,6 +94,27 @@ def test_importance(case, B):
     assert torch.equal(score, score2)
 
 
+def test_importance_channels_with_large_offsets(B):
+    """Features whose channels sit at offsets 20-60 times their spread (as trained transformers
+    have): the variance map must not lose the spread in E[x^2] - E[x]^2."""
+    import torch
+    wl = small_workload(frames=2, grid=12, dim=128, heads=2, r=0.5, seed=4)
+    _, xf, im = stored_inputs(wl)
+    rng = np.random.default_rng(8)
+    off = rng.choice([-1.0, 1.0], size=wl.dim) * rng.uniform(20.0, 60.0, size=wl.dim)
+    bits = synth.f32_to_bf16_bits((xf + off).astype(np.float32))
+    xo = synth.bf16_bits_to_f32(bits)
+    ph = hip_params(wl)
+    F, P = wl.frames, wl.patches
+    grad = torch.zeros(F, P, device="cuda")
+    score = torch.zeros(F, P, device="cuda")
+    B.litevggt_importance(ph, torch.from_numpy(im).cuda(), to_dev_bf16(bits), grad, True, score,
+                          B.alloc_ws(F * P * 4))
+    torch.cuda.synchronize()
+    ref, _ = O.importance(im, xo, oracle_params(wl))
+    assert np.abs(score.cpu().numpy() - ref).max() <= 2e-5
+
+
 def test_importance_u8_images(B):
     import torch
     wl = small_workload(frames=2, grid=8, dim=64, heads=1, r=0.5, seed=3)
