@@ -497,6 +497,28 @@ def test_global_attn_plain_qk_loose_score_bound(B, scale):
         assert np.array_equal(flags, np.array([[True, False, True, True, True, True]] * heads))
 
 
+@pytest.mark.parametrize("attn,qk_norm", [("bf16", 0), ("bf16", 1), ("fp8", 0), ("fp8", 1)])
+def test_global_attn_all_zero_queries_and_keys(B, attn, qk_norm):
+    """q = k = 0 (zero norms, zero amax, a zero score bound): every weight is equal and every
+    output row is the mean of v."""
+    import torch
+    n, heads = 333, 2
+    rng = np.random.default_rng(32)
+    vb = synth.f32_to_bf16_bits(rng.standard_normal((n, heads * 64)).astype(np.float32))
+    ph = B.make_params(1, 1, 1, heads * 64, heads, n_special=0, qk_norm=qk_norm,
+                       attn_dtype=B.ATTN_FP8_E4M3 if attn == "fp8" else B.ATTN_BF16)
+    ws = B.alloc_ws(B.litevggt_attn_ws_bytes(ph, n))
+    o = torch.full((n, heads * 64), 7.0, dtype=torch.bfloat16, device="cuda")
+    zero = torch.zeros(n, heads * 64, dtype=torch.bfloat16, device="cuda")
+    B.litevggt_global_attn(ph, n, zero, zero, to_dev_bf16(vb), o, ws)
+    torch.cuda.synchronize()
+    want = np.broadcast_to(synth.bf16_bits_to_f32(vb).astype(np.float64).mean(axis=0), (n, heads * 64))
+    got = dev_bf16_to_f64(o)
+    assert np.all(np.isfinite(got))
+    # the mean of 333 standard normals is small: the bound is relative to |v|, not to the mean
+    assert np.abs(got - want).max() <= (6e-2 if attn == "fp8" else 2e-2) * 0.2
+
+
 @pytest.mark.parametrize("attn", ["bf16", "fp8"])
 def test_global_attn_plain_qk_huge_scores(B, attn):
     """q, k as given and 3e4 times larger than unit scale: scores near 1e10, where c * s and
