@@ -213,21 +213,47 @@ __device__ __forceinline__ void lds_read1_async(u32x4 &dst, uint32_t addr) {
 constexpr int kTile = 256;
 constexpr int kStages = 4;
 constexpr int kStageU4 = 2 * 2 * 8 * 64;     // [weights|activations][2 k-steps][8 fragments][64 lanes]
-constexpr int kOutPitch = kTile * 2 + 16;    // bytes per row of the transposed tile (+16: rows 4 apart miss each other's banks)
 
-__device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
+// GELU in its erf form, x * Phi(x).  erfc(|x| / sqrt 2) by the rational-times-exponential form of
+// Abramowitz & Stegun 7.1.26 (absolute error <= 1.5e-7, four orders below a bf16 step); the
+// negative side uses erfc itself, so nothing cancels there.  A third of erff's instructions: the
+// epilogue of the first MLP layer evaluates it 65536 times per tile.
+__device__ __forceinline__ float gelu_erf(float v) {
+  const float x = fabsf(v) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, x, 1.0f));
+  float p = __builtin_fmaf(1.061405429f, t, -1.453152027f);
+  p = __builtin_fmaf(p, t, 1.421413741f);
+  p = __builtin_fmaf(p, t, -0.284496736f);
+  p = __builtin_fmaf(p, t, 0.254829592f);
+  const float erfc_abs = p * t * __builtin_amdgcn_exp2f(-1.4426950408889634f * x * x);
+  return 0.5f * v * (v < 0.f ? erfc_abs : 2.0f - erfc_abs);
+}
 
 template <bool FP8>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_bt(
     const u32x4 *__restrict__ ap, const u32x4 *__restrict__ wp, int64_t M, int KS, int nt_n,
     const float *__restrict__ bias, int gelu, uint16_t *__restrict__ out, int split,
-    const float *__restrict__ alpha_p) {
+    const float *__restrict__ alpha_p, int n_tiles) {
   extern __shared__ u32x4 ring[];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wd = wave & 3, wn = wave >> 2;
-  const int tn = blockIdx.x % nt_n, tm = blockIdx.x / nt_n;
   const int total = KS >> 1;
+  // persistent: one workgroup per CU walks the tiles (a workgroup owns a whole CU's LDS, so a
+  // launch per tile would pay a dispatch between any two tiles of a CU)
+  // Workgroup w runs on XCD w % 8.  An XCD takes the row tiles tm = x, x + 8, ... and walks
+  // them with all their column tiles, so an activation tile is fetched into one L2 only and
+  // the 32 workgroups of an XCD share a few row tiles and the weights at any time.
+  const int nt_m = n_tiles / nt_n;
+  const int xcd = blockIdx.x & (kXcd - 1), per_xcd = (int)gridDim.x >> 3;
+  const bool by_xcd = (gridDim.x & (kXcd - 1)) == 0;
+  const int my_rows = by_xcd ? (nt_m - xcd + kXcd - 1) / kXcd : 0;   // row tiles of this XCD
+  const int my_tiles = by_xcd ? my_rows * nt_n : n_tiles;
+  for (int v = by_xcd ? (int)(blockIdx.x >> 3) : (int)blockIdx.x; v < my_tiles; v += by_xcd ? per_xcd : (int)gridDim.x) {
+  const int tn = v % nt_n, tm = by_xcd ? (v / nt_n) * kXcd + xcd : v / nt_n;
+  // this tile's 256 bias values wait in LDS behind the ring (read in the epilogue, many barriers later)
+  float *bias_lds = (float *)(ring + (size_t)kStages * kStageU4);
+  if (tid < kTile) bias_lds[tid] = bias ? bias[tn * kTile + tid] : 0.f;
 
   // fetch: this wave moves fragments f = 4*wave .. 4*wave+3 of a stage (f = op*16 + ks*8 + a)
   const int f_op = wave >> 2, f_ks = (wave >> 1) & 1, f_a0 = (wave & 1) * 4;
@@ -268,8 +294,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int bi = 0; bi < 4; ++bi)
 #pragma unroll
       for (int ai = 0; ai < 2; ++ai)
-        acc[ai][bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[ai]),
-                                                             __builtin_bit_cast(bf16x8, b[bi]),
+        acc[ai][bi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b[bi]),
+                                                             __builtin_bit_cast(bf16x8, a[ai]),
                                                              acc[ai][bi], 0, 0, 0);
   };
 
@@ -320,7 +346,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const i32x8 b8 = cat8(fb[0][bi], fb[1][bi]);
 #pragma unroll
         for (int ai = 0; ai < 2; ++ai)
-          acc[ai][bi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(cat8(ac[0][ai], ac[1][ai]), b8,
+          acc[ai][bi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b8, cat8(ac[0][ai], ac[1][ai]),
                                                                         acc[ai][bi], 0, 0, 0, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         lds_read1_async(fb[0][bi], base + b_off + bi * 1024);
@@ -345,34 +371,50 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // nothing may land in LDS any more
   __syncthreads();
 
-  // bias, activation, bf16, into the transposed tile: row = token, column = output channel
+  // bias, activation, bf16, into a row-major tile in LDS: row = token, column = output channel.
+  // The weights are the first MFMA operand, so a lane holds one token (column) and, per group
+  // of four accumulator registers, four consecutive output channels: 8-byte LDS writes.  Rows
+  // are 512 bytes with the 16-byte pieces of row m stored at piece ^ (m & 7): the 32 lanes of a
+  // half-wave (32 rows, same channels) then spread over all banks, and a row is still read back
+  // as one contiguous 512 bytes.
   char *tile = (char *)ring;
   const float alpha = alpha_p ? *alpha_p : 1.0f;
-  const int ncol = wn * 128 + (lane & 31);
+  int anchor = 0;   // opaque zero: keeps the address arithmetic below inside this tile's epilogue
+  asm volatile("" : "+v"(anchor));   // (hoisted out of the tile loop it would stay live through the main loop)
+  const int tok = wd * 64 + (lane & 31) + anchor;
 #pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    const float bv = bias ? bias[tn * kTile + ncol + 32 * b] : 0.f;
+  for (int b = 0; b < 4; ++b)
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int g = 0; g < 4; ++g) {
+      const int ch0 = wn * 128 + 32 * b + 8 * g + 4 * h;
+      const f32x4 bv = *(const f32x4 *)(bias_lds + ch0);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int mrow = wd * 64 + a * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-        float v = FP8 ? acc[a][b][r] * alpha + bv : acc[a][b][r] + bv;
-        if (gelu) v = gelu_erf(v);
-        *(uint16_t *)(tile + (size_t)mrow * kOutPitch + (ncol + 32 * b) * 2) = (uint16_t)pack_bf16(v, 0.f);
+      for (int a = 0; a < 2; ++a) {
+        const int mrow = tok + 32 * a;
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          v[i] = FP8 ? acc[a][b][4 * g + i] * alpha + bv[i] : acc[a][b][4 * g + i] + bv[i];
+          if (gelu) v[i] = gelu_erf(v[i]);
+        }
+        *(u32x2 *)(tile + (size_t)mrow * (kTile * 2) + (((ch0 >> 3) ^ (mrow & 7)) << 4) + ((ch0 & 7) << 1)) =
+            u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
       }
-  }
+    }
   __syncthreads();
   // 16-byte pieces along the rows: 32 per row, 8192 per tile, 16 per thread
   const int blk = (tn * kTile) / split, col0 = (tn * kTile) % split;   // a tile never straddles two blocks
   uint16_t *ob = out + (size_t)blk * M * split + col0;
 #pragma unroll 4
   for (int i = 0; i < 16; ++i) {
-    const int c = i * 512 + tid, mrow = c >> 5, piece = c & 31;
+    const int c = i * 512 + tid + anchor, mrow = c >> 5, piece = c & 31;
     const int64_t m = (int64_t)tm * kTile + mrow;
     if (m < M)
-      *(u32x4 *)(ob + (size_t)m * split + piece * 8) = *(const u32x4 *)(tile + (size_t)mrow * kOutPitch + piece * 16);
+      *(u32x4 *)(ob + (size_t)m * split + piece * 8) =
+          *(const u32x4 *)(tile + (size_t)mrow * (kTile * 2) + ((piece ^ (mrow & 7)) << 4));
   }
+  __syncthreads();   // the transposed tile has been read: the ring may be refilled
+  }   // tiles
 }
 
 // ---------------------------------------------------------------------------------------
@@ -419,14 +461,21 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
                          hipStream_t st, bool fp8 = false, float *fp8_state = nullptr) {
   if (K % 64 != 0 || Nout % kTile != 0 || split % kTile != 0 || Nout % split != 0) return LV_ERR_SHAPE;
   int rc;
-  const size_t lds = (size_t)kTile * kOutPitch > (size_t)kStages * kStageU4 * 16 ? (size_t)kTile * kOutPitch
-                                                                                   : (size_t)kStages * kStageU4 * 16;
+  // the ring; the epilogue's output tile (256 rows of 512 bytes) has the same size
+  static_assert((size_t)kTile * kTile * 2 <= (size_t)kStages * kStageU4 * 16, "output tile must fit the ring");
+  const size_t lds = (size_t)kStages * kStageU4 * 16 + kTile * sizeof(float);   // + a tile's bias values
   static std::atomic<uint64_t> lds_done[2];
   if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<false>, lds, lds_done[0]))) return rc;
   if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<true>, lds, lds_done[1]))) return rc;
   const int nt_n = Nout / kTile;
   const int64_t nt_m = w.Mp / kTile;
   if (nt_m * nt_n >= ((int64_t)1 << 31) || w.Mp >= ((int64_t)1 << 31)) return LV_ERR_SHAPE;
+  const int n_tiles = (int)(nt_m * nt_n);
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+    return LV_ERR_HIP;
+  const unsigned grid = (unsigned)(n_tiles < n_cu ? n_tiles : n_cu);
   if (fp8) {
     auto amax = [&](const uint16_t *t, int64_t n16, uint32_t *dst) {
       const unsigned g = (unsigned)(((n16 + 255) / 256) < 4096 ? ((n16 + 255) / 256) : 4096);
@@ -442,13 +491,13 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
     hipLaunchKernelGGL(k_fp8_scales, dim3(1), dim3(64), 0, st, w.fp8sc, fp8_state);
     quant(A, M, w.Mp, w.fp8sc + 2, w.apack);
     quant(W, Nout, Nout, w.fp8sc + 3, w.wpack);
-    hipLaunchKernelGGL(k_gemm_bt<true>, dim3((unsigned)(nt_m * nt_n)), dim3(512), lds, st, w.apack, w.wpack,
-                       M, K / 32, nt_n, bias, gelu, out, split, (const float *)(w.fp8sc + 4));
+    hipLaunchKernelGGL(k_gemm_bt<true>, dim3(grid), dim3(512), lds, st, w.apack, w.wpack,
+                       M, K / 32, nt_n, bias, gelu, out, split, (const float *)(w.fp8sc + 4), n_tiles);
   } else {
     if ((rc = launch_pack_rows(A, M, w.Mp, K, w.apack, st))) return rc;
     if ((rc = launch_pack_rows(W, Nout, Nout, K, w.wpack, st))) return rc;
-    hipLaunchKernelGGL(k_gemm_bt<false>, dim3((unsigned)(nt_m * nt_n)), dim3(512), lds, st, w.apack, w.wpack,
-                       M, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr);
+    hipLaunchKernelGGL(k_gemm_bt<false>, dim3(grid), dim3(512), lds, st, w.apack, w.wpack,
+                       M, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr, n_tiles);
   }
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;
