@@ -191,6 +191,10 @@ def sustained_peaks(B, torch):
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     res["copy_gbs"] = 2 * nbytes / timed(lambda: B.litevggt_probe_stream(src, dst, nbytes, sink), 10) / 1e9
     res["read_gbs"] = nbytes / timed(lambda: B.litevggt_probe_stream(src, None, nbytes, sink), 10) / 1e9
+    # 2 KB rows (one token at dim 1024) read in a random order: the merge step's access pattern
+    n_rows = nbytes // 2048
+    order = torch.randperm(n_rows, device="cuda", generator=g).to(torch.int32)
+    res["gather_2kb_rows_gbs"] = nbytes / timed(lambda: B.litevggt_probe_gather(src, 2048, order, n_rows, sink), 10) / 1e9
     res["note"] = ("litevggt_probe_mfma / litevggt_probe_stream: 2048 x 8 waves of independent 32x32 MFMAs on "
                    "operands loaded once; copy = bytes read + written of a 2 GiB buffer")
     return res

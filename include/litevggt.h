@@ -313,10 +313,17 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
  * litevggt_probe_stream: dst != NULL: copies `bytes` from src to dst (bytes read + bytes
  *   written = 2*bytes of HBM traffic); dst == NULL: reads src only.  16 B per lane and access.
  *     src, dst [device] 16-byte aligned, bytes a positive multiple of 16; sink [device] 4 bytes
+ * litevggt_probe_gather: reads n_rows whole rows of row_bytes each, row order[i] of src at step i,
+ *   one row per wave, eight in flight: what HBM gives the merge step's access pattern (token rows
+ *   gathered through an index), with nothing written.
+ *     src [device] 16-byte aligned; row_bytes a multiple of 16, at most 2^20; order [device]
+ *     n_rows int32 row numbers, every one inside src (the caller's responsibility); sink as above
  */
 double litevggt_probe_mfma_flop(int dtype, int iters);
 int litevggt_probe_mfma(int dtype, const void *operands, int iters, float *out, void *stream);
 int litevggt_probe_stream(const void *src, void *dst, size_t bytes, void *sink, void *stream);
+int litevggt_probe_gather(const void *src, size_t row_bytes, const int32_t *order, int64_t n_rows,
+                          void *sink, void *stream);
 
 #ifdef __cplusplus
 }

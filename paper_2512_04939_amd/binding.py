@@ -28,7 +28,7 @@ EXPORTS = ["litevggt_strerror", "litevggt_plan", "litevggt_attn_ws_bytes", "lite
            "litevggt_unmerge", "litevggt_frame_attn_ws_bytes", "litevggt_frame_attn",
            "litevggt_global_block_ws_bytes", "litevggt_global_block",
            "litevggt_layers_run", "litevggt_probe_mfma", "litevggt_probe_stream",
-           "litevggt_probe_mfma_flop"]
+           "litevggt_probe_mfma_flop", "litevggt_probe_gather"]
 
 
 class LiteVGGTError(RuntimeError):
@@ -115,6 +115,7 @@ def lib() -> C.CDLL:
         L.litevggt_probe_mfma.argtypes = [i32, vp, i32, vp, vp]
         L.litevggt_probe_stream.argtypes = [vp, vp, sz, vp, vp]
         L.litevggt_probe_mfma_flop.argtypes = [i32, i32]
+        L.litevggt_probe_gather.argtypes = [vp, sz, vp, i64, vp, vp]
         for name in EXPORTS[1:]:
             if not name.endswith("_ws_bytes"):
                 getattr(L, name).restype = i32
@@ -292,3 +293,8 @@ def litevggt_probe_mfma(dtype: int, operands, iters: int, out) -> None:
 def litevggt_probe_stream(src, dst, nbytes: int, sink) -> None:
     _check(lib().litevggt_probe_stream(_ptr(src), _ptr(dst), nbytes, _ptr(sink), _stream()),
            "litevggt_probe_stream")
+
+
+def litevggt_probe_gather(src, row_bytes: int, order, n_rows: int, sink) -> None:
+    _check(lib().litevggt_probe_gather(_ptr(src), row_bytes, _ptr(order), n_rows, _ptr(sink), _stream()),
+           "litevggt_probe_gather")

@@ -70,6 +70,30 @@ __global__ __launch_bounds__(256) void k_probe_stream(const u32x4 *__restrict__ 
   if (!dst && s == 0x9e3779b9u) *sink = s;   // practically never: the loads stay, no write traffic
 }
 
+// rows of `row16` 16-byte pieces read whole, one row per wave and step, in the order `order`
+// gives them (the access pattern of a merge: 2 KB token rows gathered through an index); eight
+// rows in flight per wave, nothing written
+__global__ __launch_bounds__(256) void k_probe_gather(const u32x4 *__restrict__ src, int row16,
+                                                      const int32_t *__restrict__ order, int64_t n_rows,
+                                                      uint32_t *__restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = (int64_t)gridDim.x * 4;
+  uint32_t s = 0;
+  for (int64_t r0 = wave * 8; r0 < n_rows; r0 += n_waves * 8) {
+    int32_t idx[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) idx[u] = r0 + u < n_rows ? order[r0 + u] : -1;
+    for (int c = lane; c < row16; c += 64) {
+      u32x4 w[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) w[u] = idx[u] >= 0 ? src[(size_t)idx[u] * row16 + c] : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += w[u].x ^ w[u].y ^ w[u].z ^ w[u].w;
+    }
+  }
+  if (s == 0x9e3779b9u) *sink = s;   // practically never: the loads stay, no write traffic
+}
+
 }  // namespace lv
 
 using namespace lv;
@@ -99,6 +123,18 @@ extern "C" int litevggt_probe_stream(const void *src, void *dst, size_t bytes, v
   if (bytes == 0 || bytes % 16 != 0 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return LV_ERR_SHAPE;
   hipLaunchKernelGGL(k_probe_stream, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const u32x4 *)src,
                      (u32x4 *)dst, bytes / 16, (uint32_t *)sink);
+  LV_HIP_CHECK_LAUNCH();
+  return LV_OK;
+}
+
+extern "C" int litevggt_probe_gather(const void *src, size_t row_bytes, const int32_t *order, int64_t n_rows,
+                                     void *sink, void *stream) {
+  if (!src || !order || !sink) return LV_ERR_NULL;
+  if (n_rows < 1 || row_bytes == 0 || row_bytes % 16 != 0 || row_bytes > (1u << 20) || ((uintptr_t)src & 15))
+    return LV_ERR_SHAPE;
+  const int64_t groups = (n_rows + 31) / 32;
+  hipLaunchKernelGGL(k_probe_gather, dim3((unsigned)(groups < 16384 ? groups : 16384)), dim3(256), 0,
+                     (hipStream_t)stream, (const u32x4 *)src, (int)(row_bytes / 16), order, n_rows, (uint32_t *)sink);
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;
 }

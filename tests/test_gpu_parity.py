@@ -1115,6 +1115,11 @@ def test_probes(B):
     assert torch.equal(src, dst)
     with pytest.raises(B.LiteVGGTError):
         B.litevggt_probe_stream(src, dst, n - 1, sink)
+    order = torch.randperm(n // 2048, device="cuda").to(torch.int32)
+    B.litevggt_probe_gather(src, 2048, order, n // 2048, sink)   # reads only; rows stay inside src
+    torch.cuda.synchronize()
+    with pytest.raises(B.LiteVGGTError):
+        B.litevggt_probe_gather(src, 2050, order, n // 2048, sink)
     out = torch.zeros(2048 * 512, device="cuda")
     ones = torch.ones(65536, dtype=torch.bfloat16, device="cuda")
     B.litevggt_probe_mfma(B.ATTN_BF16, ones, 3, out)
