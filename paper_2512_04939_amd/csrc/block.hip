@@ -135,8 +135,9 @@ __global__ __launch_bounds__(256) void k_amax_bf16(const u32x4 *__restrict__ x, 
 
 // One wave: picks the scales of a layer.  state == NULL: both from the tensors' own amax.
 // Otherwise the input's scale comes from the largest of the recorded amaxes (1 while nothing
-// has been recorded), and the input's own amax is recorded afterwards.
-__global__ __launch_bounds__(64) void k_fp8_scales(uint32_t *__restrict__ sc, float *__restrict__ state) {
+// has been recorded); the input's own amax is recorded by k_fp8_record once the quantisation
+// pass, which takes it on the way, has run.
+__global__ __launch_bounds__(64) void k_fp8_scales(uint32_t *__restrict__ sc, const float *__restrict__ state) {
   const int lane = threadIdx.x;
   uint32_t src = sc[0];
   if (state) {
@@ -148,11 +149,15 @@ __global__ __launch_bounds__(64) void k_fp8_scales(uint32_t *__restrict__ sc, fl
     sc[2] = __float_as_uint(ia);
     sc[3] = __float_as_uint(iw);
     sc[4] = __float_as_uint((1.0f / ia) * (1.0f / iw));
-    if (state) {
-      uint32_t *step = (uint32_t *)(state + LV_FP8_HISTORY);
-      state[*step % LV_FP8_HISTORY] = __uint_as_float(sc[0]);
-      *step += 1;
-    }
+  }
+}
+
+// delayed scaling: the amax of the input just quantised goes into the layer's history
+__global__ void k_fp8_record(const uint32_t *__restrict__ sc, float *__restrict__ state) {
+  if (threadIdx.x == 0) {
+    uint32_t *step = (uint32_t *)(state + LV_FP8_HISTORY);
+    state[*step % LV_FP8_HISTORY] = __uint_as_float(sc[0]);
+    *step += 1;
   }
 }
 
@@ -164,9 +169,12 @@ __global__ __launch_bounds__(64) void k_fp8_scales(uint32_t *__restrict__ sc, fl
 // the tiled kernel fetches and reads both types the same way.  Rows n..n_pad-1 are zero.
 // A wave writes whole units (1 KB stores) and takes 4 consecutive units of its 32 rows (256
 // bytes of each bf16 row).  Grid: (row tiles, ceil(units / 16)).
+// amax != NULL: the largest |x| read is reduced into *amax on the way (delayed scaling needs
+// it only afterwards, for the history, so no pass of its own).
 __global__ __launch_bounds__(256) void k_quant_pack_fp8(const uint16_t *__restrict__ x, int n,
                                                         int K, const uint32_t *__restrict__ inv,
-                                                        u32x4 *__restrict__ packed) {
+                                                        u32x4 *__restrict__ packed,
+                                                        uint32_t *__restrict__ amax) {
   const int KS = K >> 5;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = lane >> 5, rr = lane & 31;
   const int t = blockIdx.x, j = t * 32 + rr;
@@ -188,6 +196,16 @@ __global__ __launch_bounds__(256) void k_quant_pack_fp8(const uint16_t *__restri
       const u32x2 lo = quant8(src[u][0], r), hi = quant8(src[u][1], r);
       packed[((size_t)t * KS + s0 + u) * 64 + lane] = u32x4{lo.x, lo.y, hi.x, hi.y};
     }
+  if (amax) {   // rows and units outside the matrix were read as zeros
+    float m = 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) m = fmaxf(m, fmaxf(absmax8(src[u][0]), absmax8(src[u][1])));
+    m = wave_max(m);
+    // one word for 10^5 waves: only a wave that would raise it sends an atomic (a stale read only
+    // sends one too many)
+    if (lane == 0 && __float_as_uint(m) > __hip_atomic_load(amax, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+      atomicMax(amax, __float_as_uint(m));
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -195,8 +213,8 @@ __global__ __launch_bounds__(256) void k_quant_pack_fp8(const uint16_t *__restri
 // accumulation.  Same machinery as the similarity kernel of the matching step: 256 x 256
 // output tiles, both operands pre-packed fragment-major, fetched straight into a 4-stage LDS
 // ring (2 k-steps per stage, 3 stages ahead), fragments read by hand one k-step ahead, 8 waves
-// of 64 rows x 128 columns.  The finished tile is converted to bf16, transposed through LDS
-// (the ring is free by then) and written in 16-byte pieces along the rows.
+// of 64 rows x 128 columns.  The finished tile is converted to bf16 into LDS (the ring is free
+// by then) and written in 16-byte pieces along the rows.
 // `split`: the output is Nout / split row-major blocks of [M, split] one after the other
 // (split = Nout: one plain matrix; split = C for the fused q|k|v projection).
 // FP8: the same ring and the same byte traffic per stage, but a stage (two 1 KB units per
@@ -481,16 +499,19 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
       const unsigned g = (unsigned)(((n16 + 255) / 256) < 4096 ? ((n16 + 255) / 256) : 4096);
       hipLaunchKernelGGL(k_amax_bf16, dim3(g), dim3(256), 0, st, (const u32x4 *)t, n16, dst);
     };
-    auto quant = [&](const uint16_t *t, int64_t n, int64_t n_pad, const uint32_t *inv, u32x4 *dst) {
+    auto quant = [&](const uint16_t *t, int64_t n, int64_t n_pad, const uint32_t *inv, u32x4 *dst, uint32_t *amax_out) {
       hipLaunchKernelGGL(k_quant_pack_fp8, dim3((unsigned)(n_pad / 32), (unsigned)((K / 32 + 15) / 16)), dim3(256), 0, st, t, (int)n,
-                         K, inv, dst);
+                         K, inv, dst, amax_out);
     };
+    // current scaling: the input's amax first, then its scale; delayed scaling: the scale comes
+    // from the history, the quantisation pass takes the amax on the way and it is recorded after
     hipLaunchKernelGGL(k_fp8_zero, dim3(1), dim3(64), 0, st, w.fp8sc);
-    amax(A, M * (K / 8), w.fp8sc);
+    if (!fp8_state) amax(A, M * (K / 8), w.fp8sc);
     amax(W, (int64_t)Nout * (K / 8), w.fp8sc + 1);
-    hipLaunchKernelGGL(k_fp8_scales, dim3(1), dim3(64), 0, st, w.fp8sc, fp8_state);
-    quant(A, M, w.Mp, w.fp8sc + 2, w.apack);
-    quant(W, Nout, Nout, w.fp8sc + 3, w.wpack);
+    hipLaunchKernelGGL(k_fp8_scales, dim3(1), dim3(64), 0, st, w.fp8sc, (const float *)fp8_state);
+    quant(A, M, w.Mp, w.fp8sc + 2, w.apack, fp8_state ? w.fp8sc : (uint32_t *)nullptr);
+    quant(W, Nout, Nout, w.fp8sc + 3, w.wpack, (uint32_t *)nullptr);
+    if (fp8_state) hipLaunchKernelGGL(k_fp8_record, dim3(1), dim3(64), 0, st, w.fp8sc, fp8_state);
     hipLaunchKernelGGL(k_gemm_bt<true>, dim3(grid), dim3(512), lds, st, w.apack, w.wpack,
                        M, K / 32, nt_n, bias, gelu, out, split, (const float *)(w.fp8sc + 4), n_tiles);
   } else {
