@@ -179,3 +179,51 @@ def test_full_size_steps_against_sampled_oracle(name, over):
         qk = O.round_bf16(O.qk_normalize(xh))
         want_u = O.attention(qk, qk, xh, rows=qrows).reshape(len(qrows), 64)
         assert max_rel_err(_f64(yub[qrows][:, cols]), want_u) <= BF16_TOL
+
+
+def test_full_size_block_against_sampled_oracle():
+    """The transformer block around the attention core at the benchmark's merged length
+    (M = 143,232 rows, dim 1024, 16 heads): the whole block runs on the GPU, the oracle follows
+    the same sequence of stored intermediates for a sample of rows (LayerNorm and the k, v
+    projections for every row, since sampled queries attend over all of them; everything after
+    the attention for the sampled rows only)."""
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from helpers import f32_to_dev_bf16
+    from paper_2512_04939_amd import binding as B
+    wl = synth.workload("f1000")
+    po, ph = oracle_params(wl), hip_params(wl)
+    pl = B.litevggt_plan(ph)
+    M, C, heads = pl.M, wl.dim, wl.heads
+    print(f"block at M={M}", flush=True)
+    gen = synth.Generator(wl)
+    zb = gen.tokens(range((M + wl.tokens_per_frame - 1) // wl.tokens_per_frame), threads=16)[:M]   # bf16 bit patterns
+    z = _f64(zb)
+    w = synth.block_weights(C, seed=wl.seed)
+    tens = {k: (f32_to_dev_bf16(v) if v.ndim == 2 else torch.from_numpy(v).cuda()) for k, v in w.items()}
+    bw = B.block_weights(tens)
+    delta = torch.empty(M, C, dtype=torch.bfloat16, device="cuda")
+    ws = B.alloc_ws(B.litevggt_global_block_ws_bytes(ph, M))
+    B.litevggt_global_block(ph, M, torch.from_numpy(zb.view(np.int16)).cuda().view(torch.bfloat16), bw, delta, ws)
+    torch.cuda.synchronize()
+    got = _f64(_host_bits(delta))
+    assert np.all(np.isfinite(got))
+
+    st = lambda a: O.round_bf16(a)
+    w64 = {k: v.astype(np.float64) for k, v in w.items()}
+    rows = np.sort(np.random.default_rng(77).choice(M, size=8, replace=False))
+    h = st(O.layer_norm(z, w64["ln1_g"], w64["ln1_b"]))
+    wq, wk, wv = (w64["w_qkv"][i * C:(i + 1) * C] for i in range(3))
+    bq, bk, bv = (w64["b_qkv"][i * C:(i + 1) * C] for i in range(3))
+    k = st(O.linear(h, wk, bk)).reshape(M, heads, 64)
+    v = st(O.linear(h, wv, bv)).reshape(M, heads, 64)
+    q = np.zeros((M, heads, 64))
+    q[rows] = st(O.linear(h[rows], wq, bq)).reshape(len(rows), heads, 64)
+    qn, kn = st(O.qk_normalize(q)), st(O.qk_normalize(k))
+    a = st(O.attention(qn, kn, v, rows=rows).reshape(len(rows), C))
+    u1 = st(O.linear(a, w64["w_o"], w64["b_o"]))
+    h2 = st(O.layer_norm(z[rows] + u1, w64["ln2_g"], w64["ln2_b"]))
+    h3 = st(O.gelu(O.linear(h2, w64["w_1"], w64["b_1"])))
+    u2 = st(O.linear(h3, w64["w_2"], w64["b_2"]))
+    want = st(u1 + u2)
+    assert max_rel_err(got[rows], want) <= BF16_TOL
