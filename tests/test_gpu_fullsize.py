@@ -227,3 +227,28 @@ def test_full_size_block_against_sampled_oracle():
     u2 = st(O.linear(h3, w64["w_2"], w64["b_2"]))
     want = st(u1 + u2)
     assert max_rel_err(got[rows], want) <= BF16_TOL
+
+
+def test_full_size_frame_attention_against_oracle_on_sampled_frames():
+    """Frame attention over all 1000 frames (16000 independent (frame, head) sequences of 1374
+    tokens) with the residual fused; the oracle recomputes three whole frames."""
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2512_04939_amd import binding as B
+    wl = synth.workload("f1000")
+    po, ph = oracle_params(wl, frame_attn=True), hip_params(wl, frame_attn=1)
+    T, C, heads, N = wl.tokens_per_frame, wl.dim, wl.heads, wl.n_tokens
+    gen = synth.Generator(wl)
+    bits = gen.tokens(threads=16)
+    x = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    out = torch.empty_like(x)
+    ws = B.alloc_ws(B.litevggt_frame_attn_ws_bytes(ph))
+    B.litevggt_frame_attn(ph, x, x, x, x, out, ws)
+    torch.cuda.synchronize()
+    for f in (0, 517, wl.frames - 1):
+        rows = slice(f * T, (f + 1) * T)
+        xf = _f64(bits[rows]).reshape(T, heads, 64)
+        qk = O.round_bf16(O.qk_normalize(xf))
+        want = xf.reshape(T, C) + O.attention(qk, qk, xf).reshape(T, C)
+        got = _f64(_host_bits(out[rows]))
+        assert max_rel_err(got, want) <= BF16_TOL, f"frame {f}"
