@@ -1,5 +1,6 @@
 """Parity at the benchmark configurations' full sizes (32, 100, 500 and 1000 frames of 37 x 37
-patches, dim 1024; 100 frames at merge ratios 0.5, 0.75, 0.9), in the launch configuration
+patches, dim 1024; 100 frames at merge ratios 0.5, 0.75, 0.9; the paper's own shape, 1000 frames
+of 28 x 37 patches under its partition rule), in the launch configuration
 bench.py times: every step runs on the whole sequence, the oracle checks sampled outputs it can
 compute one by one, plus structural properties that hold at any size.  At 100 frames the
 unmerged attention (the speedup baseline) is sampled as well."""
@@ -27,7 +28,7 @@ def _host_bits(t) -> np.ndarray:
 
 
 CASES = [("f32", {}), ("f100", {"merge_ratio": 0.5}), ("f100", {"merge_ratio": 0.75}), ("f100", {}),
-         ("f500", {}), ("f1000", {})]
+         ("f500", {}), ("f1000", {}), ("paper1000", {})]
 
 
 @pytest.mark.parametrize("name,over", CASES, ids=[n + "".join(f"-r{v}" for v in o.values()) for n, o in CASES])
