@@ -203,8 +203,11 @@ int litevggt_merge(const litevggt_params *p, const void *x, const litevggt_index
  *   q,k,v [device] [n_tokens, heads, 64] bf16 (row stride dim); o likewise, out.
  *   n_tokens = M for the merged path, N for the unmerged baseline.
  * With qk_norm the scores use the per-head RMS-normalised q and k (see litevggt_params);
- * v is used as given.  Scores are exponentiated as exp2(s*c - max*c) with one fused
- * multiply-add: accurate while |score * softmax_scale| stays below about 2^16.
+ * v is used as given.  The softmax reference is the largest score unit-RMS heads can reach
+ * (qk_norm), or, for q and k as given, the bound softmax_scale * max|q| * max|k| of each 64
+ * queries, with a running row maximum for the query blocks where that bound lies more than 60
+ * binades above some row's scores.  Exponents are always taken from the difference to the
+ * reference, so scores of any finite size give finite weights.
  * attn_dtype LV_ATTN_FP8_E4M3 quantises q,k,v per tensor (scale = amax/448, amax taken in
  * this call) and the softmax weights to e4m3 for the MFMAs; accumulation and softmax stay
  * fp32.  Without qk_norm the weights are rounded relative to a running row maximum and
