@@ -169,6 +169,21 @@ int litevggt_importance(const litevggt_params *p, const void *images, const void
                         float *grad_cache, int recompute_grad, float *score,
                         void *ws, size_t ws_bytes, void *stream);
 
+/* litevggt_importance for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and the same results, but the variance map that litevggt_importance keeps in `ws` lives
+ * in a device array inside the library (LV_STATIC_SCORE_MAX fp32 = 8 MiB, held on every GPU the
+ * library runs on until the process ends).  The call allocates and frees nothing.
+ *   frames * grid_h * grid_w > LV_STATIC_SCORE_MAX -> LV_ERR_WORKSPACE, nothing enqueued.
+ *   All calls on one GPU share that array: calls that overlap on one GPU (different streams,
+ *   or threads) race; calls on one stream are ordered.  Nothing in it has to start at zero
+ *   (every element that is read was written earlier in the same call).
+ * Other arguments as for litevggt_importance.
+ */
+#define LV_STATIC_SCORE_MAX (2u * 1024u * 1024u)
+int litevggt_importance_static(const litevggt_params *p, const void *images, const void *x,
+                               float *grad_cache, int recompute_grad, float *score, void *stream);
+
 /* Step 2, Sec. 3.4 "GA Token Partitioning".  Special tokens: PROTECTED.  Frame 0:
  * every patch token DST.  Other frames: in every cell x cell block of the grid the
  * lowest-scoring token is DST (ties: lowest index); of the remaining patch tokens

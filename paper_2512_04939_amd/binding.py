@@ -23,7 +23,9 @@ FP8_HISTORY = 80
 FP8_STATE_BYTES = 4 * (FP8_HISTORY + 2) * 4
 ROLE_PROTECTED, ROLE_DST, ROLE_SRC = 0, 1, 2
 
+STATIC_SCORE_MAX = 2 * 1024 * 1024
 EXPORTS = ["litevggt_strerror", "litevggt_plan", "litevggt_attn_ws_bytes", "litevggt_importance",
+           "litevggt_importance_static",
            "litevggt_select_anchors", "litevggt_match", "litevggt_merge", "litevggt_global_attn",
            "litevggt_unmerge", "litevggt_frame_attn_ws_bytes", "litevggt_frame_attn",
            "litevggt_global_block_ws_bytes", "litevggt_global_block",
@@ -99,6 +101,7 @@ def lib() -> C.CDLL:
         L.litevggt_attn_ws_bytes.restype = sz
         L.litevggt_attn_ws_bytes.argtypes = [PP, i64]
         L.litevggt_importance.argtypes = [PP, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.litevggt_importance_static.argtypes = [PP, vp, vp, vp, i32, vp, vp]
         L.litevggt_select_anchors.argtypes = [PP, vp, C.POINTER(Index), vp]
         L.litevggt_match.argtypes = [PP, vp, C.POINTER(Index), vp, vp, sz, vp]
         L.litevggt_merge.argtypes = [PP, vp, C.POINTER(Index), vp, vp]
@@ -200,6 +203,12 @@ def litevggt_importance(p: Params, images, x, grad_cache, recompute_grad: bool, 
     _check(lib().litevggt_importance(C.byref(p), _ptr(images), _ptr(x), _ptr(grad_cache),
                                      1 if recompute_grad else 0, _ptr(score), wp, wn, _stream()),
            "litevggt_importance")
+
+
+def litevggt_importance_static(p: Params, images, x, grad_cache, recompute_grad: bool, score) -> None:
+    _check(lib().litevggt_importance_static(C.byref(p), _ptr(images), _ptr(x), _ptr(grad_cache),
+                                            1 if recompute_grad else 0, _ptr(score), _stream()),
+           "litevggt_importance_static")
 
 
 def litevggt_select_anchors(p: Params, score, index: IndexBuffers) -> None:

@@ -169,6 +169,21 @@ int litevggt_importance(const litevggt_params *p, const void *images, const void
   return launch_ga_fuse(grad_cache, psi_v, d, p->alpha, p->beta, score, st);
 }
 
+int litevggt_importance_static(const litevggt_params *p, const void *images, const void *x,
+                               float *grad_cache, int recompute_grad, float *score, void *stream) {
+  Dims d;
+  int rc = check_params(p, &d);
+  if (rc) return rc;
+  if (p->anchor_policy == LV_POLICY_GA) {
+    if (!x || !grad_cache || !score || (recompute_grad && !images)) return LV_ERR_NULL;
+    if ((size_t)d.F * d.P > kStaticScoreFloats) return LV_ERR_WORKSPACE;
+  }
+  float *psi_v = nullptr;
+  if ((rc = static_importance_scratch(&psi_v))) return rc;
+  return litevggt_importance(p, images, x, grad_cache, recompute_grad, score, psi_v,
+                             kStaticScoreFloats * sizeof(float), stream);
+}
+
 int litevggt_select_anchors(const litevggt_params *p, const float *score, litevggt_index *index,
                             void *stream) {
   Dims d;

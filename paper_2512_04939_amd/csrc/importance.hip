@@ -265,3 +265,32 @@ int launch_naive_score(const Dims &d, int policy, uint32_t seed, float *score, h
 }
 
 }  // namespace lv
+
+// ---------------------------------------------------------------------------------
+// Scratch for callers that cannot hand over a workspace (litevggt_importance_static): the
+// variance map of one call lives in this file-scope device array.  Every GPU holds its own
+// copy at its own address, so the address is looked up once per device, with that device
+// current, and host code only ever uses the looked-up pointer (the array's name is a host-side
+// stand-in, not a device address).
+// ---------------------------------------------------------------------------------
+namespace lv {
+
+static __device__ __align__(256) float g_static_psi_v[kStaticScoreFloats];
+
+int static_importance_scratch(float **out) {
+  static std::atomic<float *> per_device[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return LV_ERR_HIP;
+  if (dev < 0 || dev >= 64) return LV_ERR_HIP;
+  float *p = per_device[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void *sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(g_static_psi_v)) != hipSuccess || !sym) return LV_ERR_HIP;
+    p = (float *)sym;
+    per_device[dev].store(p, std::memory_order_release);   // the same value from every thread
+  }
+  *out = p;
+  return LV_OK;
+}
+
+}  // namespace lv

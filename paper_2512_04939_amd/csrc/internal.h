@@ -40,6 +40,11 @@ int launch_var_map(const uint16_t *x, const Dims &d, int pool, float *psi_v, hip
 int launch_ga_fuse(const float *psi_g, const float *psi_v, const Dims &d, float alpha, float beta,
                    float *score, hipStream_t st);
 
+// Capacity of the library-owned variance-map scratch of litevggt_importance_static, and the
+// device address of that scratch on the current device (looked up once per device).
+constexpr size_t kStaticScoreFloats = LV_STATIC_SCORE_MAX;
+int static_importance_scratch(float **out);
+
 // select.hip
 int launch_select(const float *score, const Dims &d, const litevggt_plan_t &pl,
                   const litevggt_index &ix, hipStream_t st);

@@ -83,6 +83,11 @@ def test_entry_points_validate_before_launch():
     assert lib.litevggt_importance(C.byref(p), fake, fake, fake, 1, fake, None, 0, None) == -4
     assert lib.litevggt_importance(C.byref(p), fake, fake, fake, 1, fake, C.c_void_p(0x1001),
                                    1 << 30, None) == -4
+    # the variant with library-owned scratch: NULL and over-size checks come before any HIP call
+    assert lib.litevggt_importance_static(C.byref(p), None, None, None, 1, None, None) == -1
+    big = B.make_params(2000, 37, 37, 1024, 16)
+    assert 2000 * 37 * 37 > B.STATIC_SCORE_MAX
+    assert lib.litevggt_importance_static(C.byref(big), fake, fake, fake, 1, fake, None) == -4
     assert lib.litevggt_select_anchors(C.byref(p), fake, C.byref(ix), None) == -1
     assert lib.litevggt_match(C.byref(p), fake, C.byref(ix), None, fake, 1 << 30, None) == -1
     assert lib.litevggt_merge(C.byref(p), fake, C.byref(ix), fake, None) == -1
