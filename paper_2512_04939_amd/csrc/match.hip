@@ -115,7 +115,7 @@ constexpr int kGStages = 4;          // LDS ring depth
 constexpr int kGStageU4 = 2 * 2 * 8 * 64;   // u32x4 per stage: [src|dst][2 k-steps][8 fragments][64 lanes]
 constexpr int kTeamSpin = 512;       // polls of the team counter before a workgroup goes on alone
 constexpr int kInvBufs = 8;          // per-wave LDS buffers of 64 inverse dst norms
-constexpr int kGLanes = 4;           // dst tiles are dealt to this many workgroups per src tile
+constexpr int kGLanes = 4;           // dst tiles are dealt to this many workgroups per src tile (<= kMaxSweeps of k_match_finish)
 
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_match_sim(
     const u32x4 *__restrict__ srcp, const u32x4 *__restrict__ dstp, const float *__restrict__ invd,
@@ -373,10 +373,16 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }   // super-rows
 }
 
-// Final decision per src row (one wave each): merge the partial results of the sweeps; rows
-// whose two best fp32 similarities are
-// closer than kRescoreGap recompute both in float64 and decide on the fp32-rounded values,
-// lowest token index on a tie.
+// Final decision per src row (one wave each).  Every sweep hands over its two best candidates
+// by fp32 similarity (up to kMaxSweeps * 2 per row).  If the runner-up is closer than
+// kRescoreGap to the best, every candidate inside that gap is recomputed in float64 and the
+// decision is taken on those values rounded to fp32, lowest token index on a tie: the rule the
+// fp32 accumulation order cannot disturb.  A row with more near-equal candidates than one
+// sweep's two best can still lose its true best inside a sweep; what it picks instead is within
+// twice the fp32 accumulation error of it (C / 16 additions of exact 16-product sums).
+constexpr int kMaxSweeps = 4;
+static_assert(kGLanes <= kMaxSweeps, "k_match_finish reads every sweep's candidates");
+
 __global__ __launch_bounds__(256) void k_match_finish(
     const uint16_t *__restrict__ x, const int32_t *__restrict__ src_idx,
     const int32_t *__restrict__ dst_idx, const float *__restrict__ inv,
@@ -384,9 +390,17 @@ __global__ __launch_bounds__(256) void k_match_finish(
     int32_t *__restrict__ anchor_of, int32_t *slot_of, float *__restrict__ best_sim) {
   const int lane = threadIdx.x & 63, wpb = blockDim.x >> 6, nch = C >> 3;
   for (int p = blockIdx.x * wpb + (threadIdx.x >> 6); p < n_src; p += gridDim.x * wpb) {
-    Top2 t = top2p[p];
-    for (int l = 1; l < n_lanes; ++l) {    // the other sweeps' candidates for this row
-      const Top2 o = top2p[(size_t)l * n_src_pad + p];
+    float cv[2 * kMaxSweeps];
+    int ci[2 * kMaxSweeps];
+    Top2 t = Top2{-INFINITY, -1, -INFINITY, -1};
+#pragma unroll
+    for (int l = 0; l < kMaxSweeps; ++l) {    // every sweep's candidates for this row
+      Top2 o = Top2{-INFINITY, -1, -INFINITY, -1};
+      if (l < n_lanes) o = top2p[(size_t)l * n_src_pad + p];
+      cv[2 * l] = o.v1;
+      ci[2 * l] = o.i1;
+      cv[2 * l + 1] = o.v2;
+      ci[2 * l + 1] = o.i2;
       top2_insert_any(t, o.v1, o.i1);
       top2_insert_any(t, o.v2, o.i2);
     }
@@ -395,40 +409,48 @@ __global__ __launch_bounds__(256) void k_match_finish(
     int choose = t.i1 < 0 ? 0 : t.i1;
     float sim = t.i1 < 0 ? 0.f : t.v1 * invs;
     if (t.i1 >= 0 && t.i2 >= 0 && (t.v1 - t.v2) * invs < kRescoreGap) {
-      const int d1 = dst_idx[t.i1], d2 = dst_idx[t.i2];
-      double ss = 0, n1 = 0, n2 = 0, p1 = 0, p2 = 0;
+      double ss = 0;
       for (int ch = lane; ch < nch; ch += 64) {
-        const u32x4 ws = ((const u32x4 *)(x + (size_t)s * C))[ch];
-        const u32x4 w1 = ((const u32x4 *)(x + (size_t)d1 * C))[ch];
-        const u32x4 w2 = ((const u32x4 *)(x + (size_t)d2 * C))[ch];
-        const uint32_t us[4] = {ws.x, ws.y, ws.z, ws.w}, u1[4] = {w1.x, w1.y, w1.z, w1.w},
-                       u2[4] = {w2.x, w2.y, w2.z, w2.w};
+        const u32x4 w = ((const u32x4 *)(x + (size_t)s * C))[ch];
+        const uint32_t us[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const double sl = bf16_lo(us[k]), sh = bf16_hi(us[k]);
-          const double al = bf16_lo(u1[k]), ah = bf16_hi(u1[k]);
-          const double bl = bf16_lo(u2[k]), bh = bf16_hi(u2[k]);
+        for (int q = 0; q < 4; ++q) {
+          const double sl = bf16_lo(us[q]), sh = bf16_hi(us[q]);
           ss += sl * sl + sh * sh;
-          n1 += al * al + ah * ah;
-          n2 += bl * bl + bh * bh;
-          p1 += sl * al + sh * ah;
-          p2 += sl * bl + sh * bh;
         }
       }
       ss = wave_sum(ss);
-      n1 = wave_sum(n1);
-      n2 = wave_sum(n2);
-      p1 = wave_sum(p1);
-      p2 = wave_sum(p2);
       const double is = 1.0 / fmax(sqrt(ss), 1e-12);
-      const float s1 = (float)(p1 * is * (1.0 / fmax(sqrt(n1), 1e-12)));
-      const float s2 = (float)(p2 * is * (1.0 / fmax(sqrt(n2), 1e-12)));
-      if (s2 > s1 || (s2 == s1 && d2 < d1)) {
-        choose = t.i2;
-        sim = s2;
-      } else {
-        sim = s1;
+      float bs = -INFINITY;
+      int bd = 0x7fffffff, bi = choose;
+#pragma unroll
+      for (int c = 0; c < 2 * kMaxSweeps; ++c) {
+        if (ci[c] < 0 || !((t.v1 - cv[c]) * invs < kRescoreGap)) continue;   // wave-uniform
+        const int d = dst_idx[ci[c]];
+        double nn = 0, pp = 0;
+        for (int ch = lane; ch < nch; ch += 64) {
+          const u32x4 wd = ((const u32x4 *)(x + (size_t)d * C))[ch];
+          const u32x4 w = ((const u32x4 *)(x + (size_t)s * C))[ch];   // the src row again: a cache hit
+          const uint32_t us[4] = {w.x, w.y, w.z, w.w}, ud[4] = {wd.x, wd.y, wd.z, wd.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const double sl = bf16_lo(us[q]), sh = bf16_hi(us[q]);
+            const double al = bf16_lo(ud[q]), ah = bf16_hi(ud[q]);
+            nn += al * al + ah * ah;
+            pp += sl * al + sh * ah;
+          }
+        }
+        nn = wave_sum(nn);
+        pp = wave_sum(pp);
+        const float sc = (float)(pp * is * (1.0 / fmax(sqrt(nn), 1e-12)));
+        if (sc > bs || (sc == bs && d < bd)) {
+          bs = sc;
+          bd = d;
+          bi = ci[c];
+        }
       }
+      choose = bi;
+      sim = bs;
     }
     if (lane == 0) {
       const int a = dst_idx[choose];

@@ -185,12 +185,14 @@ def _check_match(B, case_like):
     gap = mt["best"] - mt["second"]
     undocumented = [int(i) for i in bad if not gap[i] < NEAR_TIE]
     assert not undocumented, f"anchor mismatches outside near-ties: {undocumented[:10]}"
-    # a near-tie loser must still be the runner-up
+    # what a near-tie loser picked is itself within 1e-6 of the oracle's choice (the runner-up, or,
+    # among several near-equal candidates, another one of them; the oracle decides on fp32-rounded
+    # values with the lowest index on ties, so the other candidate may even be closer in float64)
     for i in bad:
         d = got[src[i]]
         s64 = float(np.dot(case_like["xf"][src[i]].astype(np.float64), case_like["xf"][d].astype(np.float64))
                     * O.inv_norms(case_like["xf"][[src[i]]])[0] * O.inv_norms(case_like["xf"][[d]])[0])
-        assert abs(s64 - mt["second"][i]) < 1e-9
+        assert abs(mt["best"][i] - s64) < NEAR_TIE
     if len(src):
         assert np.abs(best.cpu().numpy()[:len(src)] - mt["best"]).max() < 5e-6
     # the index built on the GPU from its own anchors is internally consistent and, where the
@@ -238,6 +240,43 @@ def test_match_exact_duplicates_across_dst_tiles(B):
     assert tied.sum() > 100
     case_like = dict(pl=pl, idx=idx, mt=mt, ph=ph, xf=xf, x_dev=to_dev_bf16(bits))
     assert _check_match(B, case_like) == 0
+
+
+def test_match_many_near_equal_candidates(B):
+    """Several dst rows that differ from a src row by single bf16 steps in a few channels, so
+    that three to six candidates lie within the fp32 accumulation error of each other, placed in
+    one dst tile and across tiles and sweeps (what later layers of a stack produce: rows of one
+    merge group converge).  Every disagreement with the oracle must be a near-tie in the
+    oracle's own terms (its two best closer than 1e-6) and lose less than 1e-6 of similarity."""
+    import torch
+    wl = small_workload(frames=12, grid=24, dim=1024, heads=16, r=0.25, seed=41)
+    bits, xf, im = stored_inputs(wl)
+    po, ph = oracle_params(wl), hip_params(wl)
+    pl = B.litevggt_plan(ph)
+    sel = O.select_anchors(O.importance(im, xf, po)[0].astype(np.float32), po)
+    dst, src = sel["dst_idx"], sel["src_idx"]
+    assert len(dst) > 6 * 256
+    rng = np.random.default_rng(4)
+    b = bits.copy()
+    for n, s_tok in enumerate(rng.choice(src, size=200, replace=False)):
+        k = 3 + n % 4                                          # near-copies of this src row
+        if n % 2:                                              # in one 256-row dst tile
+            t0 = int(rng.integers(0, len(dst) // 256)) * 256
+            where = dst[t0 + rng.choice(256, size=k, replace=False)]
+        else:                                                  # anywhere: other tiles, other sweeps
+            where = rng.choice(dst, size=k, replace=False)
+        for d_tok in where:
+            row = b[s_tok].copy()
+            ch = rng.choice(wl.dim, size=int(rng.integers(1, 4)), replace=False)
+            row[ch] ^= 1                                       # one bf16 step in 1-3 channels
+            b[d_tok] = row
+    xf2 = synth.bf16_bits_to_f32(b)
+    mt = O.match(xf2, dst, src)
+    assert int((mt["best"] - mt["second"] < NEAR_TIE).sum()) >= 150
+    idx = O.build_index(sel["role"], src, mt["anchor"])
+    idx.update(role=sel["role"], dst_idx=dst, src_idx=src)
+    n = _check_match(B, dict(pl=pl, idx=idx, mt=mt, ph=ph, xf=xf2, x_dev=to_dev_bf16(b)))
+    print(f"many near-equal candidates: {n} near-tie differences of {len(src)} src rows")
 
 
 def test_match_constant_features_one_giant_group(B):
@@ -1000,8 +1039,10 @@ def test_layers_run_teacher_forced_and_end_to_end(B, name, layers, interval):
           f"{pl.N} rows whose merge group is the same; {n_diff} of {pl.n_src} src tokens chose another anchor")
     # The per-op tolerance holds for one layer on identical inputs (the teacher-forced part
     # above).  Along a chain the bf16 roundings of every layer's stores add up in the residual
-    # stream like a random walk (measured 0.7e-2, 1.2e-2, 2.7e-2 after 2, 4, 24 layers), so the
-    # chained bound grows with the square root of the depth beyond 4 layers.
+    # stream (measured here 0.7e-2, 1.2e-2, 2.7e-2 after 2, 4, 24 layers), so the bound of these
+    # small cases grows with the square root of the depth beyond 4 layers.  It is a bound for
+    # these sizes only: test_layers_run_f32_stack_of_24_layers shows that at 32 frames single
+    # rows of this projection-free stack are unstable beyond the first refresh interval.
     assert err <= BF16_TOL * max(1.0, (layers / 4.0) ** 0.5)
     # divergence of a chained run grows with depth (the features of a group converge, so more
     # candidates are nearly tied): bounded loosely here, exact parity is the teacher-forced part
@@ -1010,6 +1051,182 @@ def test_layers_run_teacher_forced_and_end_to_end(B, name, layers, interval):
     assert n_role <= max(2, pl.N // 50), n_role
     sizes = np.diff(_i32(ib.group_off))
     assert sizes.sum() == pl.N and sizes.min() >= 1
+
+
+def test_layers_run_without_qk_norm(B):
+    """The paper-literal projection-free layer, q = k = v = the merged tokens as given (no
+    normalisation): three layers, before the doubling residual stream takes the logits out of
+    any useful range.  Teacher-forced per layer and chained, both at the bf16 tolerance; the
+    attention goes through the per-wave score bound and, where that is loose or exceeds the
+    exponent range, the running-maximum kernel."""
+    import torch
+    for name in ("tiny2", "small_r09"):
+        wl = WORKLOADS[name]()
+        wl = synth.Workload(**{**wl.__dict__, "refresh_interval": 2, "layers": 3})
+        bits, xf, im = stored_inputs(wl)
+        po, ph = oracle_params(wl, qk_norm=False), hip_params(wl, qk_norm=0)
+        pl = B.litevggt_plan(ph)
+        trace = []
+        ref_out, ref_log = O.layers_run(im, xf, po, 3, store=_store_bf16, trace=trace)
+        im_dev = torch.from_numpy(im).cuda()
+        ws = B.alloc_ws(pl.ws_bytes)
+        grad = torch.zeros(wl.frames, wl.patches, device="cuda")
+        score = torch.zeros(wl.frames, wl.patches, device="cuda")
+        p1 = hip_params(wl, qk_norm=0, refresh_interval=1)
+        for t in trace:
+            x_dev = f32_to_dev_bf16(t["x_in"].astype(np.float32))
+            ib = B.alloc_index(pl)
+            B.litevggt_layers_run(p1, 1, im_dev, x_dev, ib, grad, score, ws)
+            torch.cuda.synchronize()
+            exp = O.global_layer(t["x_in"], O.compute_index(im, t["x_in"], po)[0], po, _store_bf16)
+            err = max_rel_err(dev_bf16_to_f64(x_dev), exp)
+            print(f"[{name}] no qk_norm, layer {t['layer']} teacher-forced: {err:.3e}; max |x| {np.abs(exp).max():.3g}")
+            assert err <= BF16_TOL
+        x_dev = to_dev_bf16(bits)
+        ib = B.alloc_index(pl)
+        log = B.litevggt_layers_run(ph, 3, im_dev, x_dev, ib, grad, score, ws)
+        torch.cuda.synchronize()
+        assert log == ref_log
+        same = _i32(ib.anchor_of) == trace[-1]["index"]["anchor_of"]
+        touched = np.union1d(_i32(ib.anchor_of)[~same], trace[-1]["index"]["anchor_of"][~same])
+        keep = same & ~np.isin(trace[-1]["index"]["anchor_of"], touched)
+        got = dev_bf16_to_f64(x_dev)
+        err = float(np.abs(got - ref_out)[keep].max() / np.abs(ref_out).max())
+        print(f"[{name}] no qk_norm, chained 3 layers: {err:.3e} on {int(keep.sum())} of {pl.N} rows")
+        assert err <= BF16_TOL and keep.sum() >= 0.9 * pl.N
+
+
+def test_layers_run_f32_stack_of_24_layers(B, capsys):
+    """The 24-layer stack at 32 frames (43,968 tokens, dim 1024, merge ratio 0.9, refresh every
+    6), the largest size at which the oracle runs every layer in full.
+    * Teacher-forced refreshes (layers 0, 6, 12, 18): on the oracle's input of that layer the GPU
+      score map is within 2e-5, the GPU partition is the oracle's rule applied to the GPU's
+      scores, and matching on the oracle's partition gives the oracle's anchors exactly (except
+      near-ties with an oracle gap < 1e-6, counted) and its slot map and CSR bit for bit.
+    * Teacher-forced layers (all 24): merge, attention and unmerge on the oracle's input and the
+      oracle's index, every row within the bf16 tolerance.
+    * Chained: the driver's own 24 layers; reported (err on rows whose group has the same
+      members, anchors and roles that differ) and bounded."""
+    import torch
+    wl = synth.workload("f32")
+    layers = 24
+    bits, xf, im = stored_inputs(wl)
+    po, ph = oracle_params(wl), hip_params(wl)
+    pl = B.litevggt_plan(ph)
+    F, P, T, C = wl.frames, wl.patches, wl.tokens_per_frame, wl.dim
+    im_dev = torch.from_numpy(im).cuda()
+    ws = B.alloc_ws(pl.ws_bytes)
+    grad = torch.zeros(F, P, device="cuda")
+    score_dev = torch.zeros(F, P, device="cuda")
+    z = torch.empty(pl.M, C, dtype=torch.bfloat16, device="cuda")
+    y = torch.empty_like(z)
+
+    def say(msg):
+        with capsys.disabled():
+            print(msg, flush=True)
+
+    x = xf.astype(np.float64)
+    psi_g, idx, ib = None, None, None
+    worst_layer, near_total = 0.0, 0
+    ref_indices, ref_at = [], []
+    say("")
+    for l in range(layers):
+        x_dev = f32_to_dev_bf16(x.astype(np.float32))           # x is bf16-representable (stored)
+        if l % wl.refresh_interval == 0:
+            idx, psi_g, score, mt = O.compute_index(im, x, po, psi_g)
+            B.litevggt_importance(ph, im_dev, x_dev, grad, l == 0, score_dev, ws)
+            torch.cuda.synchronize()
+            got_score = score_dev.cpu().numpy()
+            assert np.abs(got_score.astype(np.float64) - score.astype(np.float64)).max() <= 2e-5
+            ib_own = B.alloc_index(pl)
+            B.litevggt_select_anchors(ph, score_dev, ib_own)
+            torch.cuda.synchronize()
+            own = O.select_anchors(got_score, po)
+            assert np.array_equal(ib_own.role.cpu().numpy(), own["role"])
+            n_role = int((own["role"] != idx["role"]).sum())
+            case_like = dict(pl=pl, idx=idx, mt=mt, ph=ph, xf=x.astype(np.float32), x_dev=x_dev)
+            n_near = _check_match(B, case_like)
+            near_total += n_near
+            ib = _upload_index(B, pl, idx)
+            ref_indices.append(idx)
+            sizes = np.diff(idx["group_off"])
+            say(f"[f32] layer {l}: refresh teacher-forced: anchors and CSR exact, {n_near} near-tie differences, "
+                f"{n_role} roles differ through fp32 score ties; largest group {sizes.max()}, "
+                f"{int((mt['best'] - mt['second'] < 1e-6).sum())} oracle near-ties")
+        B.litevggt_merge(ph, x_dev, ib, z)
+        B.litevggt_global_attn(ph, pl.M, z, z, z, y, ws)
+        B.litevggt_unmerge(ph, y, ib, x_dev, x_dev)
+        torch.cuda.synchronize()
+        x = O.global_layer(x, idx, po, _store_bf16)
+        if (l + 1) % wl.refresh_interval == 0:
+            ref_at.append(x.astype(np.float32))                 # exact: x is stored as bf16
+        err = max_rel_err(dev_bf16_to_f64(x_dev), x)
+        worst_layer = max(worst_layer, err)
+        say(f"[f32] layer {l}: teacher-forced max rel err {err:.3e}")
+        assert err <= BF16_TOL
+    ref_out = x
+
+    def row_stats(got, ref):
+        """Per-row max error relative to the tensor's max: (median, 99th percentile, max, share within 2e-2)."""
+        e = np.abs(got - ref).max(axis=1) / np.abs(ref).max()
+        return float(np.median(e)), float(np.percentile(e, 99)), float(e.max()), float(np.mean(e <= BF16_TOL))
+
+    # ---- chained features, the oracle's decisions: 24 layers of merge, attention, unmerge on the
+    # GPU's own running features with the oracle's index uploaded at every refresh: the whole
+    # floating-point path chained at depth, without the discrete decisions.  This stack (no
+    # projections, no frame attention, x <- x + U(Attn(M(x)))) is not a contraction: a token that
+    # sits between two clusters of keys leans further towards one of them with every layer, so a
+    # rounding-sized difference in such a row grows by about 2.5x per layer in the affected head
+    # (seen from layer 5 on) until the two sides have settled on different clusters.  The
+    # per-tensor bound therefore holds over the first refresh interval only; beyond it the bulk
+    # of the rows is what can be bounded.
+    x_dev = to_dev_bf16(bits)
+    for l in range(layers):
+        if l % wl.refresh_interval == 0:
+            ib = _upload_index(B, pl, ref_indices[l // wl.refresh_interval])
+        B.litevggt_merge(ph, x_dev, ib, z)
+        B.litevggt_global_attn(ph, pl.M, z, z, z, y, ws)
+        B.litevggt_unmerge(ph, y, ib, x_dev, x_dev)
+        if (l + 1) % wl.refresh_interval == 0:
+            torch.cuda.synchronize()
+            med, p99, worst, ok = row_stats(dev_bf16_to_f64(x_dev), ref_at[l // wl.refresh_interval].astype(np.float64))
+            say(f"[f32] chained features with the oracle's index, after layer {l + 1}: row error median {med:.2e}, "
+                f"99th percentile {p99:.2e}, max {worst:.2e}, rows within 2e-2: {ok:.4f}")
+            if l + 1 == wl.refresh_interval:
+                assert worst <= BF16_TOL * ((l + 1) / 4.0) ** 0.5
+            assert med <= BF16_TOL and ok >= 0.85
+
+    # ---- chained, the driver's own decisions: 24 layers in one call and in refresh-sized pieces
+    # (which must be the same computation), the index of every refresh compared with the oracle's
+    x_dev = to_dev_bf16(bits)
+    ib = B.alloc_index(pl)
+    log = B.litevggt_layers_run(ph, layers, im_dev, x_dev, ib, grad, score_dev, ws)
+    torch.cuda.synchronize()
+    assert log == O.refresh_schedule(layers, wl.refresh_interval)
+    x_seg = to_dev_bf16(bits)
+    ib_seg = B.alloc_index(pl)
+    n_diff, n_role = [], []
+    for k, ref_idx in enumerate(ref_indices):
+        B.litevggt_layers_run(ph, wl.refresh_interval, im_dev, x_seg, ib_seg, grad, score_dev, ws)
+        torch.cuda.synchronize()
+        n_diff.append(int((_i32(ib_seg.anchor_of) != ref_idx["anchor_of"]).sum()))
+        n_role.append(int((ib_seg.role.cpu().numpy() != ref_idx["role"]).sum()))
+        sizes = np.diff(_i32(ib_seg.group_off))
+        assert sizes.sum() == pl.N and sizes.min() >= 1
+        med, p99, worst, ok = row_stats(dev_bf16_to_f64(x_seg), ref_at[k].astype(np.float64))
+        say(f"[f32] the driver's own chain, after layer {(k + 1) * wl.refresh_interval}: row error median {med:.2e}, "
+            f"99th percentile {p99:.2e}, max {worst:.2e}, rows within 2e-2: {ok:.4f}; {n_diff[-1]} of {pl.n_src} src "
+            f"tokens chose another anchor and {n_role[-1]} roles differ at the refresh before")
+        assert med <= BF16_TOL and ok >= 0.85
+    assert torch.equal(x_seg, x_dev) and torch.equal(ib_seg.anchor_of, ib.anchor_of)
+    assert np.all(np.isfinite(dev_bf16_to_f64(x_dev)))
+    say(f"[f32] worst teacher-forced layer {worst_layer:.3e}, {near_total} teacher-forced near-tie differences")
+    # The parity bar is the teacher-forced part.  What is asserted of the chains: the first
+    # refresh sees identical inputs and agrees exactly; later the two sides' inputs differ (by
+    # roundings, then by the rows that settled differently), so decisions on near-equal
+    # candidates differ for a minority of the tokens.
+    assert n_diff[0] == 0 and n_role[0] == 0
+    assert max(n_diff) <= pl.n_src // 10 and max(n_role) <= pl.N // 50
 
 
 def test_layer_at_ratio_zero_equals_unmerged_attention(B):
