@@ -11,7 +11,8 @@ inputs resident in HBM before the timed region.
 Prints one JSON line.  `roofline` describes the dominant kernel (the attention kernel):
 its duration is measured with HIP events that the driver records on the launch stream
 inside the timed steps.  `cpu_baseline` is the CPU oracle timed on a bounded sub-sequence
-of the same workload and scaled by each step's operation count.
+of the same workload and scaled by each step's operation count; `parity` compares the HIP
+path with that oracle run on the same sub-sequence (outside the timed region).
 """
 from __future__ import annotations
 
@@ -59,7 +60,10 @@ def parse_args():
     ap.add_argument("--qk-norm", type=int, default=1, choices=[0, 1],
                     help="1 (default): q and k RMS-normalised per head as in the model; 0: as given "
                          "(per-wave score bound, running-maximum second pass where it is loose)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the oracle leg (cpu_baseline and the parity check that rides on it)")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the single-launch timings of the attention entry point's other kernels")
     ap.add_argument("--no-peaks", action="store_true",
                     help="skip the probes of what this box sustains (pure MFMA loops, plain copy)")
     ap.add_argument("--cpu-frames", type=int, default=96,
@@ -95,22 +99,33 @@ class HipEvents:
 CALIBRATION_COPY_BYTES = 256 << 20     # read once and written once by one elementwise kernel
 
 
-def measured_traffic(workload, dtype):
-    """HBM bytes per attention launch from the committed counter summary of this workload
-    (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the calibration copy), or None."""
-    path = os.path.join(ROOT, "profiles", f"attn_{dtype}_{workload}_hbm_traffic.txt")
+def measured_traffic(workload, dtype, kernel):
+    """HBM bytes per launch of `kernel` from the committed counter summary of this workload
+    (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the calibration copy).  The counters
+    cannot be read inside an unprofiled run, so the line names the file and its hash; a summary
+    made for another kernel gives (None, source)."""
+    import hashlib
+    rel = os.path.join("profiles", f"attn_{dtype}_{workload}_hbm_traffic.txt")
     try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1].split()[0])
+        text = open(os.path.join(ROOT, rel)).read()
     except OSError:
-        pass
-    return None
+        return None, None
+    src = {"file": rel, "sha256_16": hashlib.sha256(text.encode()).hexdigest()[:16],
+           "how": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this program, not measured in this run"}
+    value = None
+    for line in text.splitlines():
+        if line.startswith("traffic_bytes_per_launch"):
+            value = float(line.split("=")[1].split()[0])
+    if f"traffic_kernel = {kernel}" not in text:
+        return None, dict(src, note=f"the summary was not made for {kernel}")
+    return value, src
 
 
-def cpu_baseline(wl, pl_full, n_frames):
+def cpu_baseline(wl, pl_full, n_frames, qk_norm, attn_dtype, B, torch):
     """Time the oracle on the first n_frames of the workload, one layer with a refresh, and
-    scale each step to the full sequence by its operation count."""
+    scale each step to the full sequence by its operation count.  The same sub-sequence then
+    goes through the HIP path (one driver layer, outside any timed region) and the two results
+    are compared: `parity`."""
     import numpy as np
     from threadpoolctl import threadpool_info
     from helpers import oracle_params
@@ -119,9 +134,12 @@ def cpu_baseline(wl, pl_full, n_frames):
 
     sub = synth.Workload(**{**wl.__dict__, "frames": n_frames})
     gen = synth.Generator(wl)                     # same canvases/offsets as the full workload
-    x = synth.stored_to_f32(gen.tokens(range(n_frames)))
+    bits = gen.tokens(range(n_frames))
+    if bits.dtype != np.uint16:
+        bits = synth.f32_to_bf16_bits(bits)
+    x = synth.bf16_bits_to_f32(bits)
     im = gen.images(range(n_frames))
-    po = oracle_params(sub)
+    po = oracle_params(sub, qk_norm=bool(qk_norm))
     pls = O.plan(po)
     t = {}
     t0 = time.perf_counter()
@@ -139,10 +157,11 @@ def cpu_baseline(wl, pl_full, n_frames):
     t["merge"] = time.perf_counter() - t0
     zz = z.reshape(z.shape[0], po.heads, po.head_dim)
     t0 = time.perf_counter()
-    y = O.attention(zz, zz, zz).reshape(z.shape)
+    qk = O.qk_normalize(zz) if qk_norm else zz
+    y = O.attention(qk, qk, zz).reshape(z.shape)
     t["attn"] = time.perf_counter() - t0
     t0 = time.perf_counter()
-    O.unmerge(y, idx["slot_of"], residual=x)
+    ref_out = O.unmerge(y, idx["slot_of"], residual=x)
     t["unmerge"] = time.perf_counter() - t0
     fr = wl.frames / n_frames
     scale = dict(importance=fr, select=fr,
@@ -153,12 +172,49 @@ def cpu_baseline(wl, pl_full, n_frames):
     full = (refreshes * sum(t[k] * scale[k] for k in ("importance", "select", "match"))
             + wl.layers * sum(t[k] * scale[k] for k in ("merge", "attn", "unmerge")))
     threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
-    return dict(value=pl_full.N / full, unit="tokens/s", cores=int(threads), kind="oracle",
+
+    # the HIP path on the same sub-sequence, against what the oracle just computed
+    ph = B.make_params(sub.frames, sub.grid_h, sub.grid_w, sub.dim, sub.heads, n_special=sub.n_special,
+                       patch=sub.patch, merge_ratio=sub.merge_ratio, refresh_interval=sub.refresh_interval,
+                       qk_norm=int(bool(qk_norm)), attn_dtype=attn_dtype)
+    pl = B.litevggt_plan(ph)
+    x_dev = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    ib = B.alloc_index(pl)
+    g_dev = torch.zeros(sub.frames, sub.patches, device="cuda")
+    s_dev = torch.zeros(sub.frames, sub.patches, device="cuda")
+    B.litevggt_layers_run(ph, 1, torch.from_numpy(im).cuda(), x_dev, ib, g_dev, s_dev, B.alloc_ws(pl.ws_bytes))
+    torch.cuda.synchronize()
+    got = x_dev.float().cpu().numpy().astype(np.float64)
+    roles_differ = int((ib.role.cpu().numpy() != sel["role"]).sum())
+    src = sel["src_idx"].astype(np.int64)
+    a_hip = ib.anchor_of.cpu().numpy().astype(np.int64)[src]
+    differ = a_hip != idx["anchor_of"][src]
+    gap = mt["best"] - mt["second"]
+    same_rows = np.ones(pls["N"], dtype=bool)      # rows whose merge group has the same members
+    if differ.any() or roles_differ:
+        a_all, r_all = ib.anchor_of.cpu().numpy().astype(np.int64), idx["anchor_of"].astype(np.int64)
+        touched = np.union1d(a_all[a_all != r_all], r_all[a_all != r_all])
+        same_rows = (a_all == r_all) & ~np.isin(r_all, touched)
+    err = float(np.abs(got - ref_out)[same_rows].max() / np.abs(ref_out).max())
+    parity = dict(sample=f"first {n_frames} frames: one refresh + one layer of the driver against the oracle "
+                         f"(float64, unrounded), N={pls['N']}, M={pls['M']}",
+                  score_max_abs_err=float(np.abs(s_dev.cpu().numpy().astype(np.float64) - score).max()),
+                  roles_differ=roles_differ,
+                  src_tokens=int(len(src)), anchors_differ=int(differ.sum()),
+                  anchors_differ_documented_near_ties=int((differ & (gap < 1e-6)).sum()),
+                  oracle_near_ties=int((gap < 1e-6).sum()),
+                  layer_max_rel_err=err, rows_compared=int(same_rows.sum()),
+                  tolerance=2e-2 if attn_dtype == B.ATTN_BF16 else 6e-2)
+    parity["ok"] = bool(parity["anchors_differ"] == parity["anchors_differ_documented_near_ties"]
+                        and err <= parity["tolerance"] and parity["score_max_abs_err"] <= 2e-5)
+    return dict(value=pl_full.N / full, unit="tokens/s", cores=int(threads), os_cpu_count=os.cpu_count(),
+                kind="oracle",
                 sample=(f"oracle timed on the first {n_frames} of {wl.frames} frames "
-                        f"(N={pls['N']}, M={pls['M']}), one refresh + one layer, "
+                        f"(N={pls['N']}, M={pls['M']}), one refresh + one layer"
+                        f"{' with q, k normalised' if qk_norm else ''}, "
                         f"{sum(t.values()):.1f} s measured; each step scaled to the full "
                         f"sequence by its operation count (extrapolated step: {full:.0f} s)"),
-                measured_s={k: round(v, 3) for k, v in t.items()})
+                measured_s={k: round(v, 3) for k, v in t.items()}), parity
 
 
 def sustained_peaks(B, torch):
@@ -321,12 +377,15 @@ def main():
              "unmerge": (B.EV_BLOCK_END, B.EV_UNMERGE_END),
              "frame_attn": (B.EV_UNMERGE_END, B.EV_FRAME_ATTN_END)}
     dur = {k: [] for k in names}
+    imp_by_layer = []
     for ev in evs:
         for l in range(L):
             for k, (a, b) in names.items():
                 if k in ("importance", "select", "match") and not log[l]:
                     continue
                 dur[k].append(ev.ms(l * E + a, l * E + b))
+                if k == "importance":
+                    imp_by_layer.append((dur[k][-1], l))
     avg = {k: (sum(v) / len(v) if v else 0.0) for k, v in dur.items()}
     # each step on the device's clock: first to last event of its driver call
     last_ev = (L - 1) * E + B.EV_FRAME_ATTN_END
@@ -350,8 +409,21 @@ def main():
         "merge": dict(ms=avg["merge"], gbs=merge_bytes / (avg["merge"] * 1e-3) / 1e9),
         "unmerge": dict(ms=avg["unmerge"], gbs=unmerge_bytes / (avg["unmerge"] * 1e-3) / 1e9),
         "importance": dict(ms=avg["importance"]),
-        "select": dict(ms=avg["select"]),
+        "select": dict(ms=avg["select"], note="per refresh: per-frame cell arg-mins and rank counting, latency-bound (5.5 MB in)"),
     }
+    if args.anchor_policy == "ga":
+        # refreshes after the first read the cached gradient map: x patch rows once + three maps
+        imp_first = [ev_ms for ev_ms, l in imp_by_layer if l == 0]
+        imp_cached = [ev_ms for ev_ms, l in imp_by_layer if l != 0]
+        imp_bytes = wl.frames * wl.patches * (C_ * 2 + 3 * 4)
+        if imp_first:
+            ops["importance"]["ms_first_refresh_with_grad_map"] = sum(imp_first) / len(imp_first)
+        if imp_cached:
+            ms_c = sum(imp_cached) / len(imp_cached)
+            ops["importance"].update(ms_cached_grad=ms_c, gbs=imp_bytes / (ms_c * 1e-3) / 1e9,
+                                     frac_hbm=imp_bytes / (ms_c * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                     note="gbs / frac_hbm: variance map + fusion of the refreshes that reuse the "
+                                          "cached gradient map, bytes = patch rows of x once + the three maps")
     if args.block:
         blk_flop = 2.0 * M * C_ * (3 * C_ + C_ + 4 * C_ + 4 * C_)
         ops["block_linear"] = dict(ms=avg["attn_pack"] + avg["block_rest"],
@@ -384,6 +456,56 @@ def main():
                              "sequence (n_tokens = N, q = k = v = x), times the layer count")
         del ws_u, o
 
+    # single launches of the attention entry point's other kernels at the merged length, on the
+    # first layer's merged tokens (index of the input features), timed around the call
+    variants = None
+    if not args.no_variants and not args.block:
+        B.litevggt_importance(ph, im, x0, grad, True, score, ws)
+        B.litevggt_select_anchors(ph, score, ib)
+        B.litevggt_match(ph, x0, ib, None, ws)
+        zv = torch.empty(M, C_, dtype=torch.bfloat16, device="cuda")
+        yv = torch.empty_like(zv)
+        B.litevggt_merge(ph, x0, ib, zv)
+
+        def launch_ms(p, reps=3):
+            wsv = B.alloc_ws(B.litevggt_attn_ws_bytes(p, M))
+            B.litevggt_global_attn(p, M, zv, zv, zv, yv, wsv)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                B.litevggt_global_attn(p, M, zv, zv, zv, yv, wsv)
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+
+        def mk(**kw):
+            base = dict(n_special=wl.n_special, patch=wl.patch, merge_ratio=wl.merge_ratio,
+                        refresh_interval=wl.refresh_interval, qk_norm=1, attn_dtype=B.ATTN_BF16)
+            base.update(kw)
+            return B.make_params(wl.frames, wl.grid_h, wl.grid_w, wl.dim, wl.heads, **base)
+
+        variants = {"note": "one litevggt_global_attn call (K/V re-layout + kernels) at M merged tokens of the first "
+                            "layer, averaged over 3 calls; frac = 4 M^2 C flop / call time / peak, so the re-layout "
+                            "(ops.attn_pack) is inside"}
+        for key, p_v, peak_v, what in (
+                ("bf16_qk_norm", mk(), PEAK_BF16_MFMA_TFLOPS, "k_attn_bf16_bounded<false>: fixed reference (unit-RMS q, k)"),
+                ("bf16_as_given", mk(qk_norm=0), PEAK_BF16_MFMA_TFLOPS,
+                 "k_attn_bf16_bounded<true>: per-wave reference from max|q| max|k|, then the gated running-maximum kernel"),
+                ("bf16_online_softmax", mk(softmax_scale=0.7), PEAK_BF16_MFMA_TFLOPS,
+                 "k_attn_bf16 alone: online softmax with a lazily raised running maximum (forced by a softmax "
+                 "scale of 0.7, beyond the fixed reference's exponent range)"),
+                ("fp8_qk_norm", mk(attn_dtype=B.ATTN_FP8_E4M3), PEAK_FP8_MFMA_TFLOPS, "k_attn_fp8_bounded"),
+                ("fp8_as_given", mk(attn_dtype=B.ATTN_FP8_E4M3, qk_norm=0), PEAK_FP8_MFMA_TFLOPS,
+                 "k_attn_fp8: running maximum")):
+            ms_v = launch_ms(p_v)
+            variants[key] = dict(kernel=what, ms_call=ms_v, tflops=attn_flop / (ms_v * 1e-3) / 1e12,
+                                 frac_mfma=attn_flop / (ms_v * 1e-3) / 1e12 / peak_v)
+        del zv, yv
+
+    roof_kernel = ("k_attn_fp8_bounded" if args.attn_dtype == "fp8" and wl_qk_norm else "k_attn_fp8" if args.attn_dtype == "fp8"
+                   else "k_attn_bf16_bounded<false>" if wl_qk_norm else "k_attn_bf16_bounded<true>")
+    traffic, traffic_src = measured_traffic(wl.name, args.attn_dtype, roof_kernel)
     out = {
         "metric": "merged global-attn tokens/s @%d frames" % wl.frames,
         "value": N / (ms_step * 1e-3),
@@ -408,12 +530,13 @@ def main():
                    "calibration_copy_bytes": CALIBRATION_COPY_BYTES,
                    "device_ms_per_step_median": step_median, "device_ms_per_step_min": step_ms[0],
                    "device_ms_per_step_max": step_ms[-1]},
-        "roofline": {"kernel": ("k_attn_fp8_bounded" if args.attn_dtype == "fp8" and wl_qk_norm else "k_attn_fp8" if args.attn_dtype == "fp8" else "k_attn_bf16_bounded"), "bound": "mfma", "achieved": attn_tf, "peak": peak_tf,
+        "roofline": {"kernel": roof_kernel, "bound": "mfma", "achieved": attn_tf, "peak": peak_tf,
                      "unit": "TFLOP/s", "frac": attn_tf / peak_tf,
-                     "traffic": measured_traffic(wl.name, args.attn_dtype),
+                     "traffic": traffic, "traffic_source": traffic_src,
                      "flop_per_launch": attn_flop, "avg_launch_ms": avg["attn"],
                      "launches_timed": len(dur["attn"])},
         "ops": ops,
+        "attn_variants": variants,
         "unmerged_attention": unmerged,
     }
     if unmerged:
@@ -421,7 +544,8 @@ def main():
     if not args.no_peaks:
         out["sustained_peaks"] = sustained_peaks(B, torch)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, pl, min(args.cpu_frames, wl.frames))
+        out["cpu_baseline"], out["parity"] = cpu_baseline(wl, pl, min(args.cpu_frames, wl.frames), args.qk_norm,
+                                                          attn_dtype, B, torch)
     print(json.dumps(out))
 
 
