@@ -40,6 +40,22 @@ __device__ __forceinline__ double wave_sum(double v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
 }
+// Sum over the 64 lanes with DPP moves only (no LDS round trips): butterflies inside each row of
+// 16 lanes (quad permutes, half-row mirror, row mirror), then lane 15 of a row broadcast into the
+// next row and lane 31 into rows 2 and 3; lane 63 holds the total, returned as a uniform value.
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ float dpp_take(float v) {   // 0 where the row is masked out
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, kRowMask, 0xF, false));
+}
+__device__ __forceinline__ float wave_sum_uniform(float v) {
+  v += dpp_take<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+  v += dpp_take<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+  v += dpp_take<0x141, 0xF>(v);   // row_half_mirror
+  v += dpp_take<0x140, 0xF>(v);   // row_mirror: every lane holds its row's sum
+  v += dpp_take<0x142, 0xA>(v);   // row_bcast15 into rows 1 and 3
+  v += dpp_take<0x143, 0xC>(v);   // row_bcast31 into rows 2 and 3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));

@@ -164,7 +164,143 @@ __global__ __launch_bounds__(128) void k_var_map(const uint16_t *__restrict__ x,
     psi_v[((size_t)f * H + i) * W + j] = (part[j * 2] + part[j * 2 + 1]) / (float)C;
 }
 
+// ---------------------------------------------------------------------------------
+// Psi_v for the 3 x 3 window, every token row read once (plus a one-column halo on each side
+// of a strip).  A workgroup (2 waves, lane = 8 channels, wave = 512 channels) owns a strip of
+// kSeg grid columns of one frame and walks down the grid rows.  When row i arrives the window
+// sums of output row i - 1 follow from
+//   sum_c var_c = (1/n) sum_window e  -  (1/n^2) sum_c (sum_window d_c)^2,
+// d = x - (the frame's first patch token), e = sum_c d_c^2 of one token: only the first moment
+// needs per-channel window sums, the second moment is a window sum of one number per token.
+// Per column the lane keeps d of row i-1 and the pair sum d(i-1) + d(i-2) in fp32, so every
+// token is widened once: vertical sum = d(i) + pair, then pair <- d(i) + d(i-1); the horizontal
+// 3-sum slides over the strip's columns.  Cells outside the grid are fed as the pivot token
+// (d = 0) and n counts the cells inside.  The bits of row i+1 are requested into a column's
+// registers as soon as that column of row i has been widened.
+// ---------------------------------------------------------------------------------
+#ifndef LV_VAR_SEG
+#define LV_VAR_SEG 4
+#endif
+constexpr int kSeg = LV_VAR_SEG;
+constexpr int kVarWaves = 2;                   // waves per workgroup: 512 channels each, 8 per lane
+
+__global__ __launch_bounds__(64 * kVarWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_var_map3(
+    const uint16_t *__restrict__ x, int F, int H, int W, int S, int C, int nseg, float *__restrict__ psi_v) {
+  constexpr int NC = kSeg + 2;               // columns a strip reads: its own and one on each side
+  __shared__ float comb[2][kVarWaves][kSeg]; // the waves' partial sums of a grid row, by row parity
+  const uint32_t nblk = (uint32_t)F * nseg;
+  const uint32_t lb = xcd_contiguous(blockIdx.x, nblk);   // neighbouring strips share an L2
+  if (lb >= nblk) return;
+  const int f = lb / nseg, j0 = (int)(lb % nseg) * kSeg;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int T = H * W + S;
+  const uint16_t *frame = x + ((size_t)f * T + S) * C;
+  float *out = psi_v + (size_t)f * H * W;
+  const float inv_c = 1.0f / (float)C;
+  for (int cbase = 0; cbase < C; cbase += 512 * kVarWaves) {
+    const int c0 = cbase + wave * 512 + lane * 8;
+    const bool on = c0 < C;
+    const u32x4 pbits = on ? *(const u32x4 *)(frame + c0) : u32x4{0u, 0u, 0u, 0u};
+    const float pv[8] = {bf16_lo(pbits.x), bf16_hi(pbits.x), bf16_lo(pbits.y), bf16_hi(pbits.y),
+                         bf16_lo(pbits.z), bf16_hi(pbits.z), bf16_lo(pbits.w), bf16_hi(pbits.w)};
+    u32x4 raw[2][NC];                          // bits of rows i and i+1, by row parity; a column's
+                                               // registers are refilled with row i+2 once used
+    float d1[NC][8], pair[NC][8];              // d(i-1) and d(i-1) + d(i-2) per column
+    float e1[NC], epair[NC];                   // the same for this lane's share of e
+    auto fetch = [&](int i, int a, u32x4 &dst) {   // column a of the strip in grid row i, or the pivot
+      const int jj = j0 - 1 + a;
+      dst = pbits;
+      if (on && i < H && jj >= 0 && jj < W) dst = *(const u32x4 *)(frame + ((size_t)i * W + jj) * C + c0);
+    };
+#pragma unroll
+    for (int a = 0; a < NC; ++a) {
+      fetch(0, a, raw[0][a]);
+      fetch(1, a, raw[1][a]);
+      e1[a] = epair[a] = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d1[a][e] = pair[a][e] = 0.f;
+    }
+    auto step = [&](auto parity, int i) {      // grid row i arrives, output row i - 1 leaves
+      u32x4(&rw)[NC] = raw[decltype(parity)::value];
+      const int io = i - 1;
+      const int nrow = min(io + 1, H - 1) - max(io - 1, 0) + 1;
+      const float inv_r = nrow == 3 ? (1.0f / 3.0f) : nrow == 2 ? 0.5f : 1.0f;
+      float v0[8], v1[8], v2[8];               // vertical sums of the last three columns
+      float ve0 = 0.f, ve1 = 0.f, ve2 = 0.f;
+      float res[kSeg];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v0[e] = v1[e] = v2[e] = 0.f;
+#pragma unroll
+      for (int a = 0; a < NC; ++a) {
+        const u32x4 w = rw[a];
+        const float xv[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
+                             bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+        fetch(i + 2, a, rw[a]);
+        float e_new = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {          // slide: columns a - 2, a - 1 stay
+          v0[e] = v1[e];
+          v1[e] = v2[e];
+          const float dn = xv[e] - pv[e];
+          e_new = __builtin_fmaf(dn, dn, e_new);
+          v2[e] = dn + pair[a][e];
+          pair[a][e] = dn + d1[a][e];
+          d1[a][e] = dn;
+        }
+        ve0 = ve1;
+        ve1 = ve2;
+        ve2 = e_new + epair[a];
+        epair[a] = e_new + e1[a];
+        e1[a] = e_new;
+        if (a >= 2) {                          // output column j0 + a - 2
+          const int jo = j0 + a - 2;
+          const int ncol = min(jo + 1, W - 1) - max(jo - 1, 0) + 1;
+          const float inv_n = (ncol == 3 ? (1.0f / 3.0f) : ncol == 2 ? 0.5f : 1.0f) * inv_r;   // scalar work
+          float sq = 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float h = v0[e] + v1[e] + v2[e];
+            sq = __builtin_fmaf(h, h, sq);
+          }
+          const float m2 = (ve0 + ve1 + ve2) * inv_n;
+          res[a - 2] = __builtin_fmaf(-sq * inv_n, inv_n, m2);
+        }
+      }
+      // every lane holds its 8 channels' share of the strip's kSeg outputs of row io
+#pragma unroll
+      for (int q = 0; q < kSeg; ++q) res[q] = wave_sum_uniform(res[q]);
+      float r = res[0];
+#pragma unroll
+      for (int q = 1; q < kSeg; ++q) r = lane == q ? res[q] : r;
+      if (lane < kSeg) comb[i & 1][wave][lane] = r;
+      __syncthreads();
+      if (wave == 0 && lane < kSeg && io >= 0 && io < H && j0 + lane < W) {
+        r = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < kVarWaves; ++w2) r += comb[i & 1][w2][lane];
+        r *= inv_c;
+        float *o = out + (size_t)io * W + j0 + lane;
+        *o = cbase ? *o + r : r;
+      }
+    };
+    // rows 0 .. H; row H is a row of pivots that flushes output row H - 1 (a step beyond it sees
+    // pivots only and writes nothing)
+    for (int i = 0; i <= H; i += 2) {
+      step(std::integral_constant<int, 0>{}, i);
+      step(std::integral_constant<int, 1>{}, i + 1);
+    }
+    __syncthreads();                           // comb is reused by the next channel pass
+  }
+}
+
 int launch_var_map(const uint16_t *x, const Dims &d, int pool, float *psi_v, hipStream_t st) {
+  if (pool == 3) {
+    const int nseg = (d.W + kSeg - 1) / kSeg;
+    hipLaunchKernelGGL(k_var_map3, dim3((unsigned)align_up((size_t)d.F * nseg, kXcd)), dim3(64 * kVarWaves), 0, st, x, d.F,
+                       d.H, d.W, d.S, d.C, nseg, psi_v);
+    LV_HIP_CHECK_LAUNCH();
+    return LV_OK;
+  }
   dim3 grid((unsigned)(align_up((size_t)d.F * d.H, kXcd)));
   size_t lds = (size_t)d.W * 2 * sizeof(float);
   switch (pool) {
