@@ -15,7 +15,9 @@ scipy.ndimage routines for the filters, a sparse averaging matrix for the merge,
 torch's scaled_dot_product_attention for the attention core, torch's float8_e4m3fn
 casts for the FP8 rounding and linear layers, closed forms for the delayed-scaling
 history, pure-Python brute force for selection and matching, the paper's recompute-count table for the
-cache schedule.  The ratio -> (cell size, number of GA tokens) rule is a
+cache schedule; the two FP8 attention emulations (attention_fp8, attention_fp8_bounded:
+diagnostics, the bar of that variant is exact attention) against scalar restatements with a
+table-driven E4M3 rounder and weights worked out by hand (tests/test_oracle_fp8_pins.py).  The ratio -> (cell size, number of GA tokens) rule is a
 definition of this build, not of the paper: **parity unpinned** for that rule
 beyond its own closed-form counts.
 """
