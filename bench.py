@@ -489,12 +489,12 @@ def main():
                             "layer, averaged over 3 calls; frac = 4 M^2 C flop / call time / peak, so the re-layout "
                             "(ops.attn_pack) is inside"}
         for key, p_v, peak_v, what in (
-                ("bf16_qk_norm", mk(), PEAK_BF16_MFMA_TFLOPS, "k_attn_bf16_bounded<false>: fixed reference (unit-RMS q, k)"),
+                ("bf16_qk_norm", mk(), PEAK_BF16_MFMA_TFLOPS, "k_attn_bf16_main<false>: fixed reference (unit-RMS q, k)"),
                 ("bf16_as_given", mk(qk_norm=0), PEAK_BF16_MFMA_TFLOPS,
-                 "k_attn_bf16_bounded<true>: per-wave reference from max|q| max|k|, then the gated running-maximum kernel"),
+                 "k_attn_bf16_main<true> (online softmax, per-wave running reference raised lazily), then the gated per-row kernel"),
                 ("bf16_online_softmax", mk(softmax_scale=0.7), PEAK_BF16_MFMA_TFLOPS,
-                 "k_attn_bf16 alone: online softmax with a lazily raised running maximum (forced by a softmax "
-                 "scale of 0.7, beyond the fixed reference's exponent range)"),
+                 "k_attn_bf16_main<true> on normalised q, k with a softmax scale of 0.7 (beyond the fixed "
+                 "reference's exponent range), then the gated per-row kernel"),
                 ("fp8_qk_norm", mk(attn_dtype=B.ATTN_FP8_E4M3), PEAK_FP8_MFMA_TFLOPS, "k_attn_fp8_bounded"),
                 ("fp8_as_given", mk(attn_dtype=B.ATTN_FP8_E4M3, qk_norm=0), PEAK_FP8_MFMA_TFLOPS,
                  "k_attn_fp8: running maximum")):
@@ -504,7 +504,7 @@ def main():
         del zv, yv
 
     roof_kernel = ("k_attn_fp8_bounded" if args.attn_dtype == "fp8" and wl_qk_norm else "k_attn_fp8" if args.attn_dtype == "fp8"
-                   else "k_attn_bf16_bounded<false>" if wl_qk_norm else "k_attn_bf16_bounded<true>")
+                   else "k_attn_bf16_main<false>" if wl_qk_norm else "k_attn_bf16_main<true>")
     traffic, traffic_src = measured_traffic(wl.name, args.attn_dtype, roof_kernel)
     out = {
         "metric": "merged global-attn tokens/s @%d frames" % wl.frames,

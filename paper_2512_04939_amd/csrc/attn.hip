@@ -58,8 +58,7 @@ __global__ __launch_bounds__(256) void k_attn_pack(const uint16_t *__restrict__ 
                                                    const uint16_t *__restrict__ v, int64_t n,
                                                    int heads, int n_kt, int qk_norm,
                                                    u32x4 *__restrict__ kp,
-                                                   u32x4 *__restrict__ vp,
-                                                   uint32_t *__restrict__ kmax) {
+                                                   u32x4 *__restrict__ vp) {
   __shared__ __attribute__((aligned(16))) uint16_t vt[kKT][72];
   const int kt = blockIdx.x, t = threadIdx.x;
   const int seq = blockIdx.y / heads, head = blockIdx.y - seq * heads;
@@ -74,12 +73,6 @@ __global__ __launch_bounds__(256) void k_attn_pack(const uint16_t *__restrict__ 
     wv = *(const u32x4 *)(v + (size_t)row * C + head * 64 + chunk * 8);
   }
   if (qk_norm) wk = rms_scale8(wk, 3);   // the 8 lanes that share a key hold its 64 values
-  if (kmax) {                            // largest |k| of this (sequence, head): bits of a float >= 0
-    float ss = sumsq8(wk);
-    for (int o2 = 1; o2 < 8; o2 <<= 1) ss += __shfl_xor(ss, o2, 64);
-    ss = wave_max(ss);
-    if ((t & 63) == 0) atomicMax(&kmax[blockIdx.y], __float_as_uint(sqrtf(ss)));
-  }
   const size_t tile = ((size_t)blockIdx.y * n_kt + kt) * 4 * kFragU4;
   kp[tile + (chunk >> 1) * kFragU4 + (chunk & 1) * 32 + key] = wk;
   *(u32x4 *)&vt[key][chunk * 8] = wv;
@@ -375,13 +368,28 @@ __global__ __launch_bounds__(512) void k_attn_bf16(
 }
 
 // ---------------------------------------------------------------------------------------
-// Bounded-score kernel (qk_norm): no running maximum, so a loop iteration has no branches
-// and the whole iteration is one basic block.  A wave owns two 32-query blocks that run half
-// a 32-key step apart, which gives every stretch of the instruction stream independent VALU
-// (exp2, bf16 pack, row sum of one block) and MFMA work (PV and next scores of the other):
+// The main attention kernel.  A wave owns two 32-query blocks that run half a 32-key step
+// apart, which gives every stretch of the instruction stream independent VALU (exp2, bf16
+// pack, row sum of one block) and MFMA work (PV and next scores of the other):
 //   A(t): weights of block 0, tile t   ||  PV of block 1, tile t-1;  scores of block 1, tile t
 //   B(t): weights of block 1, tile t   ||  PV of block 0, tile t;    scores of block 0, tile t+1
 // The MFMAs are interleaved with the VALU work by an explicit scheduling recipe.
+//
+// The softmax scale (in log2 units) is folded into q before its one bf16 rounding, so a
+// score leaves the MFMA ready for exp2.  What the exponent is taken against:
+//   ONLINE = false (unit-RMS q and k whose scores cannot exceed 64 in log2 units): nothing;
+//     softmax is invariant to the reference and exp2 of a bounded score cannot overflow.  The
+//     loop has no maximum, no subtraction, no rescale and no branch.
+//   ONLINE = true: online softmax with one running reference R per wave, raised lazily.  The
+//     score accumulators start from -R (the MFMA's C operand), so the steady state costs the
+//     same instructions plus one compare and branch per phase: a tile whose weights push a row
+//     sum beyond 2^40 (some score more than ~40 above R, or not finite) triggers a raise: R
+//     moves to that tile's maximum, O and the row sums of both blocks are rescaled by 2^-(R' - R),
+//     the scores still pending are re-based, the tile's weights are recomputed.  fp32 covers
+//     rows up to ~100 binades apart in one wave; a 256-query block in which some row ends with a
+//     sum below 2^-60 (all its scores far below its wave's reference), or whose reference grows
+//     beyond kRefUseful (where the bf16 rounding of the scaled q no longer resolves the
+//     scores), writes nothing, sets its flag, and the per-row kernel k_attn_bf16 redoes it.
 // ---------------------------------------------------------------------------------------
 // waits until every LDS operation issued so far has completed
 __device__ __forceinline__ void lds_wait(u32x4 (&a)[4], u32x4 (&b)[4]) {
@@ -393,15 +401,16 @@ __device__ __forceinline__ void lds_wait(u32x4 (&a)[4], u32x4 (&b)[4]) {
 }
 
 constexpr int kBQB = 256;            // queries per workgroup (4 waves)
-constexpr float kRefUseful = 256.0f; // largest per-wave score bound (log2 units) the first pass is tried with
+constexpr float kRefUseful = 256.0f; // largest reference (log2 units) the folded scale resolves scores against
+constexpr float kSumRaise = 1.0995116e12f;   // 2^40: a row sum beyond it raises the wave's reference
 constexpr int kBStages = 4;          // LDS ring of 64-key K/V stages
 
 
-template <bool REF>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_bf16_bounded(
+template <bool ONLINE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_bf16_main(
     const uint16_t *q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp, uint16_t *o,
-    const uint16_t *res, int64_t n, int heads, int n_seq, int n_kt, int nqb, float c,
-    const uint32_t *__restrict__ kmax, uint32_t *__restrict__ redo, int redo_stride) {
+    const uint16_t *res, int64_t n, int heads, int n_seq, int n_kt, int nqb, float c, int qk_norm,
+    uint32_t *__restrict__ redo, int redo_stride) {
   __shared__ u32x4 ks[kBStages][8 * kFragU4];
   __shared__ u32x4 vs[kBStages][8 * kFragU4];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ql = lane & 31;
@@ -443,12 +452,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   fetch(0);
   fetch(min(1, nkv - 1));
 
-  // Q^T fragments, RMS-normalised per head with the softmax scale (log2 units) folded in.
-  // REF (q, k as given): only the scale is folded in, and the wave's 64 queries share the
-  // reference scale * max |q| * max |k| * (1 + 2^-7) >= any of their scores (Cauchy-Schwarz; the
-  // factor covers the bf16 rounding of the scaled q), which the scores start from.
+  // Q^T fragments with the softmax scale (log2 units) folded in, RMS-normalised per head when
+  // qk_norm is set
   bf16x8 qf[2][4];
-  float rf[2] = {0.f, 0.f};
 #pragma unroll
   for (int sub = 0; sub < 2; ++sub) {
     const int64_t row = min(q0 + sub * 32 + ql, n - 1);
@@ -458,8 +464,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int s = 0; s < 4; ++s) w[s] = *(const u32x4 *)(qp + 16 * s);
     float ss = (sumsq8(w[0]) + sumsq8(w[1])) + (sumsq8(w[2]) + sumsq8(w[3]));
     ss += __shfl_xor(ss, 32, 64);
-    const float r = REF ? c : c / sqrtf(ss * (1.0f / 64.0f) + kQkEps);
-    if (REF) rf[sub] = sqrtf(ss);
+    const float r = qk_norm ? c / sqrtf(ss * (1.0f / 64.0f) + kQkEps) : c;
 #pragma unroll
     for (int s = 0; s < 4; ++s) qf[sub][s] = __builtin_bit_cast(bf16x8, scale8(w[s], r));
   }
@@ -472,23 +477,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[sub][dt][r] = 0.f;
   float lrow[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
-  // what the score accumulators start from: 0, or minus the reference of the wave's longest
-  // query (16 registers that stay live through the loop; one per query block would not fit, a
-  // subtraction per score would cost a fifth of the kernel's VALU time)
+  // what the score accumulators start from: 0, or minus the wave's running reference (16
+  // registers that stay live through the loop; one per query block would not fit, a subtraction
+  // per score would cost a fifth of the kernel's VALU time)
   f32x16 s_start = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (REF) {
-    const float ref = c * wave_max(fmaxf(rf[0], rf[1])) * __uint_as_float(kmax[sh]) * (1.0f + 0.0078125f);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s_start[r] = -ref;
-    // Scores have to come within 60 of the bound for it to serve; when it is this large they
-    // almost never do (and not finite means they cannot), so the block goes to the second pass
-    // without being computed here first.
-    if (__syncthreads_or(!(ref <= kRefUseful))) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the two stages already requested land before the workgroup ends
-      if (tid == 0) redo[(size_t)sh * redo_stride + qb] = 1u;
-      return;
-    }
-  }
+  float ref_run = 0.f;         // ONLINE: the reference R (uniform over the wave)
+  bool over = false;           // ONLINE: R went beyond kRefUseful
+  float lnew[2] = {0.f, 0.f};  // ONLINE: row sums including the tile whose weights were just taken
 
   f32x16 sacc[2];      // [query block]: scores of its current 32-key tile
   u32x4 pb[2][2];      // [query block][u]: bf16 weights of its current 32-key tile
@@ -552,8 +547,49 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       }
       pb[sub][u] = u32x4{w[0], w[1], w[2], w[3]};
     }
-    lrow[sub][0] = l0;
-    lrow[sub][1] = l1;
+    if (ONLINE) {      // held back until settle() has seen them
+      lnew[0] = l0;
+      lnew[1] = l1;
+    } else {
+      lrow[sub][0] = l0;
+      lrow[sub][1] = l1;
+    }
+  };
+  // ONLINE, at the end of the phase that took the weights of block `sub`: accept the new row
+  // sums, or raise the reference first.  At this point the other block's weights have been
+  // consumed (its PV was issued in this phase), its scores of the next tile are pending, and no
+  // MFMA of `sub`'s tile has been issued yet.
+  auto settle = [&](int sub) {
+    if (!ONLINE) return;
+    __builtin_amdgcn_sched_barrier(0);
+    if (__builtin_amdgcn_ballot_w64(!(lnew[0] + lnew[1] <= kSumRaise)) != 0) {
+      // fragment reads issued by hand may be in flight: let them land before anything else
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      float mx = sacc[sub][0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[sub][r]);
+      const float delta = fmaxf(wave_max(mx), 0.f);      // how far the tile's maximum lies above R
+      const float alpha = __builtin_amdgcn_exp2f(-delta);
+      ref_run += delta;
+      over |= !(ref_run <= kRefUseful);
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        lrow[b][0] *= alpha;
+        lrow[b][1] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[b][dt][r] *= alpha;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[b][r] -= delta;   // own tile: redone below; other block: pending scores
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_start[r] = -ref_run;
+      weights(sub);
+    }
+    lrow[sub][0] = lnew[0];
+    lrow[sub][1] = lnew[1];
+    __builtin_amdgcn_sched_barrier(0);
   };
   // One phase = 8 MFMAs + the weights of 16 scores per lane (16 exp2, 8 pack, 16 add).  The
   // recipe asks the scheduler to spread the MFMAs over the VALU work; A phases re-fill fv
@@ -593,6 +629,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     mma_pv(1, v_prev);
     mma_s(1, k_cur);
     recipe();
+    settle(0);
   };
   // B(t), t <= nkt-2: weights of block 1 || PV(t) and scores(t+1) of block 0
   auto phase_b = [&](u32x4(&v_cur)[4], u32x4(&k_next)[4], int fq = -1) {
@@ -606,6 +643,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     mma_pv(0, v_cur);
     mma_s(0, k_next);
     recipe();
+    settle(1);
   };
 
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -615,11 +653,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   load_k(0, fk[0]);
   mma_s(0, fk[0]);
   mask_tail(0, 0);
-  weights(0);
-  mma_s(1, fk[0]);
+  if (ONLINE) {
+    // the reference starts at the largest score of the first tile (both blocks)
+    mma_s(1, fk[0]);
+    mask_tail(0, 1);
+    float mx = fmaxf(sacc[0][0], sacc[1][0]);
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(sacc[0][r], sacc[1][r]));
+    ref_run = wave_max(mx);
+    // A reference this large cannot serve (and one that is not finite cannot at all): the block
+    // goes to the second pass without being computed here first.
+    if (__syncthreads_or(!(ref_run <= kRefUseful))) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the stages already requested land before the workgroup ends
+      if (tid == 0) redo[(size_t)sh * redo_stride + qb] = 1u;
+      return;
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      s_start[r] = -ref_run;
+      sacc[0][r] -= ref_run;
+      sacc[1][r] -= ref_run;
+    }
+    weights(0);
+    lrow[0][0] = lnew[0];
+    lrow[0][1] = lnew[1];
+  } else {
+    weights(0);
+    mma_s(1, fk[0]);
+  }
   load_v(0, fv[0]);
   load_k(1, fk[1]);
-  if (nkv == 1) mask_tail(0, 1);
+  if (!ONLINE && nkv == 1) mask_tail(0, 1);
   // steady state: stage i holds tiles 2i, 2i+1; iteration i reads stages i and i+1, stage i+2
   // is in flight since the previous iteration and stage i+3 is fetched now, into the slot of
   // stage i-1, which every wave finished reading before the previous barrier.  (Past the end
@@ -657,6 +721,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   lds_wait(fv[1], fk[0]);
   weights(1);
   mma_pv(0, fv[1]);
+  settle(1);
   mma_pv(1, fv[1]);
 
   float lsub[2];
@@ -665,12 +730,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const float lsum = lrow[sub][0] + lrow[sub][1];
     lsub[sub] = lsum + __shfl_xor(lsum, 32, 64);
   }
-  if (REF) {
-    // A row whose scores all lie ~60 binades or more below its reference (the bound is loose when
-    // no key is both long and aligned with the query) has lost its weights to underflow: the whole
-    // 256-query block is left to the running-maximum kernel, and nothing of it is written here
-    // (the output may alias the residual).
-    bool low = false;
+  if (ONLINE) {
+    // A row whose scores all lie ~60 binades or more below its wave's reference has lost its
+    // weights to underflow, and a reference beyond kRefUseful is not resolved: the whole
+    // 256-query block is left to the per-row kernel, and nothing of it is written here (the
+    // output may alias the residual).
+    bool low = over;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) low |= q0 + sub * 32 + ql < n && !(lsub[sub] >= 8.67e-19f);   // 2^-60
     if (__syncthreads_or(low)) {
@@ -1064,7 +1129,7 @@ __global__ __launch_bounds__(512) void k_attn_fp8(
 // query block, and k_attn_fp8 (running maximum) recomputes the flagged blocks afterwards.  With
 // q = k (the layer driver) every row has the weight 2^8.75 of its own key and nothing is flagged.
 //
-// Structure as k_attn_bf16_bounded with a 64-key stage in place of a 32-key tile (the FP8 MFMA
+// Structure as k_attn_bf16_main with a 64-key stage in place of a 32-key tile (the FP8 MFMA
 // contracts 64 keys at once): a wave owns two 32-query blocks half a stage apart,
 //   A(t): weights of block 0, stage t   ||  PV of block 1, stage t-1;  scores of block 1, stage t
 //   B(t): weights of block 1, stage t   ||  PV of block 0, stage t;    scores of block 0, stage t+1
@@ -1359,8 +1424,8 @@ size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype, int n_seq) {
   // the second-pass kernel, and the flags
   size_t total = 256 + 2 * align_up(per, 256);
   if (attn_dtype == LV_ATTN_FP8_E4M3) total += 2 * align_up(per, 256) + align_up(fp8_flag_words(heads, n_tokens) * 4, 256);
-  // bf16 without qk_norm: per (sequence, head) the largest |k|, then the flags of the first pass
-  else total += align_up(((size_t)heads * n_seq + fp8_flag_words(heads * n_seq, n_tokens)) * 4, 256);
+  // bf16: the flags of the online-softmax pass (one word per 256-query block)
+  else total += align_up(fp8_flag_words(heads * n_seq, n_tokens) * 4, 256);
   return total;
 }
 
@@ -1416,32 +1481,29 @@ int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_
   const size_t per = align_up((size_t)heads * n_seq * n_kt * 4 * kFragU4 * sizeof(u32x4), 256);
   u32x4 *kp = (u32x4 *)frag;
   u32x4 *vp = (u32x4 *)(frag + per);
-  // three ways: q, k normalised with exponents that stay in range: the branch-free kernel;
-  // q, k as given: the same kernel with a per-query reference from |q| and the head's largest
-  // |k|, then the running-maximum kernel on the blocks where that bound was too loose (normally
-  // none: its workgroups return at once); otherwise the running-maximum kernel alone
+  // two ways: q, k normalised with exponents that stay in range: the branch-free kernel with
+  // no reference; otherwise (q, k as given, or a softmax scale beyond that range) the same kernel
+  // as online softmax with a per-wave running reference, then the per-row kernel on the query
+  // blocks the first pass flagged (normally none: its workgroups return at once)
   const bool bounded = qk_norm && 64.25f * c <= 64.0f;
-  const bool by_ref = !qk_norm;
-  uint32_t *kmax = (uint32_t *)(frag + 2 * per);
-  uint32_t *redo = kmax + (size_t)heads * n_seq;
-  if (by_ref) {
-    const size_t words = (size_t)heads * n_seq + fp8_flag_words(heads * n_seq, n);
-    hipLaunchKernelGGL(k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, kmax, words);
+  uint32_t *redo = (uint32_t *)(frag + 2 * per);
+  if (!bounded) {
+    const size_t words = fp8_flag_words(heads * n_seq, n);
+    hipLaunchKernelGGL(k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, redo, words);
   }
   hipLaunchKernelGGL(k_attn_pack, dim3((unsigned)n_kt, (unsigned)(heads * n_seq)), dim3(256), 0, st,
-                     k, v, n, heads, n_kt, qk_norm, kp, vp, by_ref ? kmax : (uint32_t *)nullptr);
+                     k, v, n, heads, n_kt, qk_norm, kp, vp);
   if (after_pack && hipEventRecord(after_pack, st) != hipSuccess) return LV_ERR_HIP;
   const int nqb2 = (int)((n + kBQB - 1) / kBQB);
-  if (bounded)
-    hipLaunchKernelGGL(k_attn_bf16_bounded<false>, dim3((unsigned)(nqb2 * heads * n_seq)), dim3(256), 0,
-                       st, q, kp, vp, o, res, n, heads, n_seq, n_kt, nqb2, c, (const uint32_t *)nullptr,
-                       (uint32_t *)nullptr, 0);
-  if (by_ref)
-    hipLaunchKernelGGL(k_attn_bf16_bounded<true>, dim3((unsigned)(nqb2 * heads * n_seq)), dim3(256), 0,
-                       st, q, kp, vp, o, res, n, heads, n_seq, n_kt, nqb2, c, kmax, redo, 2 * nqb);
-  if (!bounded)
+  if (bounded) {
+    hipLaunchKernelGGL(k_attn_bf16_main<false>, dim3((unsigned)(nqb2 * heads * n_seq)), dim3(256), 0,
+                       st, q, kp, vp, o, res, n, heads, n_seq, n_kt, nqb2, c, qk_norm, (uint32_t *)nullptr, 0);
+  } else {
+    hipLaunchKernelGGL(k_attn_bf16_main<true>, dim3((unsigned)(nqb2 * heads * n_seq)), dim3(256), 0,
+                       st, q, kp, vp, o, res, n, heads, n_seq, n_kt, nqb2, c, qk_norm, redo, 2 * nqb);
     hipLaunchKernelGGL(k_attn_bf16, dim3((unsigned)(nqb * heads * n_seq)), dim3(512), 0, st, q, kp,
-                       vp, o, res, n, heads, n_seq, n_kt, nqb, c, qk_norm, by_ref ? redo : (const uint32_t *)nullptr);
+                       vp, o, res, n, heads, n_seq, n_kt, nqb, c, qk_norm, (const uint32_t *)redo);
+  }
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;
 }

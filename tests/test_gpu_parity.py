@@ -503,11 +503,14 @@ def _loose_bound_rows(rng, n_seq, n, heads):
 
 
 @pytest.mark.parametrize("scale", [1.0, 4.0])
-def test_global_attn_plain_qk_loose_score_bound(B, scale):
-    """Without qk_norm the kernel exponentiates every query against scale |q| max|k|.  Blocks in
-    which some row's scores all sit more than ~60 binades below that are recomputed with a running
-    maximum; scale 4 puts every block there, scale 1 only the blocks with ordinary queries next
-    to the long key.  Either way the result is the softmax of the definition."""
+def test_global_attn_plain_qk_rows_far_below_their_waves_reference(B, scale):
+    """Without qk_norm the main kernel runs online softmax with one running reference per wave of
+    64 queries.  One key is 40 times longer than the rest: a query aligned with it scores 100+
+    binades above its neighbours' best scores, whose weights underflow against the shared
+    reference; such 256-query blocks (and the block of the long key's own query, whose reference
+    passes the range the folded scale resolves) are flagged and redone by the per-row kernel.
+    Block 1 holds queries 50 times shorter, whose scores all lie within a few binades: it is the
+    one block the first pass finishes.  Either way the result is the softmax of the definition."""
     import torch
     n, heads = 1374, 3
     rng = np.random.default_rng(int(scale * 10))
@@ -525,15 +528,68 @@ def test_global_attn_plain_qk_loose_score_bound(B, scale):
     assert max_rel_err(got, ref) <= BF16_TOL
     if scale == 1.0:
         # flags of the first pass: one word per (head, 256-query block), rows of 2 * ceil(n / 512)
-        # words, behind the per-head largest |k|; block 1 (short queries) is the one not redone
+        # words, behind the packed K and V
         base = (ws.data_ptr() + 255) // 256 * 256 - ws.data_ptr() + 256
         per = (heads * 2 * ((n + 63) // 64) * 4 * 64 * 16 + 255) // 256 * 256
         stride = 2 * ((n + 511) // 512)
-        words = ws[base + 2 * per:base + 2 * per + (heads + heads * stride) * 4].cpu().numpy().view(np.uint32)
-        kmax = words[:heads].view(np.float32)
-        assert np.allclose(kmax, np.sqrt((qs.astype(np.float64) ** 2).sum(-1)).max(0), rtol=1e-5)
-        flags = words[heads:].reshape(heads, stride)[:, :6] != 0
-        assert np.array_equal(flags, np.array([[True, False, True, True, True, True]] * heads))
+        words = ws[base + 2 * per:base + 2 * per + heads * stride * 4].cpu().numpy().view(np.uint32)
+        flags = words.reshape(heads, stride)[:, :6] != 0
+        assert not flags[:, 1].any()                 # the short queries: done by the first pass
+        assert flags[:, 0].all()                     # the long key's own query: reference out of range
+        # spread of the best scores inside each wave of the other blocks, from the definition
+        s = np.einsum("qhd,khd->hqk", qs.astype(np.float64), qs.astype(np.float64)) * 0.125 * np.log2(np.e)
+        best = s.max(axis=2)                         # [head, query]
+        for hd in range(heads):
+            for blk in range(2, 6):
+                rows = best[hd, blk * 256:min(n, blk * 256 + 256)]
+                spread = max(np.ptp(rows[w:w + 64]) for w in range(0, len(rows), 64))
+                if spread > 70:
+                    assert flags[hd, blk], (hd, blk, spread)
+                elif spread < 50:
+                    assert not flags[hd, blk], (hd, blk, spread)
+
+
+def test_global_attn_online_softmax_reference_raised_many_times(B):
+    """Keys ordered so that every query's scores climb by ~400 binades along the sequence: the
+    per-wave reference of the online softmax is raised again and again (by both query blocks of
+    a wave, in the loop and in its ragged tail), with O, the row sums and the pending scores
+    rescaled each time.  With and without qk_norm's kernel choice (a softmax scale of 0.7 takes
+    normalised q, k out of the fixed-reference range)."""
+    import torch
+    n, heads = 1237, 2
+    rng = np.random.default_rng(91)
+    u = rng.choice([-1.0, 1.0], size=(1, heads, 64))
+    a = rng.uniform(0.95, 1.05, size=(n, heads, 1))        # best scores within ~20 binades inside a wave
+    ramp = np.linspace(-17.0, 17.0, n).reshape(n, 1, 1)
+    q = (u * a + 0.05 * rng.standard_normal((n, heads, 64))).astype(np.float32)
+    k = (u * ramp + 0.05 * rng.standard_normal((n, heads, 64))).astype(np.float32)
+    v = rng.standard_normal((n, heads, 64)).astype(np.float32)
+    bits = [synth.f32_to_bf16_bits(t.reshape(n, heads * 64)) for t in (q, k, v)]
+    qs, ks, vs = (synth.bf16_bits_to_f32(b).reshape(n, heads, 64) for b in bits)
+    s = np.einsum("qhd,khd->hqk", qs.astype(np.float64), ks.astype(np.float64)) * 0.125 * np.log2(np.e)
+    assert s[:, :, :32].max() < -140 and 150 < s.max() < 250         # a climb of ~300 binades, final reference in range
+    ph = B.make_params(1, 1, 1, heads * 64, heads, n_special=0)
+    ws = B.alloc_ws(B.litevggt_attn_ws_bytes(ph, n))
+    o = torch.zeros(n, heads * 64, dtype=torch.bfloat16, device="cuda")
+    B.litevggt_global_attn(ph, n, *(to_dev_bf16(b) for b in bits), o, ws)
+    torch.cuda.synchronize()
+    got = dev_bf16_to_f64(o).reshape(n, heads, 64)
+    assert np.all(np.isfinite(got))
+    assert max_rel_err(got, O.attention(qs, ks, vs)) <= BF16_TOL
+    base = (ws.data_ptr() + 255) // 256 * 256 - ws.data_ptr() + 256
+    per = (heads * 2 * ((n + 63) // 64) * 4 * 64 * 16 + 255) // 256 * 256
+    words = ws[base + 2 * per:base + 2 * per + heads * 2 * ((n + 511) // 512) * 4].cpu().numpy().view(np.uint32)
+    assert not words.any()                           # the first pass served every block itself
+    # normalised q, k with a scale beyond the fixed reference's range: scores up to 64 * 0.7 log2(e)
+    q2, k2, v2 = synth.random_qkv(n, heads, 64, seed=92, scale=3.0)
+    k2 = (q2 + 0.5 * k2).astype(np.float32)                      # some keys close to their queries
+    bits = [synth.f32_to_bf16_bits(t.reshape(n, heads * 64)) for t in (q2, k2, v2)]
+    ph = B.make_params(1, 1, 1, heads * 64, heads, n_special=0, qk_norm=1, softmax_scale=0.7)
+    B.litevggt_global_attn(ph, n, *(to_dev_bf16(b) for b in bits), o, ws)
+    torch.cuda.synchronize()
+    qs, ks, vs = (synth.bf16_bits_to_f32(b).reshape(n, heads, 64) for b in bits)
+    ref = O.attention(O.round_bf16(O.qk_normalize(qs)), O.round_bf16(O.qk_normalize(ks)), vs, scale=0.7)
+    assert max_rel_err(dev_bf16_to_f64(o).reshape(n, heads, 64), ref) <= BF16_TOL
 
 
 @pytest.mark.parametrize("attn,qk_norm", [("bf16", 0), ("bf16", 1), ("fp8", 0), ("fp8", 1)])
