@@ -700,20 +700,29 @@ def test_global_attn_fp8_random(B, n, heads, qk_norm):
     placement of the weights' quantisation points (the kernel rounds each weight relative to
     its running softmax reference, the emulation relative to the final row maximum: same noise
     level, different noise, 5e-2 here); with qk_norm both sides use the same fixed reference
-    and differ only where a score rounds differently in fp32 and float64 (2e-2).  Against exact
-    attention this input is the worst case for E4M3 weights: attention is nearly uniform, the
-    output is a small mean of many values (cancellation) while the 2^-4 relative rounding of
-    every weight does not cancel; kernel and emulation both land at 6-8e-2 here, so the bound
-    on this input is 1e-1 and the 6e-2 bar is checked on workload features below."""
+    and differ only where a score rounds differently in fp32 and float64 (2e-2).
+
+    Against exact attention the bar of the FP8 variant is 6e-2.  This input class is outside
+    what the recipe itself (q, k, v quantised per tensor to E4M3) can deliver, whatever computes
+    it: attention is nearly uniform, the output is a small mean of many values (cancellation),
+    and with the softmax weights kept exact in float64 the quantisation of q, k, v alone is
+    6.5e-2 .. 7.9e-2 from exact attention on these three cases (q and k alone: 5.2e-2 ..
+    6.7e-2).  That floor is computed here from the oracle and the kernel is held to it plus
+    1.5e-2 (the E4M3 weights add their own noise: measured 7.96e-2, 8.37e-2, ~6.5e-2); the 6e-2 bar is asserted on workload features (test_global_attn_fp8_workload_features
+    and the full-size test at 1000 frames)."""
     import torch
     q, k, v = synth.random_qkv(n, heads, 64, seed=300 + n, scale=1.3)
     bits = [synth.f32_to_bf16_bits(a.reshape(n, heads * 64)) for a in (q, k, v)]
     got, qs, ks, vs, ws = _fp8_case(B, *bits, n, heads, qk_norm)
     emu = O.attention_fp8_bounded(qs, ks, vs) if qk_norm else O.attention_fp8(qs, ks, vs)
     exact = O.attention(qs, ks, vs)
-    print(f"fp8 random n={n}: vs emulation {max_rel_err(got, emu):.2e}, vs exact {max_rel_err(got, exact):.2e}")
+    floor = max_rel_err(O.attention_fp8(qs, ks, vs, quantize_p=False), exact)   # exact weights, E4M3 q, k, v
+    err = max_rel_err(got, exact)
+    print(f"fp8 random n={n}: vs emulation {max_rel_err(got, emu):.2e}, vs exact {err:.2e}; "
+          f"the recipe with exact weights: {floor:.2e}")
     assert max_rel_err(got, emu) <= (2e-2 if qk_norm else 5e-2)
-    assert max_rel_err(got, exact) <= 1e-1 and max_rel_err(emu, exact) <= 1e-1
+    assert floor > FP8_TOL                       # the input quantisation alone is out of tolerance here
+    assert err <= floor + 1.5e-2 and max_rel_err(emu, exact) <= floor + 1.5e-2   # + the E4M3 weights' own noise
     # decode the first 32-key tile of K from the workspace
     base = (ws.data_ptr() + 255) // 256 * 256 - ws.data_ptr() + 256
     k8, _ = O.quantize_e4m3(ks)
@@ -754,8 +763,12 @@ def test_global_attn_fp8_rows_far_below_the_score_bound(B):
     bits = [synth.f32_to_bf16_bits(a.reshape(n, heads * 64).astype(np.float32)) for a in (q, k, v)]
     got, qs, ks, vs, ws = _fp8_case(B, *bits, n, heads, 1)
     exact = O.attention(qs, ks, vs)
-    assert max_rel_err(got[:400], exact[:400]) <= 1e-1      # near-uniform attention, see the test above
-    assert max_rel_err(got[400:], exact[400:]) <= 1e-1
+    # against exact attention: 6e-2, or, where the input quantisation alone (q, k, v in E4M3, weights
+    # exact) is already beyond that (near-uniform attention, see the test above), that floor + 1.5e-2
+    recipe = O.attention_fp8(qs, ks, vs, quantize_p=False)
+    for rows in (slice(0, 400), slice(400, n)):
+        floor = max_rel_err(recipe[rows], exact[rows])
+        assert max_rel_err(got[rows], exact[rows]) <= max(FP8_TOL, floor + 1.5e-2), (rows, floor)
     # rows 0 .. 399 are recomputed (with them the rest of their 256-row blocks, rows 400 .. 511)
     assert max_rel_err(got[:400], O.attention_fp8(qs, ks, vs)[:400]) <= 5e-2
     assert max_rel_err(got[512:], O.attention_fp8_bounded(qs, ks, vs)[512:]) <= 2e-2
