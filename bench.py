@@ -502,6 +502,27 @@ def main():
             variants[key] = dict(kernel=what, ms_call=ms_v, tflops=attn_flop / (ms_v * 1e-3) / 1e12,
                                  frac_mfma=attn_flop / (ms_v * 1e-3) / 1e12 / peak_v)
         del zv, yv
+        # the whole stack with the other setting of qk_norm (one step, not part of `value`): with
+        # q = k = v = the merged tokens as given, the residual stream doubles per layer and from
+        # the third layer on every score lies beyond the range the folded softmax scale resolves,
+        # so those layers run the online pass (which flags its blocks after the first key tile)
+        # and then the per-row kernel
+        p_other = mk(qk_norm=0 if wl_qk_norm else 1, attn_dtype=attn_dtype)
+        x.copy_(x0)
+        B.litevggt_layers_run(p_other, L, im, x, ib, grad, score, ws)
+        torch.cuda.synchronize()
+        ev_o = HipEvents(lib, n_ev)
+        x.copy_(x0)
+        t0 = time.perf_counter()
+        B.litevggt_layers_run(p_other, L, im, x, ib, grad, score, ws, events=ev_o.arr)
+        torch.cuda.synchronize()
+        other_ms = 1e3 * (time.perf_counter() - t0)
+        per_layer = [ev_o.ms(l * E + B.EV_ATTN_PACK_END, l * E + B.EV_ATTN_END) for l in range(L)]
+        ev_o.close()
+        variants["stack_with_qk_norm_%d" % (0 if wl_qk_norm else 1)] = dict(
+            ms_per_step=other_ms, tokens_per_s=N / (other_ms * 1e-3),
+            attn_ms_first_layers=[round(v, 2) for v in per_layer[:4]], attn_ms_last_layer=round(per_layer[-1], 2),
+            output_finite=bool(torch.isfinite(x.float()).all().item()))
 
     roof_kernel = ("k_attn_fp8_bounded" if args.attn_dtype == "fp8" and wl_qk_norm else "k_attn_fp8" if args.attn_dtype == "fp8"
                    else "k_attn_bf16_main<false>" if wl_qk_norm else "k_attn_bf16_main<true>")
