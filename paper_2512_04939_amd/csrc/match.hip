@@ -153,8 +153,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // memory round trip.  kInvBufs buffers in turn: stages are requested up to kGStages ahead,
     // which with one stage per tile (C = 32) is that many tiles not yet folded.
     float *inv_lds = (float *)(ring + (size_t)kGStages * kGStageU4) + wave * (kInvBufs * 64);
-    auto fetch = [&]() {
-      if (pf_s == 0 && pf_g < total) {
+    // fetch_part<0>: the inverse norms and fragments 0, 1 of the stage; fetch_part<1>: fragments
+    // 2, 3 and the bookkeeping.
+    auto fetch_part = [&](auto part) {
+      constexpr int P = decltype(part)::value;
+      if (P == 0 && pf_s == 0 && pf_g < total) {
         __builtin_amdgcn_global_load_lds(invd + (size_t)pf_tile * kGTile + wd * 64 + lane,
                                          inv_lds + (pf_t & (kInvBufs - 1)) * 64, 4, 0, 0);
         ++pf_t;
@@ -164,14 +167,20 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                          ((size_t)(tile * 8 + f_a0) * KS + (size_t)(pf_s * 2 + f_ks)) * 64 + lane;
       u32x4 *dst = ring + (size_t)(pf_g & (kGStages - 1)) * kGStageU4 + (size_t)(wave * 4) * 64;
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 2 * P; i < 2 * P + 2; ++i)
         __builtin_amdgcn_global_load_lds(src + (size_t)i * KS * 64, dst + i * 64, 16, 0, 0);
-      ++pf_g;
-      // past the end the last stage is fetched again (into a free slot nobody reads)
-      if (pf_g < total && ++pf_s == SPT) {
-        pf_s = 0;
-        pf_tile += n_lanes;
+      if (P == 1) {
+        ++pf_g;
+        // past the end the last stage is fetched again (into a free slot nobody reads)
+        if (pf_g < total && ++pf_s == SPT) {
+          pf_s = 0;
+          pf_tile += n_lanes;
+        }
       }
+    };
+    auto fetch = [&]() {
+      fetch_part(std::integral_constant<int, 0>{});
+      fetch_part(std::integral_constant<int, 1>{});
     };
     const uint32_t ring_lane = lds_addr(&ring[lane]);
     // byte offsets of this wave's fragments inside a stage, k-step 0: src (B operand) fragments
@@ -314,11 +323,16 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       __builtin_amdgcn_sched_barrier(0);
       mma_pair(fb[1], fa[1], 1);
       __builtin_amdgcn_sched_barrier(0);
-      fetch();                                                 // stage g+4 -> slot of stage g
+      // The stage's loads go out in two halves with an MFMA pair and the fragment reads between
+      // them: eight waves issuing all five loads at once right behind the barrier was measured
+      // 1 % slower.  (Anything moved ahead of the barrier, into k-step 0, costs 2-6 %.)
+      fetch_part(std::integral_constant<int, 0>{});            // stage g+4 -> slot of stage g, first half
       __builtin_amdgcn_sched_barrier(0);
       mma_pair(fb[1], fa[1], 2);
       __builtin_amdgcn_sched_barrier(0);
       read_frags(g + 1, 0, fb[0], fa[0]);                      // past the end: a stale slot, never used
+      __builtin_amdgcn_sched_barrier(0);
+      fetch_part(std::integral_constant<int, 1>{});            // second half
       __builtin_amdgcn_sched_barrier(0);
       mma_pair(fb[1], fa[1], 3);
       if (++sidx == SPT) {
