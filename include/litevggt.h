@@ -5,8 +5,9 @@
  *
  * Conventions (every entry point):
  *   - returns 0 (LV_OK) or a negative LV_ERR_* code; litevggt_strerror() names it.
- *     Arguments are validated on the host before anything is launched; on an error
- *     nothing has been enqueued.
+ *     Arguments are validated on the host before anything is launched: on an argument
+ *     error (every code but LV_ERR_HIP) nothing has been enqueued.  LV_ERR_HIP reports a
+ *     failed launch or event record; work enqueued before it stays enqueued.
  *   - pointers marked [device] are device memory owned by the caller; the library
  *     never allocates, frees or keeps them.  Pointers marked [host] are host memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only
@@ -218,11 +219,13 @@ int litevggt_merge(const litevggt_params *p, const void *x, const litevggt_index
  *   q,k,v [device] [n_tokens, heads, 64] bf16 (row stride dim); o likewise, out.
  *   n_tokens = M for the merged path, N for the unmerged baseline.
  * With qk_norm the scores use the per-head RMS-normalised q and k (see litevggt_params);
- * v is used as given.  The softmax reference is the largest score unit-RMS heads can reach
- * (qk_norm), or, for q and k as given, the bound softmax_scale * max|q| * max|k| of each 64
- * queries, with a running row maximum for the query blocks where that bound lies more than 60
- * binades above some row's scores.  Exponents are always taken from the difference to the
- * reference, so scores of any finite size give finite weights.
+ * v is used as given.  Normalised q and k whose scaled scores cannot leave the exponent range
+ * need no softmax reference at all; otherwise (q and k as given, or a large softmax_scale) the
+ * softmax is computed online: a running reference per wave of 64 queries, raised when a row sum
+ * shows that a score went far above it, with a running maximum per query row for the query
+ * blocks where rows lie more than 60 binades apart or scores exceed 256 in log2 units.
+ * Exponents are always taken from the difference to the reference, so scores of any finite
+ * size give finite weights.
  * attn_dtype LV_ATTN_FP8_E4M3 quantises q,k,v per tensor (scale = amax/448, amax taken in
  * this call) and the softmax weights to e4m3 for the MFMAs; accumulation and softmax stay
  * fp32.  Without qk_norm the weights are rounded relative to a running row maximum and

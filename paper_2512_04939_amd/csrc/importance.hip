@@ -307,9 +307,6 @@ int launch_var_map(const uint16_t *x, const Dims &d, int pool, float *psi_v, hip
     case 1:
       hipLaunchKernelGGL(k_var_map<1>, grid, dim3(128), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
       break;
-    case 3:
-      hipLaunchKernelGGL(k_var_map<3>, grid, dim3(128), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
-      break;
     case 5:
       hipLaunchKernelGGL(k_var_map<5>, grid, dim3(128), lds, st, x, d.F, d.H, d.W, d.S, d.C, psi_v);
       break;
