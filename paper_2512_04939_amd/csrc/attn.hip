@@ -649,6 +649,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   fetch(min(2, nkv - 1));                  // in flight during the prologue and the first iteration
+  if (q0 >= n) {
+    // All 64 queries of this wave lie beyond the sequence end (the ragged last block: 1374
+    // tokens per frame are 5.4 blocks).  The wave only moves its share of the K/V stages and
+    // keeps the workgroup's barriers company, leaving both pipes of its SIMD to the other
+    // workgroup resident there.
+    if (ONLINE && __syncthreads_or(0)) {     // the other waves' first-tile check
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      return;
+    }
+    for (int i = 0; i < nkv - 2; ++i) {
+      fslot = (i + 3) & (kBStages - 1);
+      foff = (size_t)min(i + 3, nkv - 1) * 8 * kFragU4 + tid;
+      fetch1(0);
+      fetch1(1);
+      fetch1(2);
+      asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      fetch1(3);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (ONLINE) __syncthreads_or(0);         // the other waves' final check
+    return;
+  }
   // prologue: scores of tile 0 for both blocks, weights of block 0, then V(0) and K(1)
   load_k(0, fk[0]);
   mma_s(0, fk[0]);
