@@ -21,26 +21,16 @@ namespace lv {
 // ---------------------------------------------------------------------------------------
 constexpr float kLnEps = 1e-6f;
 
+// one row: lane holds the 16-byte pieces lane, lane + 64, ... of x (and of add); o = the normalised row
 template <int CPL>
-__global__ __launch_bounds__(256) void k_layernorm(const uint16_t *__restrict__ x,
-                                                   const uint16_t *__restrict__ add,
-                                                   const float *__restrict__ gamma,
-                                                   const float *__restrict__ beta, int64_t M, int C,
-                                                   uint16_t *__restrict__ out) {
-  const int lane = threadIdx.x & 63, nch = C >> 3;
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= M) return;
+__device__ __forceinline__ void ln_row(const u32x4 (&w)[CPL], const u32x4 (&a)[CPL],
+                                       const float *__restrict__ gamma, const float *__restrict__ beta,
+                                       int lane, int nch, int C, u32x4 (&o)[CPL]) {
   float v[CPL][8];
   float sum = 0.f;
 #pragma unroll
   for (int c = 0; c < CPL; ++c) {
-    const int ch = lane + 64 * c;
-    u32x4 w = {0u, 0u, 0u, 0u}, a = {0u, 0u, 0u, 0u};
-    if (ch < nch) {
-      w = ((const u32x4 *)(x + (size_t)row * C))[ch];
-      if (add) a = ((const u32x4 *)(add + (size_t)row * C))[ch];
-    }
-    const uint32_t uw[4] = {w.x, w.y, w.z, w.w}, ua[4] = {a.x, a.y, a.z, a.w};
+    const uint32_t uw[4] = {w[c].x, w[c].y, w[c].z, w[c].w}, ua[4] = {a[c].x, a[c].y, a[c].z, a[c].w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       v[c][2 * i] = bf16_lo(uw[i]) + bf16_lo(ua[i]);
@@ -59,22 +49,117 @@ __global__ __launch_bounds__(256) void k_layernorm(const uint16_t *__restrict__ 
 #pragma unroll
   for (int c = 0; c < CPL; ++c) {
     const int ch = lane + 64 * c;
+    o[c] = u32x4{0u, 0u, 0u, 0u};
     if (ch < nch) {
       const f32x4 g0 = ((const f32x4 *)gamma)[2 * ch], g1 = ((const f32x4 *)gamma)[2 * ch + 1];
       const f32x4 b0 = ((const f32x4 *)beta)[2 * ch], b1 = ((const f32x4 *)beta)[2 * ch + 1];
-      u32x4 o;
-      o.x = pack_bf16((v[c][0] - mean) * rstd * g0[0] + b0[0], (v[c][1] - mean) * rstd * g0[1] + b0[1]);
-      o.y = pack_bf16((v[c][2] - mean) * rstd * g0[2] + b0[2], (v[c][3] - mean) * rstd * g0[3] + b0[3]);
-      o.z = pack_bf16((v[c][4] - mean) * rstd * g1[0] + b1[0], (v[c][5] - mean) * rstd * g1[1] + b1[1]);
-      o.w = pack_bf16((v[c][6] - mean) * rstd * g1[2] + b1[2], (v[c][7] - mean) * rstd * g1[3] + b1[3]);
-      ((u32x4 *)(out + (size_t)row * C))[ch] = o;
+      o[c].x = pack_bf16((v[c][0] - mean) * rstd * g0[0] + b0[0], (v[c][1] - mean) * rstd * g0[1] + b0[1]);
+      o[c].y = pack_bf16((v[c][2] - mean) * rstd * g0[2] + b0[2], (v[c][3] - mean) * rstd * g0[3] + b0[3]);
+      o[c].z = pack_bf16((v[c][4] - mean) * rstd * g1[0] + b1[0], (v[c][5] - mean) * rstd * g1[1] + b1[1]);
+      o[c].w = pack_bf16((v[c][6] - mean) * rstd * g1[2] + b1[2], (v[c][7] - mean) * rstd * g1[3] + b1[3]);
     }
   }
 }
 
+template <int CPL>
+__device__ __forceinline__ void ln_load(const uint16_t *__restrict__ x, const uint16_t *__restrict__ add,
+                                        int64_t row, int C, int lane, int nch, u32x4 (&w)[CPL], u32x4 (&a)[CPL]) {
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane + 64 * c;
+    w[c] = u32x4{0u, 0u, 0u, 0u};
+    a[c] = u32x4{0u, 0u, 0u, 0u};
+    if (ch < nch) {
+      w[c] = ((const u32x4 *)(x + (size_t)row * C))[ch];
+      if (add) a[c] = ((const u32x4 *)(add + (size_t)row * C))[ch];
+    }
+  }
+}
+
+template <int CPL>
+__global__ __launch_bounds__(256) void k_layernorm(const uint16_t *__restrict__ x,
+                                                   const uint16_t *__restrict__ add,
+                                                   const float *__restrict__ gamma,
+                                                   const float *__restrict__ beta, int64_t M, int C,
+                                                   uint16_t *__restrict__ out) {
+  const int lane = threadIdx.x & 63, nch = C >> 3;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  u32x4 w[CPL], a[CPL], o[CPL];
+  ln_load<CPL>(x, add, row, C, lane, nch, w, a);
+  ln_row<CPL>(w, a, gamma, beta, lane, nch, C, o);
+#pragma unroll
+  for (int c = 0; c < CPL; ++c)
+    if (lane + 64 * c < nch) ((u32x4 *)(out + (size_t)row * C))[lane + 64 * c] = o[c];
+}
+
+// The same LayerNorm with the result written as a linear layer's activation operand (the
+// fragment order k_pack_rows produces: [row / 32][k-step of 16 channels][lane = row % 32 + 32 *
+// (second 8 of the 16)], 16 bytes each).  A workgroup owns the 32 rows of one fragment row, a
+// wave 8 of them (their loads are all issued before the first row is reduced); the normalised
+// rows meet in LDS (row stride C * 2 + 16 bytes: the 32 rows a wave reads back at one channel
+// piece then lie in different banks) and leave as one contiguous run of 32 * C * 2 bytes.
+// Rows beyond M are written as zeros.
+template <int CPL>
+__global__ __launch_bounds__(256) void k_layernorm_packed(const uint16_t *__restrict__ x,
+                                                          const uint16_t *__restrict__ add,
+                                                          const float *__restrict__ gamma,
+                                                          const float *__restrict__ beta, int64_t M, int C,
+                                                          u32x4 *__restrict__ packed) {
+  extern __shared__ u32x4 ln_stage[];
+  constexpr int RB = CPL <= 2 ? 8 : 4;   // rows whose loads are in flight together
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nch = C >> 3, stride = nch + 1;
+#pragma unroll 1
+  for (int j0 = 0; j0 < 8; j0 += RB) {
+    u32x4 w[RB][CPL], a[RB][CPL];
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+      const int64_t row = (int64_t)blockIdx.x * 32 + wave * 8 + j0 + j;
+      ln_load<CPL>(x, add, row < M ? row : 0, C, lane, row < M ? nch : 0, w[j], a[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < RB; ++j) {
+      const int rr = wave * 8 + j0 + j;
+      u32x4 o[CPL];
+      ln_row<CPL>(w[j], a[j], gamma, beta, lane, nch, C, o);
+      const bool live = (int64_t)blockIdx.x * 32 + rr < M;
+#pragma unroll
+      for (int c = 0; c < CPL; ++c)
+        if (lane + 64 * c < nch) ln_stage[rr * stride + lane + 64 * c] = live ? o[c] : u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+  __syncthreads();
+  const int pieces = 32 * nch;   // = (C / 16) k-steps x 64 lanes
+  for (int p = threadIdx.x; p < pieces; p += 256) {
+    const int ks = p >> 6, lp = p & 63;
+    packed[(size_t)blockIdx.x * pieces + p] = ln_stage[(lp & 31) * stride + 2 * ks + (lp >> 5)];
+  }
+}
+
 static int launch_layernorm(const uint16_t *x, const uint16_t *add, const float *gamma,
-                            const float *beta, int64_t M, int C, uint16_t *out, hipStream_t st) {
+                            const float *beta, int64_t M, int C, uint16_t *out, hipStream_t st,
+                            u32x4 *packed = nullptr, int64_t Mp = 0) {
   const int cpl = (C / 8 + 63) / 64;
+  if (C % 16 != 0 || cpl > 4) return LV_ERR_SHAPE;
+  if (packed) {
+    if (Mp % 32 != 0 || Mp < M) return LV_ERR_SHAPE;
+    const size_t lds = (size_t)32 * (C / 8 + 1) * 16;
+    static std::atomic<uint64_t> lds_done[4];
+    const unsigned grid = (unsigned)(Mp / 32);
+    int rc;
+#define LV_LNP(CPL)                                                                                      \
+  if ((rc = allow_dynamic_lds((const void *)k_layernorm_packed<CPL>, lds, lds_done[CPL - 1]))) return rc; \
+  hipLaunchKernelGGL(k_layernorm_packed<CPL>, dim3(grid), dim3(256), lds, st, x, add, gamma, beta, M, C, packed)
+    switch (cpl) {
+      case 1: LV_LNP(1); break;
+      case 2: LV_LNP(2); break;
+      case 3: LV_LNP(3); break;
+      default: LV_LNP(4); break;
+    }
+#undef LV_LNP
+    LV_HIP_CHECK_LAUNCH();
+    return LV_OK;
+  }
   const unsigned grid = (unsigned)((M + 3) / 4);
 #define LV_LN(CPL) \
   hipLaunchKernelGGL(k_layernorm<CPL>, dim3(grid), dim3(256), 0, st, x, add, gamma, beta, M, C, out)
@@ -88,22 +173,6 @@ static int launch_layernorm(const uint16_t *x, const uint16_t *add, const float 
 #undef LV_LN
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;
-}
-
-// out = a + b, bf16, one rounding
-__global__ __launch_bounds__(256) void k_add_bf16(const u32x4 *__restrict__ a,
-                                                  const u32x4 *__restrict__ b, int64_t n16,
-                                                  u32x4 *__restrict__ out) {
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
-       i += (int64_t)gridDim.x * blockDim.x) {
-    const u32x4 x = a[i], y = b[i];
-    u32x4 o;
-    o.x = pack_bf16(bf16_lo(x.x) + bf16_lo(y.x), bf16_hi(x.x) + bf16_hi(y.x));
-    o.y = pack_bf16(bf16_lo(x.y) + bf16_lo(y.y), bf16_hi(x.y) + bf16_hi(y.y));
-    o.z = pack_bf16(bf16_lo(x.z) + bf16_lo(y.z), bf16_hi(x.z) + bf16_hi(y.z));
-    o.w = pack_bf16(bf16_lo(x.w) + bf16_lo(y.w), bf16_hi(x.w) + bf16_hi(y.w));
-    out[i] = o;
-  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -247,11 +316,11 @@ __device__ __forceinline__ float gelu_erf(float v) {
   return 0.5f * v * (v < 0.f ? erfc_abs : 2.0f - erfc_abs);
 }
 
-template <bool FP8>
+template <bool FP8, bool PACKED>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_bt(
     const u32x4 *__restrict__ ap, const u32x4 *__restrict__ wp, int64_t M, int KS, int nt_n,
     const float *__restrict__ bias, int gelu, uint16_t *__restrict__ out, int split,
-    const float *__restrict__ alpha_p, int n_tiles) {
+    const float *__restrict__ alpha_p, int n_tiles, const uint16_t *__restrict__ addend) {
   extern __shared__ u32x4 ring[];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -267,18 +336,22 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const bool by_xcd = (gridDim.x & (kXcd - 1)) == 0;
   const int my_rows = by_xcd ? (nt_m - xcd + kXcd - 1) / kXcd : 0;   // row tiles of this XCD
   const int my_tiles = by_xcd ? my_rows * nt_n : n_tiles;
-  for (int v = by_xcd ? (int)(blockIdx.x >> 3) : (int)blockIdx.x; v < my_tiles; v += by_xcd ? per_xcd : (int)gridDim.x) {
+  const int v_step = by_xcd ? per_xcd : (int)gridDim.x;
+  bool primed = false;   // PACKED: the previous tile's epilogue has issued this tile's first stages
+  int parity = 0;
+  for (int v = by_xcd ? (int)(blockIdx.x >> 3) : (int)blockIdx.x; v < my_tiles; v += v_step, parity ^= 1) {
   const int tn = v % nt_n, tm = by_xcd ? (v / nt_n) * kXcd + xcd : v / nt_n;
-  // this tile's 256 bias values wait in LDS behind the ring (read in the epilogue, many barriers later)
-  float *bias_lds = (float *)(ring + (size_t)kStages * kStageU4);
+  // this tile's 256 bias values wait in LDS behind the ring (read in the epilogue, many barriers
+  // later); two buffers in turn, so a wave still in the previous tile's epilogue reads its own
+  float *bias_lds = (float *)(ring + (size_t)kStages * kStageU4) + parity * kTile;
   if (tid < kTile) bias_lds[tid] = bias ? bias[tn * kTile + tid] : 0.f;
 
   // fetch: this wave moves fragments f = 4*wave .. 4*wave+3 of a stage (f = op*16 + ks*8 + a)
   const int f_op = wave >> 2, f_ks = (wave >> 1) & 1, f_a0 = (wave & 1) * 4;
-  int pf_g = 0;
+  int pf_g = 0, f_tm = tm, f_tn = tn;
   auto fetch = [&]() {
     const int s = pf_g < total ? pf_g : total - 1;   // past the end: the last stage again, into a free slot
-    const u32x4 *src = (f_op ? ap + (size_t)(tm * 8 + f_a0) * KS * 64 : wp + (size_t)(tn * 8 + f_a0) * KS * 64) +
+    const u32x4 *src = (f_op ? ap + (size_t)(f_tm * 8 + f_a0) * KS * 64 : wp + (size_t)(f_tn * 8 + f_a0) * KS * 64) +
                        (size_t)(s * 2 + f_ks) * 64 + lane;
     u32x4 *dst = ring + (size_t)(pf_g & (kStages - 1)) * kStageU4 + (size_t)(wave * 4) * 64;
 #pragma unroll
@@ -317,9 +390,15 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                                              acc[ai][bi], 0, 0, 0);
   };
 
+  if (PACKED && primed) {
+    pf_g = kStages;
+    // the stages were issued ahead of the previous epilogue's stores: wait for everything
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  } else {
 #pragma unroll
-  for (int i = 0; i < kStages; ++i) fetch();                 // stages 0..3
-  asm volatile("s_waitcnt vmcnt(12)" ::: "memory");          // stage 0 has landed (this wave's part)
+    for (int i = 0; i < kStages; ++i) fetch();               // stages 0..3
+    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");        // stage 0 has landed (this wave's part)
+  }
   __builtin_amdgcn_s_barrier();
   if constexpr (!FP8) {
     read_frags(0, 0, fb[0], fa[0]);
@@ -399,6 +478,53 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const float alpha = alpha_p ? *alpha_p : 1.0f;
   int anchor = 0;   // opaque zero: keeps the address arithmetic below inside this tile's epilogue
   asm volatile("" : "+v"(anchor));   // (hoisted out of the tile loop it would stay live through the main loop)
+  if constexpr (PACKED) {
+    // The output is the next linear layer's activation operand and is written in that kernel's
+    // fragment order straight from the accumulators: out[(row / 32) * KSn + k-step][lane], where
+    // a k-step is 16 of this layer's output channels and lane = row % 32 + 32 * (second 8 of
+    // the 16).  A lane holds, per group of four registers, channels 8g + 4h .. + 3 of its token:
+    // lanes l and l + 32 trade halves (one swap per register pair), after which lane l has
+    // channels 0-7 and lane l + 32 channels 8-15 of the k-step, and a wave stores 1 KB in a row.
+    // Nothing goes through LDS, so the next tile's first stages are issued before the arithmetic.
+    if (v + v_step < my_tiles) {
+      const int v2 = v + v_step;
+      f_tn = v2 % nt_n;
+      f_tm = by_xcd ? (v2 / nt_n) * kXcd + xcd : v2 / nt_n;
+      pf_g = 0;
+#pragma unroll
+      for (int i = 0; i < kStages; ++i) fetch();
+      primed = true;
+    } else {
+      primed = false;
+    }
+    const int KSn = nt_n * (kTile / 16);
+    u32x4 *op = (u32x4 *)out + ((size_t)(tm * 8 + wd * 2) * KSn + tn * (kTile / 16) + wn * 8) * 64 + lane + anchor;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int gp = 0; gp < 2; ++gp) {
+        const int ch0 = wn * 128 + 32 * b + 16 * gp + 4 * h;
+        const f32x4 bv0 = *(const f32x4 *)(bias_lds + ch0), bv1 = *(const f32x4 *)(bias_lds + ch0 + 8);
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+          float v0[4], v1[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            v0[i] = acc[a][b][8 * gp + i] + bv0[i];
+            v1[i] = acc[a][b][8 * gp + 4 + i] + bv1[i];
+            if (gelu) {
+              v0[i] = gelu_erf(v0[i]);
+              v1[i] = gelu_erf(v1[i]);
+            }
+          }
+          // first operand's lanes 32-63 <-> second operand's lanes 0-31
+          const auto s0 = __builtin_amdgcn_permlane32_swap(pack_bf16(v0[0], v0[1]), pack_bf16(v1[0], v1[1]), false, false);
+          const auto s1 = __builtin_amdgcn_permlane32_swap(pack_bf16(v0[2], v0[3]), pack_bf16(v1[2], v1[3]), false, false);
+          op[((size_t)a * KSn + 2 * b + gp) * 64] = u32x4{s0[0], s1[0], s0[1], s1[1]};
+        }
+      }
+    continue;
+  }
   const int tok = wd * 64 + (lane & 31) + anchor;
 #pragma unroll
   for (int b = 0; b < 4; ++b)
@@ -427,9 +553,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   for (int i = 0; i < 16; ++i) {
     const int c = i * 512 + tid + anchor, mrow = c >> 5, piece = c & 31;
     const int64_t m = (int64_t)tm * kTile + mrow;
-    if (m < M)
-      *(u32x4 *)(ob + (size_t)m * split + piece * 8) =
-          *(const u32x4 *)(tile + (size_t)mrow * (kTile * 2) + ((piece ^ (mrow & 7)) << 4));
+    if (m < M) {
+      u32x4 t = *(const u32x4 *)(tile + (size_t)mrow * (kTile * 2) + ((piece ^ (mrow & 7)) << 4));
+      if (addend) {   // out = addend + (this layer's output, already rounded to bf16): one more rounding
+        const u32x4 y = *(const u32x4 *)(addend + (ob - out) + (size_t)m * split + piece * 8);
+        t.x = pack_bf16(bf16_lo(t.x) + bf16_lo(y.x), bf16_hi(t.x) + bf16_hi(y.x));
+        t.y = pack_bf16(bf16_lo(t.y) + bf16_lo(y.y), bf16_hi(t.y) + bf16_hi(y.y));
+        t.z = pack_bf16(bf16_lo(t.z) + bf16_lo(y.z), bf16_hi(t.z) + bf16_hi(y.z));
+        t.w = pack_bf16(bf16_lo(t.w) + bf16_lo(y.w), bf16_hi(t.w) + bf16_hi(y.w));
+      }
+      *(u32x4 *)(ob + (size_t)m * split + piece * 8) = t;
+    }
   }
   __syncthreads();   // the transposed tile has been read: the ring may be refilled
   }   // tiles
@@ -437,7 +571,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
 // ---------------------------------------------------------------------------------------
 struct BlockWs {
-  uint16_t *h, *qkv, *a, *u1, *u2, *h3;
+  uint16_t *h, *qkv, *a, *u1, *h3;
   u32x4 *apack, *wpack;
   uint32_t *fp8sc;
   void *attn;
@@ -458,9 +592,8 @@ static BlockWs carve_block(int64_t M, int C, int heads, int attn_dtype, char *ba
   w.qkv = (uint16_t *)take((size_t)3 * M * C * 2);
   w.a = (uint16_t *)take((size_t)M * C * 2);
   w.u1 = (uint16_t *)take((size_t)M * C * 2);
-  w.u2 = (uint16_t *)take((size_t)M * C * 2);
-  w.h3 = (uint16_t *)take((size_t)M * 4 * C * 2);
-  w.apack = (u32x4 *)take((size_t)w.Mp * 4 * C * 2);
+  w.h3 = (uint16_t *)take((size_t)w.Mp * 4 * C * 2);   // row-major (FP8 layers) or in fragment order (bf16 layers)
+  w.apack = (u32x4 *)take((size_t)w.Mp * 4 * C);       // a layer's activation operand: bf16 with K = C, FP8 with K <= 4C
   w.wpack = (u32x4 *)take((size_t)4 * C * C * 2);
   w.fp8sc = (uint32_t *)take(kFp8Words * sizeof(uint32_t));
   w.attn = take(attn_ws_bytes(heads, M, attn_dtype));
@@ -474,17 +607,25 @@ size_t block_ws_bytes(int64_t M, int C, int heads, int attn_dtype) {
 
 // Y = A W^T + bias: packs both operands (FP8: after taking their amax and quantising them),
 // then the tiled kernel.  fp8_state: the layer's delayed-scaling state, or NULL.
+// bf16 layers only: `a_packed` (the activation operand already in fragment order, A unused),
+// `pack_out` (out receives the result in fragment order for a layer with K = Nout, padded rows
+// included: Mp x Nout elements), `addend` (row-major, same shape as out: out = addend + result).
 static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W, int Nout,
                          const float *bias, int gelu, uint16_t *out, int split, BlockWs &w,
-                         hipStream_t st, bool fp8 = false, float *fp8_state = nullptr) {
+                         hipStream_t st, bool fp8 = false, float *fp8_state = nullptr,
+                         const u32x4 *a_packed = nullptr, bool pack_out = false,
+                         const uint16_t *addend = nullptr) {
+  if (fp8 && (a_packed || pack_out)) return LV_ERR_PARAM;
+  if (pack_out && (addend || split != Nout)) return LV_ERR_PARAM;
   if (K % 64 != 0 || Nout % kTile != 0 || split % kTile != 0 || Nout % split != 0) return LV_ERR_SHAPE;
   int rc;
   // the ring; the epilogue's output tile (256 rows of 512 bytes) has the same size
   static_assert((size_t)kTile * kTile * 2 <= (size_t)kStages * kStageU4 * 16, "output tile must fit the ring");
-  const size_t lds = (size_t)kStages * kStageU4 * 16 + kTile * sizeof(float);   // + a tile's bias values
-  static std::atomic<uint64_t> lds_done[2];
-  if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<false>, lds, lds_done[0]))) return rc;
-  if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<true>, lds, lds_done[1]))) return rc;
+  const size_t lds = (size_t)kStages * kStageU4 * 16 + 2 * kTile * sizeof(float);   // + two tiles' bias values
+  static std::atomic<uint64_t> lds_done[3];
+  if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<false, false>, lds, lds_done[0]))) return rc;
+  if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<true, false>, lds, lds_done[1]))) return rc;
+  if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<false, true>, lds, lds_done[2]))) return rc;
   const int nt_n = Nout / kTile;
   const int64_t nt_m = w.Mp / kTile;
   if (nt_m * nt_n >= ((int64_t)1 << 31) || w.Mp >= ((int64_t)1 << 31)) return LV_ERR_SHAPE;
@@ -512,13 +653,20 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
     quant(A, M, w.Mp, w.fp8sc + 2, w.apack, fp8_state ? w.fp8sc : (uint32_t *)nullptr);
     quant(W, Nout, Nout, w.fp8sc + 3, w.wpack, (uint32_t *)nullptr);
     if (fp8_state) hipLaunchKernelGGL(k_fp8_record, dim3(1), dim3(64), 0, st, w.fp8sc, fp8_state);
-    hipLaunchKernelGGL(k_gemm_bt<true>, dim3(grid), dim3(512), lds, st, w.apack, w.wpack,
-                       M, K / 32, nt_n, bias, gelu, out, split, (const float *)(w.fp8sc + 4), n_tiles);
+    hipLaunchKernelGGL((k_gemm_bt<true, false>), dim3(grid), dim3(512), lds, st, w.apack, w.wpack,
+                       M, K / 32, nt_n, bias, gelu, out, split, (const float *)(w.fp8sc + 4), n_tiles, addend);
   } else {
-    if ((rc = launch_pack_rows(A, M, w.Mp, K, w.apack, st))) return rc;
+    if (!a_packed) {
+      if ((rc = launch_pack_rows(A, M, w.Mp, K, w.apack, st))) return rc;
+      a_packed = w.apack;
+    }
     if ((rc = launch_pack_rows(W, Nout, Nout, K, w.wpack, st))) return rc;
-    hipLaunchKernelGGL(k_gemm_bt<false>, dim3(grid), dim3(512), lds, st, w.apack, w.wpack,
-                       M, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr, n_tiles);
+    if (pack_out)
+      hipLaunchKernelGGL((k_gemm_bt<false, true>), dim3(grid), dim3(512), lds, st, a_packed, w.wpack,
+                         M, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr, n_tiles, addend);
+    else
+      hipLaunchKernelGGL((k_gemm_bt<false, false>), dim3(grid), dim3(512), lds, st, a_packed, w.wpack,
+                         M, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr, n_tiles, addend);
   }
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;
@@ -534,25 +682,25 @@ int launch_global_block(const uint16_t *z, int64_t M, int C, int heads, float sc
   auto state = [&](int layer) -> float * {   // delayed scaling: this layer's history
     return f8 && bw.fp8_recipe == LV_FP8_DELAYED ? (float *)bw.fp8_state + layer * (LV_FP8_HISTORY + 2) : nullptr;
   };
-  if ((rc = launch_layernorm(z, nullptr, bw.ln1_g, bw.ln1_b, M, C, w.h, st))) return rc;
-  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_qkv, 3 * C, bw.b_qkv, 0, w.qkv, C, w, st, f8, state(0))))
+  // bf16 layers: the LayerNorms write their result in the following layer's operand order
+  u32x4 *const ln_packed = f8 ? nullptr : w.apack;
+  if ((rc = launch_layernorm(z, nullptr, bw.ln1_g, bw.ln1_b, M, C, w.h, st, ln_packed, w.Mp))) return rc;
+  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_qkv, 3 * C, bw.b_qkv, 0, w.qkv, C, w, st, f8, state(0),
+                          ln_packed)))
     return rc;
   const uint16_t *q = w.qkv, *k = w.qkv + (size_t)M * C, *v = w.qkv + (size_t)2 * M * C;
   if ((rc = launch_attn(q, k, v, w.a, M, heads, scale, attn_dtype, qk_norm, w.attn, st, after_pack)))
     return rc;
   if (after_attn && hipEventRecord(after_attn, st) != hipSuccess) return LV_ERR_HIP;
   if ((rc = launch_linear(w.a, M, C, (const uint16_t *)bw.w_o, C, bw.b_o, 0, w.u1, C, w, st, f8, state(1)))) return rc;
-  if ((rc = launch_layernorm(z, w.u1, bw.ln2_g, bw.ln2_b, M, C, w.h, st))) return rc;
-  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_1, 4 * C, bw.b_1, 1, w.h3, 4 * C, w, st, f8, state(2))))
+  if ((rc = launch_layernorm(z, w.u1, bw.ln2_g, bw.ln2_b, M, C, w.h, st, ln_packed, w.Mp))) return rc;
+  // bf16 layers: the first MLP layer writes its output in the second one's operand order; the
+  // second one's epilogue adds u1 (delta = u1 + u2, u2 rounded to bf16 first as if it were stored)
+  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_1, 4 * C, bw.b_1, 1, w.h3, 4 * C, w, st, f8, state(2),
+                          ln_packed, !f8)))
     return rc;
-  if ((rc = launch_linear(w.h3, M, 4 * C, (const uint16_t *)bw.w_2, C, bw.b_2, 0, w.u2, C, w, st, f8, state(3))))
-    return rc;
-  const int64_t n16 = M * C / 8;
-  const unsigned grid = (unsigned)(((n16 + 255) / 256) < 65536 ? ((n16 + 255) / 256) : 65536);
-  hipLaunchKernelGGL(k_add_bf16, dim3(grid), dim3(256), 0, st, (const u32x4 *)w.u1, (const u32x4 *)w.u2,
-                     n16, (u32x4 *)delta);
-  LV_HIP_CHECK_LAUNCH();
-  return LV_OK;
+  return launch_linear(w.h3, M, 4 * C, (const uint16_t *)bw.w_2, C, bw.b_2, 0, delta, C, w, st, f8, state(3),
+                       f8 ? nullptr : (const u32x4 *)w.h3, false, w.u1);
 }
 
 }  // namespace lv
