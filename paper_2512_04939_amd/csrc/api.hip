@@ -82,6 +82,7 @@ size_t importance_ws_bytes(const Dims &d) { return align_up((size_t)d.F * d.P * 
 // driver scratch: z and y [M,C] bf16, then the larger of the per-op scratches
 size_t driver_ws_bytes(const litevggt_params *p, const Dims &d, const litevggt_plan_t &pl) {
   size_t zy = 2 * align_up((size_t)pl.M * d.C * 2, 256);
+  if (p->block) zy += block_wpack_bytes(d.C);   // the block's weights in operand order, kept across the layers
   size_t op = importance_ws_bytes(d);
   size_t m = match_ws_bytes(d, pl);
   if (m > op) op = m;
@@ -317,7 +318,8 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
   const size_t zy = align_up((size_t)pl.M * d.C * 2, 256);
   uint16_t *z = (uint16_t *)ws;
   uint16_t *y = (uint16_t *)((char *)ws + zy);
-  void *op_ws = (char *)ws + 2 * zy;
+  void *wpack = (char *)ws + 2 * zy;   // block only: the weights in operand order, written by the first layer
+  void *op_ws = (char *)wpack + (p->block ? block_wpack_bytes(d.C) : 0);
   uint16_t *xx = (uint16_t *)x;
   for (int l = 0; l < n_layers; ++l) {
     const bool refresh = (l % p->refresh_interval) == 0;
@@ -358,7 +360,7 @@ int litevggt_layers_run(const litevggt_params *p, int n_layers, const void *imag
     if (p->block) {
       rc = launch_global_block(z, pl.M, d.C, d.heads, scale_of(p), p->attn_dtype, p->qk_norm,
                                *p->block, y, op_ws, st, ev ? ev[LV_EV_ATTN_PACK_END] : nullptr,
-                               ev ? ev[LV_EV_ATTN_END] : nullptr);
+                               ev ? ev[LV_EV_ATTN_END] : nullptr, wpack, l > 0);
       if (rc) return rc;
     } else {
       rc = launch_attn(z, z, z, y, pl.M, d.heads, scale_of(p), p->attn_dtype, p->qk_norm, op_ws, st,

@@ -406,7 +406,10 @@ constexpr float kSumRaise = 1.0995116e12f;   // 2^40: a row sum beyond it raises
 constexpr int kBStages = 4;          // LDS ring of 64-key K/V stages
 
 
-template <bool ONLINE>
+// PACKED (one sequence, no residual, not ONLINE): `o` is a linear layer's activation operand
+// buffer and receives the output rows in that layer's fragment order, [row / 32][k-step of 16
+// channels][lane = row % 32 + 32 * (second 8 of the 16)], 16 bytes each.
+template <bool ONLINE, bool PACKED = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_bf16_main(
     const uint16_t *q, const u32x4 *__restrict__ kp, const u32x4 *__restrict__ vp, uint16_t *o,
     const uint16_t *res, int64_t n, int heads, int n_seq, int n_kt, int nqb, float c, int qk_norm,
@@ -765,6 +768,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       if (tid == 0) redo[(size_t)sh * redo_stride + qb] = 1u;
       return;
     }
+  }
+  if constexpr (PACKED) {
+    // a lane holds channels 8g + 4h .. + 3 of its query per group of four registers: lanes l and
+    // l + 32 trade halves (first operand's lanes 32-63 <-> second operand's lanes 0-31), after
+    // which lane l has channels 0-7 and lane l + 32 channels 8-15 of a k-step: 1 KB per store
+    u32x4 *op = (u32x4 *)o;
+    const int KS = C >> 4;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      const bool live = q0 + sub * 32 + ql < n;
+      const float inv = live ? 1.0f / lsub[sub] : 0.f;
+      const size_t base = ((size_t)((q0 + sub * 32) >> 5) * KS + head * 4) * 64 + lane;
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int gp = 0; gp < 2; ++gp) {
+          float r[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) r[i] = live ? oacc[sub][dt][8 * gp + i] * inv : 0.f;
+          const auto s0 = __builtin_amdgcn_permlane32_swap(pack_bf16(r[0], r[1]), pack_bf16(r[4], r[5]), false, false);
+          const auto s1 = __builtin_amdgcn_permlane32_swap(pack_bf16(r[2], r[3]), pack_bf16(r[6], r[7]), false, false);
+          op[base + (size_t)(dt * 2 + gp) * 64] = u32x4{s0[0], s1[0], s0[1], s1[1]};
+        }
+    }
+    return;
   }
 #pragma unroll
   for (int sub = 0; sub < 2; ++sub) {
@@ -1458,7 +1486,9 @@ size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype, int n_seq) {
 // rows it writes and nothing else of them) are supported by the bf16 kernels only.
 int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_t *o,
                 int64_t n, int heads, float scale, int attn_dtype, int qk_norm, void *ws,
-                hipStream_t st, hipEvent_t after_pack, int n_seq, const uint16_t *res) {
+                hipStream_t st, hipEvent_t after_pack, int n_seq, const uint16_t *res,
+                void *o_packed, bool *wrote_packed) {
+  if (wrote_packed) *wrote_packed = false;
   if (n_seq < 1 || (int64_t)heads * n_seq > 65535) return LV_ERR_SHAPE;
   if ((n_seq > 1 || res) && attn_dtype != LV_ATTN_BF16) return LV_ERR_DTYPE;
   const int n_kt = n_key_tiles(n);
@@ -1518,7 +1548,12 @@ int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_
                      k, v, n, heads, n_kt, qk_norm, kp, vp);
   if (after_pack && hipEventRecord(after_pack, st) != hipSuccess) return LV_ERR_HIP;
   const int nqb2 = (int)((n + kBQB - 1) / kBQB);
-  if (bounded) {
+  if (bounded && o_packed && wrote_packed && n_seq == 1 && !res) {
+    hipLaunchKernelGGL((k_attn_bf16_main<false, true>), dim3((unsigned)(nqb2 * heads)), dim3(256), 0,
+                       st, q, kp, vp, (uint16_t *)o_packed, res, n, heads, n_seq, n_kt, nqb2, c, qk_norm,
+                       (uint32_t *)nullptr, 0);
+    *wrote_packed = true;
+  } else if (bounded) {
     hipLaunchKernelGGL(k_attn_bf16_main<false>, dim3((unsigned)(nqb2 * heads * n_seq)), dim3(256), 0,
                        st, q, kp, vp, o, res, n, heads, n_seq, n_kt, nqb2, c, qk_norm, (uint32_t *)nullptr, 0);
   } else {

@@ -579,6 +579,9 @@ struct BlockWs {
   int64_t Mp;
 };
 
+// the four weight matrices in operand order, one after the other (qkv, output, MLP 1, MLP 2)
+size_t block_wpack_bytes(int C) { return align_up((size_t)12 * C * C * 2, 256); }
+
 static BlockWs carve_block(int64_t M, int C, int heads, int attn_dtype, char *base) {
   BlockWs w;
   size_t off = 0;
@@ -594,7 +597,7 @@ static BlockWs carve_block(int64_t M, int C, int heads, int attn_dtype, char *ba
   w.u1 = (uint16_t *)take((size_t)M * C * 2);
   w.h3 = (uint16_t *)take((size_t)w.Mp * 4 * C * 2);   // row-major (FP8 layers) or in fragment order (bf16 layers)
   w.apack = (u32x4 *)take((size_t)w.Mp * 4 * C);       // a layer's activation operand: bf16 with K = C, FP8 with K <= 4C
-  w.wpack = (u32x4 *)take((size_t)4 * C * C * 2);
+  w.wpack = (u32x4 *)take(block_wpack_bytes(C));
   w.fp8sc = (uint32_t *)take(kFp8Words * sizeof(uint32_t));
   w.attn = take(attn_ws_bytes(heads, M, attn_dtype));
   w.bytes = off;
@@ -614,7 +617,9 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
                          const float *bias, int gelu, uint16_t *out, int split, BlockWs &w,
                          hipStream_t st, bool fp8 = false, float *fp8_state = nullptr,
                          const u32x4 *a_packed = nullptr, bool pack_out = false,
-                         const uint16_t *addend = nullptr) {
+                         const uint16_t *addend = nullptr, u32x4 *w_packed = nullptr, bool pack_w = true) {
+  if (!w_packed) w_packed = w.wpack;
+  if (fp8 && !pack_w) return LV_ERR_PARAM;
   if (fp8 && (a_packed || pack_out)) return LV_ERR_PARAM;
   if (pack_out && (addend || split != Nout)) return LV_ERR_PARAM;
   if (K % 64 != 0 || Nout % kTile != 0 || split % kTile != 0 || Nout % split != 0) return LV_ERR_SHAPE;
@@ -651,21 +656,21 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
     amax(W, (int64_t)Nout * (K / 8), w.fp8sc + 1);
     hipLaunchKernelGGL(k_fp8_scales, dim3(1), dim3(64), 0, st, w.fp8sc, (const float *)fp8_state);
     quant(A, M, w.Mp, w.fp8sc + 2, w.apack, fp8_state ? w.fp8sc : (uint32_t *)nullptr);
-    quant(W, Nout, Nout, w.fp8sc + 3, w.wpack, (uint32_t *)nullptr);
+    quant(W, Nout, Nout, w.fp8sc + 3, w_packed, (uint32_t *)nullptr);
     if (fp8_state) hipLaunchKernelGGL(k_fp8_record, dim3(1), dim3(64), 0, st, w.fp8sc, fp8_state);
-    hipLaunchKernelGGL((k_gemm_bt<true, false>), dim3(grid), dim3(512), lds, st, w.apack, w.wpack,
+    hipLaunchKernelGGL((k_gemm_bt<true, false>), dim3(grid), dim3(512), lds, st, w.apack, w_packed,
                        M, K / 32, nt_n, bias, gelu, out, split, (const float *)(w.fp8sc + 4), n_tiles, addend);
   } else {
     if (!a_packed) {
       if ((rc = launch_pack_rows(A, M, w.Mp, K, w.apack, st))) return rc;
       a_packed = w.apack;
     }
-    if ((rc = launch_pack_rows(W, Nout, Nout, K, w.wpack, st))) return rc;
+    if (pack_w && (rc = launch_pack_rows(W, Nout, Nout, K, w_packed, st))) return rc;
     if (pack_out)
-      hipLaunchKernelGGL((k_gemm_bt<false, true>), dim3(grid), dim3(512), lds, st, a_packed, w.wpack,
+      hipLaunchKernelGGL((k_gemm_bt<false, true>), dim3(grid), dim3(512), lds, st, a_packed, w_packed,
                          M, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr, n_tiles, addend);
     else
-      hipLaunchKernelGGL((k_gemm_bt<false, false>), dim3(grid), dim3(512), lds, st, a_packed, w.wpack,
+      hipLaunchKernelGGL((k_gemm_bt<false, false>), dim3(grid), dim3(512), lds, st, a_packed, w_packed,
                          M, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr, n_tiles, addend);
   }
   LV_HIP_CHECK_LAUNCH();
@@ -674,11 +679,18 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
 
 int launch_global_block(const uint16_t *z, int64_t M, int C, int heads, float scale, int attn_dtype,
                         int qk_norm, const litevggt_block_weights &bw, uint16_t *delta, void *ws,
-                        hipStream_t st, hipEvent_t after_pack, hipEvent_t after_attn) {
+                        hipStream_t st, hipEvent_t after_pack, hipEvent_t after_attn, void *wpack_keep,
+                        bool wpack_ready) {
   if (C % kTile != 0) return LV_ERR_SHAPE;
   BlockWs w = carve_block(M, C, heads, attn_dtype, (char *)ws);
   int rc;
   const bool f8 = bw.linear_dtype == LV_LINEAR_FP8_E4M3;
+  // the weights in operand order: in the workspace, or (bf16 layers) in a buffer of the caller's
+  // that outlives the call and may already hold them
+  u32x4 *const wp = !f8 && wpack_keep ? (u32x4 *)wpack_keep : w.wpack;
+  const bool pack_w = !(wp == wpack_keep && wpack_ready);
+  const size_t cc16 = (size_t)C * C * 2 / 16;
+  u32x4 *const wp_qkv = wp, *const wp_o = wp + 3 * cc16, *const wp_1 = wp + 4 * cc16, *const wp_2 = wp + 8 * cc16;
   auto state = [&](int layer) -> float * {   // delayed scaling: this layer's history
     return f8 && bw.fp8_recipe == LV_FP8_DELAYED ? (float *)bw.fp8_state + layer * (LV_FP8_HISTORY + 2) : nullptr;
   };
@@ -686,21 +698,26 @@ int launch_global_block(const uint16_t *z, int64_t M, int C, int heads, float sc
   u32x4 *const ln_packed = f8 ? nullptr : w.apack;
   if ((rc = launch_layernorm(z, nullptr, bw.ln1_g, bw.ln1_b, M, C, w.h, st, ln_packed, w.Mp))) return rc;
   if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_qkv, 3 * C, bw.b_qkv, 0, w.qkv, C, w, st, f8, state(0),
-                          ln_packed)))
+                          ln_packed, false, nullptr, wp_qkv, pack_w)))
     return rc;
   const uint16_t *q = w.qkv, *k = w.qkv + (size_t)M * C, *v = w.qkv + (size_t)2 * M * C;
-  if ((rc = launch_attn(q, k, v, w.a, M, heads, scale, attn_dtype, qk_norm, w.attn, st, after_pack)))
+  // bf16 layers: where the attention kernel can, it writes the output projection's operand itself
+  bool a_is_packed = false;
+  if ((rc = launch_attn(q, k, v, w.a, M, heads, scale, attn_dtype, qk_norm, w.attn, st, after_pack, 1, nullptr,
+                        f8 ? nullptr : (void *)w.apack, &a_is_packed)))
     return rc;
   if (after_attn && hipEventRecord(after_attn, st) != hipSuccess) return LV_ERR_HIP;
-  if ((rc = launch_linear(w.a, M, C, (const uint16_t *)bw.w_o, C, bw.b_o, 0, w.u1, C, w, st, f8, state(1)))) return rc;
+  if ((rc = launch_linear(w.a, M, C, (const uint16_t *)bw.w_o, C, bw.b_o, 0, w.u1, C, w, st, f8, state(1),
+                          a_is_packed ? w.apack : nullptr, false, nullptr, wp_o, pack_w)))
+    return rc;
   if ((rc = launch_layernorm(z, w.u1, bw.ln2_g, bw.ln2_b, M, C, w.h, st, ln_packed, w.Mp))) return rc;
   // bf16 layers: the first MLP layer writes its output in the second one's operand order; the
   // second one's epilogue adds u1 (delta = u1 + u2, u2 rounded to bf16 first as if it were stored)
   if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_1, 4 * C, bw.b_1, 1, w.h3, 4 * C, w, st, f8, state(2),
-                          ln_packed, !f8)))
+                          ln_packed, !f8, nullptr, wp_1, pack_w)))
     return rc;
   return launch_linear(w.h3, M, 4 * C, (const uint16_t *)bw.w_2, C, bw.b_2, 0, delta, C, w, st, f8, state(3),
-                       f8 ? nullptr : (const u32x4 *)w.h3, false, w.u1);
+                       f8 ? nullptr : (const u32x4 *)w.h3, false, w.u1, wp_2, pack_w);
 }
 
 }  // namespace lv

@@ -61,12 +61,16 @@ int launch_pack_rows(const uint16_t *x, int64_t n, int64_t n_pad, int C, void *p
 
 // block.hip
 size_t block_ws_bytes(int64_t M, int C, int heads, int attn_dtype);
+size_t block_wpack_bytes(int C);
 // delta = Block(z) - z for M tokens; the two events (optional) are recorded around the
-// attention kernel inside the block
+// attention kernel inside the block.  wpack_keep (optional, block_wpack_bytes(C), bf16 layers
+// only): receives the weights in the linear kernel's operand order, or, with wpack_ready,
+// already holds them from an earlier call with the same weights.
 int launch_global_block(const uint16_t *z, int64_t M, int C, int heads, float scale, int attn_dtype,
                         int qk_norm, const litevggt_block_weights &bw, uint16_t *delta, void *ws,
                         hipStream_t st, hipEvent_t after_pack = nullptr,
-                        hipEvent_t after_attn = nullptr);
+                        hipEvent_t after_attn = nullptr, void *wpack_keep = nullptr,
+                        bool wpack_ready = false);
 
 // merge.hip
 int launch_merge(const uint16_t *x, const Dims &d, int64_t M, const litevggt_index &ix,
@@ -77,10 +81,13 @@ int launch_unmerge(const uint16_t *y, const Dims &d, const litevggt_index &ix,
 // attn.hip
 size_t attn_ws_bytes(int heads, int64_t n_tokens, int attn_dtype, int n_seq = 1);
 // `after_pack`, when not NULL, is recorded between the K/V re-layout and the main kernel;
-// n_seq sequences of n_tokens each; res: optional residual added to the output
+// n_seq sequences of n_tokens each; res: optional residual added to the output.  o_packed
+// (optional, with wrote_packed): a linear layer's activation operand buffer for align_up(n_tokens,
+// 256) rows; when the bf16 fixed-reference kernel runs it writes the output there in that
+// layer's fragment order instead of to o, and *wrote_packed tells whether it did.
 int launch_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, uint16_t *o,
                 int64_t n_tokens, int heads, float scale, int attn_dtype, int qk_norm, void *ws,
                 hipStream_t st, hipEvent_t after_pack = nullptr, int n_seq = 1,
-                const uint16_t *res = nullptr);
+                const uint16_t *res = nullptr, void *o_packed = nullptr, bool *wrote_packed = nullptr);
 
 }  // namespace lv
