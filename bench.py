@@ -428,12 +428,15 @@ def main():
         blk_flop = 2.0 * M * C_ * (3 * C_ + C_ + 4 * C_ + 4 * C_)
         ops["block_linear"] = dict(ms=avg["attn_pack"] + avg["block_rest"],
                                    tflops=blk_flop / ((avg["attn_pack"] + avg["block_rest"]) * 1e-3) / 1e12,
+                                   frac_mfma=blk_flop / ((avg["attn_pack"] + avg["block_rest"]) * 1e-3) / 1e12
+                                   / (PEAK_FP8_MFMA_TFLOPS if args.linear_dtype.startswith("fp8") else PEAK_BF16_MFMA_TFLOPS),
                                    note="everything of the block except the attention kernel: 2 LayerNorms, "
                                         "4 linear layers (24 M C^2 flop), operand re-layouts (FP8: amax and "
                                         "quantisation passes), K/V re-layout")
     if args.frame_attn:
         fa_flop = 4.0 * wl.frames * wl.tokens_per_frame ** 2 * C_
         ops["frame_attn"] = dict(ms=avg["frame_attn"], tflops=fa_flop / (avg["frame_attn"] * 1e-3) / 1e12,
+                                 frac_mfma=fa_flop / (avg["frame_attn"] * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
                                  note="pack + kernel, F independent sequences of P + 5 tokens")
     ops["match"]["frac_mfma"] = ops["match"]["tflops"] / PEAK_BF16_MFMA_TFLOPS
     ops["merge"]["frac_hbm"] = ops["merge"]["gbs"] / PEAK_HBM_GBS

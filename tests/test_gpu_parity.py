@@ -839,10 +839,15 @@ def _dev_block_weights(B, w):
     return t, B.block_weights(t)
 
 
-@pytest.mark.parametrize("n,dim,heads,qk_norm", [(300, 256, 4, 1), (777, 256, 4, 0), (520, 1024, 16, 1)])
+@pytest.mark.parametrize("n,dim,heads,qk_norm", [(300, 256, 4, 1), (777, 256, 4, 0), (520, 1024, 16, 1),
+                                                 (5000, 1024, 16, 1)])
 def test_global_block(B, n, dim, heads, qk_norm):
     """LN -> qkv projection -> attention -> output projection -> LN -> GELU MLP against the
-    oracle; n is ragged against the 256-row tiles, dim 1024 runs 4-16 output tiles per row."""
+    oracle; n is ragged against the 256-row tiles, dim 1024 runs 4-16 output tiles per row.
+    With 5000 rows the first MLP layer has 320 tiles, more than one per compute unit, so
+    workgroups walk from one tile to the next (the fetches of the next tile are issued ahead of
+    the epilogue); with qk_norm 0 the attention output takes the row-major way into the output
+    projection, with qk_norm 1 the attention kernel writes that layer's operand itself."""
     import torch
     w = synth.block_weights(dim, seed=n)
     tens, bw = _dev_block_weights(B, w)
