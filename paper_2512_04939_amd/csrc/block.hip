@@ -100,15 +100,63 @@ __global__ __launch_bounds__(256) void k_layernorm(const uint16_t *__restrict__ 
 // rows meet in LDS (row stride C * 2 + 16 bytes: the 32 rows a wave reads back at one channel
 // piece then lie in different banks) and leave as one contiguous run of 32 * C * 2 bytes.
 // Rows beyond M are written as zeros.
-template <int CPL>
+//
+// FP8: the normalised row (rounded to bf16, as if it had been stored) is quantised with the
+// scale *inv to E4M3 codes and leaves in the FP8 operand order of k_quant_pack_fp8 (units of 32
+// rows x 32 channels, lane h * 32 + r holds the 16 codes of channels 32u + 16h .. + 15 of row
+// r); the largest |value| of the rows below M is reduced into *amax.  Row stride in LDS: C + 16
+// bytes.
+template <int CPL, bool FP8>
 __global__ __launch_bounds__(256) void k_layernorm_packed(const uint16_t *__restrict__ x,
                                                           const uint16_t *__restrict__ add,
                                                           const float *__restrict__ gamma,
                                                           const float *__restrict__ beta, int64_t M, int C,
-                                                          u32x4 *__restrict__ packed) {
+                                                          u32x4 *__restrict__ packed,
+                                                          const uint32_t *__restrict__ inv,
+                                                          uint32_t *__restrict__ amax) {
   extern __shared__ u32x4 ln_stage[];
   constexpr int RB = CPL <= 2 ? 8 : 4;   // rows whose loads are in flight together
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nch = C >> 3, stride = nch + 1;
+  if constexpr (FP8) {
+    const float r = __uint_as_float(*inv);
+    const int stride8 = (C >> 3) + 2;   // u32x2 per row
+    u32x2 *stage8 = (u32x2 *)ln_stage;
+    float m = 0.f;
+#pragma unroll 1
+    for (int j0 = 0; j0 < 8; j0 += RB) {
+      u32x4 w[RB][CPL], a[RB][CPL];
+#pragma unroll
+      for (int j = 0; j < RB; ++j) {
+        const int64_t row = (int64_t)blockIdx.x * 32 + wave * 8 + j0 + j;
+        ln_load<CPL>(x, add, row < M ? row : 0, C, lane, row < M ? nch : 0, w[j], a[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < RB; ++j) {
+        const int rr = wave * 8 + j0 + j;
+        u32x4 o[CPL];
+        ln_row<CPL>(w[j], a[j], gamma, beta, lane, nch, C, o);
+        const bool live = (int64_t)blockIdx.x * 32 + rr < M;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+          if (lane + 64 * c < nch) {
+            if (live) m = fmaxf(m, absmax8(o[c]));
+            stage8[rr * stride8 + lane + 64 * c] = live ? quant8(o[c], r) : u32x2{0u, 0u};
+          }
+      }
+    }
+    m = wave_max(m);
+    if (lane == 0 && __float_as_uint(m) > __hip_atomic_load(amax, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+      atomicMax(amax, __float_as_uint(m));
+    __syncthreads();
+    const int pieces = 32 * (C >> 4);   // = (C / 32) units x 64 lanes
+    for (int p = threadIdx.x; p < pieces; p += 256) {
+      const int u = p >> 6, lp = p & 63;
+      const u32x2 *src = stage8 + (lp & 31) * stride8 + 4 * u + 2 * (lp >> 5);
+      const u32x2 lo = src[0], hi = src[1];
+      packed[(size_t)blockIdx.x * pieces + p] = u32x4{lo.x, lo.y, hi.x, hi.y};
+    }
+    return;
+  }
 #pragma unroll 1
   for (int j0 = 0; j0 < 8; j0 += RB) {
     u32x4 w[RB][CPL], a[RB][CPL];
@@ -136,25 +184,40 @@ __global__ __launch_bounds__(256) void k_layernorm_packed(const uint16_t *__rest
   }
 }
 
+// packed: the result goes there in a linear layer's operand order (Mp rows, the ones beyond M
+// zero) instead of to out; with fp8_inv / fp8_amax as E4M3 codes (scale *fp8_inv, the largest
+// |value| reduced into *fp8_amax), else as bf16
 static int launch_layernorm(const uint16_t *x, const uint16_t *add, const float *gamma,
                             const float *beta, int64_t M, int C, uint16_t *out, hipStream_t st,
-                            u32x4 *packed = nullptr, int64_t Mp = 0) {
+                            u32x4 *packed = nullptr, int64_t Mp = 0, const uint32_t *fp8_inv = nullptr,
+                            uint32_t *fp8_amax = nullptr) {
   const int cpl = (C / 8 + 63) / 64;
-  if (C % 16 != 0 || cpl > 4) return LV_ERR_SHAPE;
+  if (C % 32 != 0 || cpl > 4) return LV_ERR_SHAPE;
   if (packed) {
-    if (Mp % 32 != 0 || Mp < M) return LV_ERR_SHAPE;
-    const size_t lds = (size_t)32 * (C / 8 + 1) * 16;
-    static std::atomic<uint64_t> lds_done[4];
+    if (Mp % 32 != 0 || Mp < M || !fp8_inv != !fp8_amax) return LV_ERR_SHAPE;
+    const size_t lds = (size_t)32 * (C / 8 + 1) * 16;   // the FP8 rows (C + 16 bytes) fit as well
+    static std::atomic<uint64_t> lds_done[8];
     const unsigned grid = (unsigned)(Mp / 32);
     int rc;
-#define LV_LNP(CPL)                                                                                      \
-  if ((rc = allow_dynamic_lds((const void *)k_layernorm_packed<CPL>, lds, lds_done[CPL - 1]))) return rc; \
-  hipLaunchKernelGGL(k_layernorm_packed<CPL>, dim3(grid), dim3(256), lds, st, x, add, gamma, beta, M, C, packed)
-    switch (cpl) {
-      case 1: LV_LNP(1); break;
-      case 2: LV_LNP(2); break;
-      case 3: LV_LNP(3); break;
-      default: LV_LNP(4); break;
+#define LV_LNP(CPL, F8)                                                                                       \
+  if ((rc = allow_dynamic_lds((const void *)k_layernorm_packed<CPL, F8>, lds, lds_done[(CPL - 1) * 2 + F8])))   \
+    return rc;                                                                                                \
+  hipLaunchKernelGGL((k_layernorm_packed<CPL, F8>), dim3(grid), dim3(256), lds, st, x, add, gamma, beta, M, C,  \
+                     packed, fp8_inv, fp8_amax)
+    if (fp8_inv) {
+      switch (cpl) {
+        case 1: LV_LNP(1, true); break;
+        case 2: LV_LNP(2, true); break;
+        case 3: LV_LNP(3, true); break;
+        default: LV_LNP(4, true); break;
+      }
+    } else {
+      switch (cpl) {
+        case 1: LV_LNP(1, false); break;
+        case 2: LV_LNP(2, false); break;
+        case 3: LV_LNP(3, false); break;
+        default: LV_LNP(4, false); break;
+      }
     }
 #undef LV_LNP
     LV_HIP_CHECK_LAUNCH();
@@ -202,31 +265,13 @@ __global__ __launch_bounds__(256) void k_amax_bf16(const u32x4 *__restrict__ x, 
     atomicMax(amax, __float_as_uint(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]))));
 }
 
-// One wave: picks the scales of a layer.  state == NULL: both from the tensors' own amax.
-// Otherwise the input's scale comes from the largest of the recorded amaxes (1 while nothing
-// has been recorded); the input's own amax is recorded by k_fp8_record once the quantisation
-// pass, which takes it on the way, has run.
-__global__ __launch_bounds__(64) void k_fp8_scales(uint32_t *__restrict__ sc, const float *__restrict__ state) {
-  const int lane = threadIdx.x;
-  uint32_t src = sc[0];
-  if (state) {
-    float m = fmaxf(state[lane], lane + 64 < LV_FP8_HISTORY ? state[lane + 64] : 0.f);
-    src = __float_as_uint(wave_max(m));
-  }
-  if (lane == 0) {
-    const float ia = fp8_scale_inv(src), iw = fp8_scale_inv(sc[1]);
+// One wave: picks the scales of a layer from the tensors' own amax (current scaling).
+__global__ __launch_bounds__(64) void k_fp8_scales(uint32_t *__restrict__ sc) {
+  if (threadIdx.x == 0) {
+    const float ia = fp8_scale_inv(sc[0]), iw = fp8_scale_inv(sc[1]);
     sc[2] = __float_as_uint(ia);
     sc[3] = __float_as_uint(iw);
     sc[4] = __float_as_uint((1.0f / ia) * (1.0f / iw));
-  }
-}
-
-// delayed scaling: the amax of the input just quantised goes into the layer's history
-__global__ void k_fp8_record(const uint32_t *__restrict__ sc, float *__restrict__ state) {
-  if (threadIdx.x == 0) {
-    uint32_t *step = (uint32_t *)(state + LV_FP8_HISTORY);
-    state[*step % LV_FP8_HISTORY] = __uint_as_float(sc[0]);
-    *step += 1;
   }
 }
 
@@ -320,7 +365,8 @@ template <bool FP8, bool PACKED>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_gemm_bt(
     const u32x4 *__restrict__ ap, const u32x4 *__restrict__ wp, int64_t M, int KS, int nt_n,
     const float *__restrict__ bias, int gelu, uint16_t *__restrict__ out, int split,
-    const float *__restrict__ alpha_p, int n_tiles, const uint16_t *__restrict__ addend) {
+    const float *__restrict__ alpha_p, int n_tiles, const uint16_t *__restrict__ addend,
+    const uint32_t *__restrict__ out_inv, uint32_t *__restrict__ out_amax) {
   extern __shared__ u32x4 ring[];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -497,6 +543,46 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     } else {
       primed = false;
     }
+    if constexpr (FP8) {
+      // E4M3 codes for an FP8 layer with K = Nout (units of 32 rows x 32 channels, lane h * 32 + r
+      // holds the 16 codes of channels 32u + 16h .. + 15 of row r): every value is rounded to
+      // bf16 as if it had been stored, then scaled by *out_inv; a lane has one dword of four codes
+      // per register group g, lanes l and l + 32 trade groups 2, 3 against groups 0, 1.  The
+      // largest |value| of the rows below M goes into *out_amax; rows beyond M are written as zeros.
+      const float r = __uint_as_float(*out_inv);
+      const int KSn = nt_n * (kTile / 32);
+      u32x4 *op = (u32x4 *)out + ((size_t)(tm * 8 + wd * 2) * KSn + tn * (kTile / 32) + wn * 4) * 64 + lane + anchor;
+      float m = 0.f;
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+          const bool live = (int64_t)tm * kTile + wd * 64 + 32 * a + (lane & 31) < M;
+          uint32_t d[4];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 bv = *(const f32x4 *)(bias_lds + wn * 128 + 32 * b + 8 * g + 4 * h);
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              v[i] = acc[a][b][4 * g + i] * alpha + bv[i];
+              if (gelu) v[i] = gelu_erf(v[i]);
+            }
+            const uint32_t p0 = pack_bf16(v[0], v[1]), p1 = pack_bf16(v[2], v[3]);
+            if (live) m = fmaxf(m, fmaxf(fmaxf(fabsf(bf16_lo(p0)), fabsf(bf16_hi(p0))), fmaxf(fabsf(bf16_lo(p1)), fabsf(bf16_hi(p1)))));
+            d[g] = live ? cvt4_fp8(clamp448(bf16_lo(p0) * r), clamp448(bf16_hi(p0) * r), clamp448(bf16_lo(p1) * r),
+                                   clamp448(bf16_hi(p1) * r))
+                        : 0u;
+          }
+          const auto s0 = __builtin_amdgcn_permlane32_swap(d[0], d[2], false, false);
+          const auto s1 = __builtin_amdgcn_permlane32_swap(d[1], d[3], false, false);
+          op[((size_t)a * KSn + b) * 64] = u32x4{s0[0], s0[1], s1[0], s1[1]};
+        }
+      m = wave_max(m);
+      if (lane == 0 && __float_as_uint(m) > __hip_atomic_load(out_amax, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        atomicMax(out_amax, __float_as_uint(m));
+      continue;
+    }
     const int KSn = nt_n * (kTile / 16);
     u32x4 *op = (u32x4 *)out + ((size_t)(tm * 8 + wd * 2) * KSn + tn * (kTile / 16) + wn * 8) * 64 + lane + anchor;
 #pragma unroll
@@ -579,8 +665,9 @@ struct BlockWs {
   int64_t Mp;
 };
 
-// the four weight matrices in operand order, one after the other (qkv, output, MLP 1, MLP 2)
-size_t block_wpack_bytes(int C) { return align_up((size_t)12 * C * C * 2, 256); }
+// the four weight matrices in operand order, one after the other (qkv, output, MLP 1, MLP 2),
+// then a 256-byte tail for their four amaxes (FP8 layers)
+size_t block_wpack_bytes(int C) { return align_up((size_t)12 * C * C * 2, 256) + 256; }
 
 static BlockWs carve_block(int64_t M, int C, int heads, int attn_dtype, char *base) {
   BlockWs w;
@@ -598,7 +685,7 @@ static BlockWs carve_block(int64_t M, int C, int heads, int attn_dtype, char *ba
   w.h3 = (uint16_t *)take((size_t)w.Mp * 4 * C * 2);   // row-major (FP8 layers) or in fragment order (bf16 layers)
   w.apack = (u32x4 *)take((size_t)w.Mp * 4 * C);       // a layer's activation operand: bf16 with K = C, FP8 with K <= 4C
   w.wpack = (u32x4 *)take(block_wpack_bytes(C));
-  w.fp8sc = (uint32_t *)take(kFp8Words * sizeof(uint32_t));
+  w.fp8sc = (uint32_t *)take(4 * kFp8Words * sizeof(uint32_t));   // one set per linear layer
   w.attn = take(attn_ws_bytes(heads, M, attn_dtype));
   w.bytes = off;
   return w;
@@ -608,29 +695,40 @@ size_t block_ws_bytes(int64_t M, int C, int heads, int attn_dtype) {
   return carve_block(M, C, heads, attn_dtype, nullptr).bytes;
 }
 
-// Y = A W^T + bias: packs both operands (FP8: after taking their amax and quantising them),
-// then the tiled kernel.  fp8_state: the layer's delayed-scaling state, or NULL.
-// bf16 layers only: `a_packed` (the activation operand already in fragment order, A unused),
-// `pack_out` (out receives the result in fragment order for a layer with K = Nout, padded rows
-// included: Mp x Nout elements), `addend` (row-major, same shape as out: out = addend + result).
+// What a linear layer finds ready and what it leaves behind.
+struct LinearOpts {
+  bool fp8 = false;
+  const u32x4 *a_packed = nullptr;     // the activation operand, already in operand order (then A is unused)
+  bool pack_out = false;               // out receives the next layer's (K = Nout) operand, Mp rows, instead of row-major rows
+  const uint16_t *addend = nullptr;    // row-major, same shape as out: out = addend + result
+  u32x4 *w_packed = nullptr;           // where the weight operand lives (default: the workspace)
+  bool pack_w = true;                  // false: w_packed already holds it
+  // FP8 with this layer's scalars prepared by k_fp8_prepare (nothing is zeroed, derived or
+  // recorded here): A, unless a_packed, is quantised with sc[2] and its amax reduced into sc[0];
+  // W, if pack_w, is quantised with sc[3]
+  uint32_t *sc = nullptr;
+  const uint32_t *out_inv = nullptr;   // FP8 pack_out: the next layer's input scale ...
+  uint32_t *out_amax = nullptr;        // ... and where the largest |output| is reduced into
+};
+
+// Y = A W^T + bias: brings both operands into operand order where they are not yet (FP8: after
+// taking their amax and quantising them), then the tiled kernel.
 static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W, int Nout,
                          const float *bias, int gelu, uint16_t *out, int split, BlockWs &w,
-                         hipStream_t st, bool fp8 = false, float *fp8_state = nullptr,
-                         const u32x4 *a_packed = nullptr, bool pack_out = false,
-                         const uint16_t *addend = nullptr, u32x4 *w_packed = nullptr, bool pack_w = true) {
-  if (!w_packed) w_packed = w.wpack;
-  if (fp8 && !pack_w) return LV_ERR_PARAM;
-  if (fp8 && (a_packed || pack_out)) return LV_ERR_PARAM;
-  if (pack_out && (addend || split != Nout)) return LV_ERR_PARAM;
+                         hipStream_t st, const LinearOpts &o) {
+  u32x4 *const w_packed = o.w_packed ? o.w_packed : w.wpack;
+  if (o.fp8 && !o.sc && (!o.pack_w || o.a_packed || o.pack_out)) return LV_ERR_PARAM;
+  if (o.pack_out && (o.addend || split != Nout || (o.fp8 && (!o.out_inv || !o.out_amax)))) return LV_ERR_PARAM;
   if (K % 64 != 0 || Nout % kTile != 0 || split % kTile != 0 || Nout % split != 0) return LV_ERR_SHAPE;
   int rc;
   // the ring; the epilogue's output tile (256 rows of 512 bytes) has the same size
   static_assert((size_t)kTile * kTile * 2 <= (size_t)kStages * kStageU4 * 16, "output tile must fit the ring");
   const size_t lds = (size_t)kStages * kStageU4 * 16 + 2 * kTile * sizeof(float);   // + two tiles' bias values
-  static std::atomic<uint64_t> lds_done[3];
+  static std::atomic<uint64_t> lds_done[4];
   if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<false, false>, lds, lds_done[0]))) return rc;
   if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<true, false>, lds, lds_done[1]))) return rc;
   if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<false, true>, lds, lds_done[2]))) return rc;
+  if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<true, true>, lds, lds_done[3]))) return rc;
   const int nt_n = Nout / kTile;
   const int64_t nt_m = w.Mp / kTile;
   if (nt_m * nt_n >= ((int64_t)1 << 31) || w.Mp >= ((int64_t)1 << 31)) return LV_ERR_SHAPE;
@@ -640,7 +738,8 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
       hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
     return LV_ERR_HIP;
   const unsigned grid = (unsigned)(n_tiles < n_cu ? n_tiles : n_cu);
-  if (fp8) {
+  const u32x4 *a_packed = o.a_packed;
+  if (o.fp8) {
     auto amax = [&](const uint16_t *t, int64_t n16, uint32_t *dst) {
       const unsigned g = (unsigned)(((n16 + 255) / 256) < 4096 ? ((n16 + 255) / 256) : 4096);
       hipLaunchKernelGGL(k_amax_bf16, dim3(g), dim3(256), 0, st, (const u32x4 *)t, n16, dst);
@@ -649,32 +748,79 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
       hipLaunchKernelGGL(k_quant_pack_fp8, dim3((unsigned)(n_pad / 32), (unsigned)((K / 32 + 15) / 16)), dim3(256), 0, st, t, (int)n,
                          K, inv, dst, amax_out);
     };
-    // current scaling: the input's amax first, then its scale; delayed scaling: the scale comes
-    // from the history, the quantisation pass takes the amax on the way and it is recorded after
-    hipLaunchKernelGGL(k_fp8_zero, dim3(1), dim3(64), 0, st, w.fp8sc);
-    if (!fp8_state) amax(A, M * (K / 8), w.fp8sc);
-    amax(W, (int64_t)Nout * (K / 8), w.fp8sc + 1);
-    hipLaunchKernelGGL(k_fp8_scales, dim3(1), dim3(64), 0, st, w.fp8sc, (const float *)fp8_state);
-    quant(A, M, w.Mp, w.fp8sc + 2, w.apack, fp8_state ? w.fp8sc : (uint32_t *)nullptr);
-    quant(W, Nout, Nout, w.fp8sc + 3, w_packed, (uint32_t *)nullptr);
-    if (fp8_state) hipLaunchKernelGGL(k_fp8_record, dim3(1), dim3(64), 0, st, w.fp8sc, fp8_state);
-    hipLaunchKernelGGL((k_gemm_bt<true, false>), dim3(grid), dim3(512), lds, st, w.apack, w_packed,
-                       M, K / 32, nt_n, bias, gelu, out, split, (const float *)(w.fp8sc + 4), n_tiles, addend);
+    uint32_t *sc = o.sc;
+    if (!sc) {
+      // current scaling: both amaxes first, then the scales, then the two quantisation passes
+      sc = w.fp8sc;
+      hipLaunchKernelGGL(k_fp8_zero, dim3(1), dim3(64), 0, st, sc);
+      amax(A, M * (K / 8), sc);
+      amax(W, (int64_t)Nout * (K / 8), sc + 1);
+      hipLaunchKernelGGL(k_fp8_scales, dim3(1), dim3(64), 0, st, sc);
+      quant(A, M, w.Mp, sc + 2, w.apack, (uint32_t *)nullptr);
+      quant(W, Nout, Nout, sc + 3, w_packed, (uint32_t *)nullptr);
+      a_packed = w.apack;
+    } else {
+      if (!a_packed) {
+        quant(A, M, w.Mp, sc + 2, w.apack, sc);
+        a_packed = w.apack;
+      }
+      if (o.pack_w) quant(W, Nout, Nout, sc + 3, w_packed, (uint32_t *)nullptr);
+    }
+    if (o.pack_out)
+      hipLaunchKernelGGL((k_gemm_bt<true, true>), dim3(grid), dim3(512), lds, st, a_packed, w_packed, M, K / 32,
+                         nt_n, bias, gelu, out, split, (const float *)(sc + 4), n_tiles, o.addend, o.out_inv,
+                         o.out_amax);
+    else
+      hipLaunchKernelGGL((k_gemm_bt<true, false>), dim3(grid), dim3(512), lds, st, a_packed, w_packed, M, K / 32,
+                         nt_n, bias, gelu, out, split, (const float *)(sc + 4), n_tiles, o.addend,
+                         (const uint32_t *)nullptr, (uint32_t *)nullptr);
   } else {
     if (!a_packed) {
       if ((rc = launch_pack_rows(A, M, w.Mp, K, w.apack, st))) return rc;
       a_packed = w.apack;
     }
-    if (pack_w && (rc = launch_pack_rows(W, Nout, Nout, K, w_packed, st))) return rc;
-    if (pack_out)
-      hipLaunchKernelGGL((k_gemm_bt<false, true>), dim3(grid), dim3(512), lds, st, a_packed, w_packed,
-                         M, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr, n_tiles, addend);
+    if (o.pack_w && (rc = launch_pack_rows(W, Nout, Nout, K, w_packed, st))) return rc;
+    if (o.pack_out)
+      hipLaunchKernelGGL((k_gemm_bt<false, true>), dim3(grid), dim3(512), lds, st, a_packed, w_packed, M, K / 16,
+                         nt_n, bias, gelu, out, split, (const float *)nullptr, n_tiles, o.addend,
+                         (const uint32_t *)nullptr, (uint32_t *)nullptr);
     else
-      hipLaunchKernelGGL((k_gemm_bt<false, false>), dim3(grid), dim3(512), lds, st, a_packed, w_packed,
-                         M, K / 16, nt_n, bias, gelu, out, split, (const float *)nullptr, n_tiles, addend);
+      hipLaunchKernelGGL((k_gemm_bt<false, false>), dim3(grid), dim3(512), lds, st, a_packed, w_packed, M, K / 16,
+                         nt_n, bias, gelu, out, split, (const float *)nullptr, n_tiles, o.addend,
+                         (const uint32_t *)nullptr, (uint32_t *)nullptr);
   }
   LV_HIP_CHECK_LAUNCH();
   return LV_OK;
+}
+
+// Delayed scaling with every layer's scalars prepared ahead of the kernels that produce the
+// layers' inputs: block L of the grid fills the 8 words of layer L (input amax cleared, the
+// weight's amax, 448 / the largest recorded input amax, 448 / the weight's amax, the product of
+// the two inverse scales).  Same arithmetic as k_fp8_scales; a history with nothing recorded yet gives scale 1.
+__global__ __launch_bounds__(64) void k_fp8_prepare(uint32_t *__restrict__ sc, const float *__restrict__ state,
+                                                    const uint32_t *__restrict__ wamax) {
+  const int lane = threadIdx.x, L = blockIdx.x;
+  const float *hist = state + (size_t)L * (LV_FP8_HISTORY + 2);
+  const float m = wave_max(fmaxf(hist[lane], lane + 64 < LV_FP8_HISTORY ? hist[lane + 64] : 0.f));
+  if (lane == 0) {
+    uint32_t *s = sc + L * kFp8Words;
+    const float ia = fp8_scale_inv(__float_as_uint(m)), iw = fp8_scale_inv(wamax[L]);
+    s[0] = 0u;
+    s[1] = wamax[L];
+    s[2] = __float_as_uint(ia);
+    s[3] = __float_as_uint(iw);
+    s[4] = __float_as_uint((1.0f / ia) * (1.0f / iw));
+  }
+}
+
+// ... and, once the four layers have run, each layer's input amax goes into its history
+__global__ void k_fp8_record_all(const uint32_t *__restrict__ sc, float *__restrict__ state) {
+  if (threadIdx.x < 4) {
+    float *hist = state + (size_t)threadIdx.x * (LV_FP8_HISTORY + 2);
+    uint32_t *step = (uint32_t *)(hist + LV_FP8_HISTORY);
+    hist[*step % LV_FP8_HISTORY] = __uint_as_float(sc[threadIdx.x * kFp8Words]);
+    *step += 1;
+  }
 }
 
 int launch_global_block(const uint16_t *z, int64_t M, int C, int heads, float scale, int attn_dtype,
@@ -685,39 +831,104 @@ int launch_global_block(const uint16_t *z, int64_t M, int C, int heads, float sc
   BlockWs w = carve_block(M, C, heads, attn_dtype, (char *)ws);
   int rc;
   const bool f8 = bw.linear_dtype == LV_LINEAR_FP8_E4M3;
-  // the weights in operand order: in the workspace, or (bf16 layers) in a buffer of the caller's
-  // that outlives the call and may already hold them
-  u32x4 *const wp = !f8 && wpack_keep ? (u32x4 *)wpack_keep : w.wpack;
-  const bool pack_w = !(wp == wpack_keep && wpack_ready);
+  const bool delayed = f8 && bw.fp8_recipe == LV_FP8_DELAYED;
+  // The weights in operand order: in the workspace, or in a buffer of the caller's that outlives
+  // the call and may already hold them (bf16 layers, and FP8 layers under delayed scaling, where
+  // a weight's scale depends on nothing but the weight; the four amaxes follow the matrices).
+  const bool keep = wpack_keep && (!f8 || delayed);
+  u32x4 *const wp = keep ? (u32x4 *)wpack_keep : w.wpack;
+  const bool pack_w = !(keep && wpack_ready);
   const size_t cc16 = (size_t)C * C * 2 / 16;
-  u32x4 *const wp_qkv = wp, *const wp_o = wp + 3 * cc16, *const wp_1 = wp + 4 * cc16, *const wp_2 = wp + 8 * cc16;
-  auto state = [&](int layer) -> float * {   // delayed scaling: this layer's history
-    return f8 && bw.fp8_recipe == LV_FP8_DELAYED ? (float *)bw.fp8_state + layer * (LV_FP8_HISTORY + 2) : nullptr;
+  u32x4 *const wp_l[4] = {wp, wp + 3 * cc16, wp + 4 * cc16, wp + 8 * cc16};
+  uint32_t *const wamax = (uint32_t *)(wp + 12 * cc16);
+  const uint16_t *const W[4] = {(const uint16_t *)bw.w_qkv, (const uint16_t *)bw.w_o, (const uint16_t *)bw.w_1,
+                                (const uint16_t *)bw.w_2};
+  const int w_rows[4] = {3 * C, C, 4 * C, C}, w_k[4] = {C, C, C, 4 * C};
+  const float *const bias[4] = {bw.b_qkv, bw.b_o, bw.b_1, bw.b_2};
+  const uint16_t *q = w.qkv, *k = w.qkv + (size_t)M * C, *v = w.qkv + (size_t)2 * M * C;
+
+  if (delayed) {
+    // FP8 layers, delayed scaling: every input scale is known before its tensor exists, so the
+    // LayerNorms and the first MLP layer quantise their results themselves (taking the amax for
+    // the history on the way); only the attention output goes through k_quant_pack_fp8.
+    uint32_t *const sc = w.fp8sc;
+    if (pack_w) {
+      hipLaunchKernelGGL(k_fp8_zero, dim3(1), dim3(64), 0, st, wamax);
+      for (int l = 0; l < 4; ++l) {
+        const int64_t n16 = (int64_t)w_rows[l] * (w_k[l] / 8);
+        const unsigned g = (unsigned)(((n16 + 255) / 256) < 4096 ? ((n16 + 255) / 256) : 4096);
+        hipLaunchKernelGGL(k_amax_bf16, dim3(g), dim3(256), 0, st, (const u32x4 *)W[l], n16, wamax + l);
+      }
+    }
+    hipLaunchKernelGGL(k_fp8_prepare, dim3(4), dim3(64), 0, st, sc, (const float *)bw.fp8_state, (const uint32_t *)wamax);
+    auto layer = [&](int l) {
+      LinearOpts o;
+      o.fp8 = true;
+      o.sc = sc + l * kFp8Words;
+      o.w_packed = wp_l[l];
+      o.pack_w = pack_w;
+      return o;
+    };
+    if ((rc = launch_layernorm(z, nullptr, bw.ln1_g, bw.ln1_b, M, C, nullptr, st, w.apack, w.Mp, sc + 2, sc))) return rc;
+    LinearOpts o = layer(0);
+    o.a_packed = w.apack;
+    if ((rc = launch_linear(nullptr, M, C, W[0], 3 * C, bias[0], 0, w.qkv, C, w, st, o))) return rc;
+    if ((rc = launch_attn(q, k, v, w.a, M, heads, scale, attn_dtype, qk_norm, w.attn, st, after_pack))) return rc;
+    if (after_attn && hipEventRecord(after_attn, st) != hipSuccess) return LV_ERR_HIP;
+    o = layer(1);
+    if ((rc = launch_linear(w.a, M, C, W[1], C, bias[1], 0, w.u1, C, w, st, o))) return rc;
+    if ((rc = launch_layernorm(z, w.u1, bw.ln2_g, bw.ln2_b, M, C, nullptr, st, w.apack, w.Mp,
+                               sc + 2 * kFp8Words + 2, sc + 2 * kFp8Words)))
+      return rc;
+    o = layer(2);
+    o.a_packed = w.apack;
+    o.pack_out = true;
+    o.out_inv = sc + 3 * kFp8Words + 2;
+    o.out_amax = sc + 3 * kFp8Words;
+    if ((rc = launch_linear(nullptr, M, C, W[2], 4 * C, bias[2], 1, w.h3, 4 * C, w, st, o))) return rc;
+    o = layer(3);
+    o.a_packed = (const u32x4 *)w.h3;
+    o.addend = w.u1;
+    if ((rc = launch_linear(nullptr, M, 4 * C, W[3], C, bias[3], 0, delta, C, w, st, o))) return rc;
+    hipLaunchKernelGGL(k_fp8_record_all, dim3(1), dim3(64), 0, st, (const uint32_t *)sc, (float *)bw.fp8_state);
+    LV_HIP_CHECK_LAUNCH();
+    return LV_OK;
+  }
+
+  auto layer = [&](int l) {
+    LinearOpts o;
+    o.fp8 = f8;
+    o.w_packed = wp_l[l];
+    o.pack_w = f8 || pack_w;
+    return o;
   };
   // bf16 layers: the LayerNorms write their result in the following layer's operand order
   u32x4 *const ln_packed = f8 ? nullptr : w.apack;
   if ((rc = launch_layernorm(z, nullptr, bw.ln1_g, bw.ln1_b, M, C, w.h, st, ln_packed, w.Mp))) return rc;
-  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_qkv, 3 * C, bw.b_qkv, 0, w.qkv, C, w, st, f8, state(0),
-                          ln_packed, false, nullptr, wp_qkv, pack_w)))
-    return rc;
-  const uint16_t *q = w.qkv, *k = w.qkv + (size_t)M * C, *v = w.qkv + (size_t)2 * M * C;
+  LinearOpts o = layer(0);
+  o.a_packed = ln_packed;
+  if ((rc = launch_linear(w.h, M, C, W[0], 3 * C, bias[0], 0, w.qkv, C, w, st, o))) return rc;
   // bf16 layers: where the attention kernel can, it writes the output projection's operand itself
   bool a_is_packed = false;
   if ((rc = launch_attn(q, k, v, w.a, M, heads, scale, attn_dtype, qk_norm, w.attn, st, after_pack, 1, nullptr,
                         f8 ? nullptr : (void *)w.apack, &a_is_packed)))
     return rc;
   if (after_attn && hipEventRecord(after_attn, st) != hipSuccess) return LV_ERR_HIP;
-  if ((rc = launch_linear(w.a, M, C, (const uint16_t *)bw.w_o, C, bw.b_o, 0, w.u1, C, w, st, f8, state(1),
-                          a_is_packed ? w.apack : nullptr, false, nullptr, wp_o, pack_w)))
-    return rc;
+  o = layer(1);
+  o.a_packed = a_is_packed ? w.apack : nullptr;
+  if ((rc = launch_linear(w.a, M, C, W[1], C, bias[1], 0, w.u1, C, w, st, o))) return rc;
   if ((rc = launch_layernorm(z, w.u1, bw.ln2_g, bw.ln2_b, M, C, w.h, st, ln_packed, w.Mp))) return rc;
-  // bf16 layers: the first MLP layer writes its output in the second one's operand order; the
-  // second one's epilogue adds u1 (delta = u1 + u2, u2 rounded to bf16 first as if it were stored)
-  if ((rc = launch_linear(w.h, M, C, (const uint16_t *)bw.w_1, 4 * C, bw.b_1, 1, w.h3, 4 * C, w, st, f8, state(2),
-                          ln_packed, !f8, nullptr, wp_1, pack_w)))
-    return rc;
-  return launch_linear(w.h3, M, 4 * C, (const uint16_t *)bw.w_2, C, bw.b_2, 0, delta, C, w, st, f8, state(3),
-                       f8 ? nullptr : (const u32x4 *)w.h3, false, w.u1, wp_2, pack_w);
+  // bf16 layers: the first MLP layer writes its output in the second one's operand order.  All
+  // layers: the second one's epilogue adds u1 (delta = u1 + u2, u2 rounded to bf16 first as if
+  // it had been stored).
+  o = layer(2);
+  o.a_packed = ln_packed;
+  o.pack_out = !f8;
+  if ((rc = launch_linear(w.h, M, C, W[2], 4 * C, bias[2], 1, w.h3, 4 * C, w, st, o))) return rc;
+  o = layer(3);
+  o.a_packed = f8 ? nullptr : (const u32x4 *)w.h3;
+  o.addend = w.u1;
+  return launch_linear(w.h3, M, 4 * C, W[3], C, bias[3], 0, delta, C, w, st, o);
 }
 
 }  // namespace lv

@@ -895,12 +895,15 @@ def test_global_block_fp8_linear_current_scaling(B, n, dim, heads):
     assert max_rel_err(got, exact) <= 1e-1
 
 
-def test_global_block_fp8_linear_delayed_scaling(B):
-    """Delayed scaling over four calls with inputs of different range: the scale of a call
+@pytest.mark.parametrize("n,dim,heads,amps", [(300, 256, 4, (1.5, 0.4, 3.0, 1.0)), (4200, 1024, 16, (1.5, 0.4))])
+def test_global_block_fp8_linear_delayed_scaling(B, n, dim, heads, amps):
+    """Delayed scaling over several calls with inputs of different range: the scale of a call
     comes from the amaxes the earlier calls recorded (1 in the first call, where most codes
-    are coarse), and the device state equals the oracle's history."""
+    are coarse), and the device state equals the oracle's history.  Under this recipe the
+    LayerNorms and the first MLP layer quantise their own results; with 4200 rows that layer has
+    more tiles than compute units, so workgroups walk from tile to tile, and the last row tile
+    is ragged (its padding rows must stay out of the recorded amax)."""
     import torch
-    n, dim, heads = 300, 256, 4
     w = synth.block_weights(dim, seed=9)
     tens, _ = _dev_block_weights(B, w)
     state = torch.zeros(B.FP8_STATE_BYTES, dtype=torch.uint8, device="cuda")
@@ -912,7 +915,7 @@ def test_global_block_fp8_linear_delayed_scaling(B):
     w64 = {k: v.astype(np.float64) for k, v in w.items()}
     ws = B.alloc_ws(B.litevggt_global_block_ws_bytes(ph, n))
     rng = np.random.default_rng(77)
-    for call, amp in enumerate((1.5, 0.4, 3.0, 1.0)):
+    for call, amp in enumerate(amps):
         zb = synth.f32_to_bf16_bits((rng.standard_normal((n, dim)) * amp).astype(np.float32))
         z = synth.bf16_bits_to_f32(zb).astype(np.float64)
         want = O.global_block(z, w64, po, _store_bf16)
@@ -967,6 +970,39 @@ def test_layers_run_with_block_and_frame_attention(B, linear):
     torch.cuda.synchronize()
     assert log == ref_log
     assert max_rel_err(dev_bf16_to_f64(x_dev), ref_out) <= tol
+
+
+def test_layers_run_block_fp8_delayed_scaling_over_layers(B):
+    """The layer driver with FP8 linear layers under delayed scaling: three chained layers share
+    one block's weights and histories (the weights are quantised by the first layer only), so
+    layer l quantises with the amaxes layers 0 .. l-1 recorded.  Output and histories against
+    the oracle's chained run."""
+    import torch
+    wl = synth.workload("tiny2")
+    bits, xf, im = stored_inputs(wl)
+    w = synth.block_weights(wl.dim, seed=6)
+    tens, _ = _dev_block_weights(B, w)
+    state = torch.zeros(B.FP8_STATE_BYTES, dtype=torch.uint8, device="cuda")
+    bw = B.block_weights(tens, linear_dtype=B.LINEAR_FP8_E4M3, fp8_recipe=B.FP8_DELAYED, fp8_state=state)
+    hist = [O.Fp8History() for _ in range(4)]
+    po = oracle_params(wl, linear_fp8=True, fp8_history=hist,
+                       block={k: v.astype(np.float64) for k, v in w.items()})
+    ph = hip_params(wl, block=bw)
+    pl = B.litevggt_plan(ph)
+    ref_out, ref_log = O.layers_run(im, xf, po, 3, store=_store_bf16)
+    x_dev = to_dev_bf16(bits)
+    ib = B.alloc_index(pl)
+    grad = torch.zeros(wl.frames, wl.patches, device="cuda")
+    score = torch.zeros(wl.frames, wl.patches, device="cuda")
+    log = B.litevggt_layers_run(ph, 3, torch.from_numpy(im).cuda(), x_dev, ib, grad, score, B.alloc_ws(pl.ws_bytes))
+    torch.cuda.synchronize()
+    assert log == ref_log
+    assert max_rel_err(dev_bf16_to_f64(x_dev), ref_out) <= FP8_EMU_TOL
+    st = state.cpu().numpy().view(np.float32).reshape(4, B.FP8_HISTORY + 2)
+    for layer in range(4):
+        assert st[layer, B.FP8_HISTORY:].view(np.uint32)[0] == 3 == hist[layer].step
+        assert np.allclose(st[layer, :B.FP8_HISTORY], hist[layer].hist, rtol=2e-2, atol=0)
+        assert np.all(st[layer, :3] > 0) and np.all(st[layer, 3:B.FP8_HISTORY] == 0)
 
 
 # ------------------------------------------------------------------------- frame attention
