@@ -328,9 +328,14 @@ __global__ __launch_bounds__(256) void k_quant_pack_fp8(const uint16_t *__restri
 // output tiles, both operands pre-packed fragment-major, fetched straight into a 4-stage LDS
 // ring (2 k-steps per stage, 3 stages ahead), fragments read by hand one k-step ahead, 8 waves
 // of 64 rows x 128 columns.  The finished tile is converted to bf16 into LDS (the ring is free
-// by then) and written in 16-byte pieces along the rows.
+// by then) and written in 16-byte pieces along the rows; `addend` (optional, shaped like the
+// output) is added to the rounded result on the way out.
 // `split`: the output is Nout / split row-major blocks of [M, split] one after the other
 // (split = Nout: one plain matrix; split = C for the fused q|k|v projection).
+// PACKED: the output is the activation operand of a following layer with K = Nout and is
+// written in that layer's operand order straight from the accumulators (bf16 fragments, or,
+// with FP8, E4M3 codes quantised with *out_inv while the largest |value| goes to *out_amax);
+// the ring stays free, so the next tile's first stages are fetched during the epilogue.
 // FP8: the same ring and the same byte traffic per stage, but a stage (two 1 KB units per
 // fragment) is one k-step of 64 for v_mfma_f32_32x32x64_f8f6f4, whose operands are the two
 // units of a fragment side by side in 8 registers: per stage a wave issues 8 MFMAs of twice
