@@ -470,14 +470,15 @@ def main():
         yv = torch.empty_like(zv)
         B.litevggt_merge(ph, x0, ib, zv)
 
-        def launch_ms(p, reps=3):
+        def launch_ms(p, reps=3, q=None):
+            q = zv if q is None else q
             wsv = B.alloc_ws(B.litevggt_attn_ws_bytes(p, M))
-            B.litevggt_global_attn(p, M, zv, zv, zv, yv, wsv)
+            B.litevggt_global_attn(p, M, q, zv, zv, yv, wsv)
             torch.cuda.synchronize()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
             for _ in range(reps):
-                B.litevggt_global_attn(p, M, zv, zv, zv, yv, wsv)
+                B.litevggt_global_attn(p, M, q, zv, zv, yv, wsv)
             b.record()
             torch.cuda.synchronize()
             return a.elapsed_time(b) / reps
@@ -492,11 +493,11 @@ def main():
                             "layer, averaged over 3 calls; frac = 4 M^2 C flop / call time / peak, so the re-layout "
                             "(ops.attn_pack) is inside"}
         for key, p_v, peak_v, what in (
-                ("bf16_qk_norm", mk(), PEAK_BF16_MFMA_TFLOPS, "k_attn_bf16_main<false>: fixed reference (unit-RMS q, k)"),
+                ("bf16_qk_norm", mk(), PEAK_BF16_MFMA_TFLOPS, "k_attn_bf16_main<false, false>: fixed reference (unit-RMS q, k)"),
                 ("bf16_as_given", mk(qk_norm=0), PEAK_BF16_MFMA_TFLOPS,
-                 "k_attn_bf16_main<true> (online softmax, per-wave running reference raised lazily), then the gated per-row kernel"),
+                 "k_attn_bf16_main<true, false> (online softmax, per-wave running reference raised lazily), then the gated per-row kernel"),
                 ("bf16_online_softmax", mk(softmax_scale=0.7), PEAK_BF16_MFMA_TFLOPS,
-                 "k_attn_bf16_main<true> on normalised q, k with a softmax scale of 0.7 (beyond the fixed "
+                 "k_attn_bf16_main<true, false> on normalised q, k with a softmax scale of 0.7 (beyond the fixed "
                  "reference's exponent range), then the gated per-row kernel"),
                 ("fp8_qk_norm", mk(attn_dtype=B.ATTN_FP8_E4M3), PEAK_FP8_MFMA_TFLOPS, "k_attn_fp8_bounded"),
                 ("fp8_as_given", mk(attn_dtype=B.ATTN_FP8_E4M3, qk_norm=0), PEAK_FP8_MFMA_TFLOPS,
@@ -504,7 +505,17 @@ def main():
             ms_v = launch_ms(p_v)
             variants[key] = dict(kernel=what, ms_call=ms_v, tflops=attn_flop / (ms_v * 1e-3) / 1e12,
                                  frac_mfma=attn_flop / (ms_v * 1e-3) / 1e12 / peak_v)
-        del zv, yv
+        # the same kernel and launch as bf16_qk_norm with an all-zero q: an identical instruction
+        # stream whose score MFMAs and exponentials toggle no operand bits.  Whatever it gains is
+        # clock (power), not work
+        zq = torch.zeros_like(zv)
+        ms_v = launch_ms(mk(), q=zq)
+        variants["bf16_qk_norm_zero_q"] = dict(
+            kernel="k_attn_bf16_main<false, false> with q = 0 (same instructions, operands that toggle no bits): "
+                   "how much of the kernel's time is the clock the chip holds under this kernel's power draw",
+            ms_call=ms_v, tflops=attn_flop / (ms_v * 1e-3) / 1e12,
+            frac_mfma=attn_flop / (ms_v * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS)
+        del zv, yv, zq
         # the whole stack with the other setting of qk_norm (one step, not part of `value`): with
         # q = k = v = the merged tokens as given, the residual stream doubles per layer and from
         # the third layer on every score lies beyond the range the folded softmax scale resolves,
@@ -528,7 +539,7 @@ def main():
             output_finite=bool(torch.isfinite(x.float()).all().item()))
 
     roof_kernel = ("k_attn_fp8_bounded" if args.attn_dtype == "fp8" and wl_qk_norm else "k_attn_fp8" if args.attn_dtype == "fp8"
-                   else "k_attn_bf16_main<false>" if wl_qk_norm else "k_attn_bf16_main<true>")
+                   else "k_attn_bf16_main<false, false>" if wl_qk_norm else "k_attn_bf16_main<true, false>")
     traffic, traffic_src = measured_traffic(wl.name, args.attn_dtype, roof_kernel)
     out = {
         "metric": "merged global-attn tokens/s @%d frames" % wl.frames,
