@@ -327,15 +327,15 @@ __global__ __launch_bounds__(256) void k_quant_pack_fp8(const uint16_t *__restri
 // accumulation.  Same machinery as the similarity kernel of the matching step: 256 x 256
 // output tiles, both operands pre-packed fragment-major, fetched straight into a 4-stage LDS
 // ring (2 k-steps per stage, 3 stages ahead), fragments read by hand one k-step ahead, 8 waves
-// of 64 rows x 128 columns.  The finished tile is converted to bf16 into LDS (the ring is free
-// by then) and written in 16-byte pieces along the rows; `addend` (optional, shaped like the
-// output) is added to the rounded result on the way out.
+// of 64 rows x 128 columns.  The finished tile goes from the accumulators straight to global
+// memory (bias, optional GELU, one rounding to bf16); `addend` (optional, shaped like the
+// output) is added to the rounded result on the way out.  The ring is free meanwhile, so the
+// next tile's first stages are fetched during the epilogue.
 // `split`: the output is Nout / split row-major blocks of [M, split] one after the other
 // (split = Nout: one plain matrix; split = C for the fused q|k|v projection).
 // PACKED: the output is the activation operand of a following layer with K = Nout and is
 // written in that layer's operand order straight from the accumulators (bf16 fragments, or,
-// with FP8, E4M3 codes quantised with *out_inv while the largest |value| goes to *out_amax);
-// the ring stays free, so the next tile's first stages are fetched during the epilogue.
+// with FP8, E4M3 codes quantised with *out_inv while the largest |value| goes to *out_amax).
 // FP8: the same ring and the same byte traffic per stage, but a stage (two 1 KB units per
 // fragment) is one k-step of 64 for v_mfma_f32_32x32x64_f8f6f4, whose operands are the two
 // units of a fragment side by side in 8 registers: per stage a wave issues 8 MFMAs of twice
@@ -388,7 +388,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int my_rows = by_xcd ? (nt_m - xcd + kXcd - 1) / kXcd : 0;   // row tiles of this XCD
   const int my_tiles = by_xcd ? my_rows * nt_n : n_tiles;
   const int v_step = by_xcd ? per_xcd : (int)gridDim.x;
-  bool primed = false;   // PACKED: the previous tile's epilogue has issued this tile's first stages
+  bool primed = false;   // the previous tile's epilogue has issued this tile's first stages
   int parity = 0;
   for (int v = by_xcd ? (int)(blockIdx.x >> 3) : (int)blockIdx.x; v < my_tiles; v += v_step, parity ^= 1) {
   const int tn = v % nt_n, tm = by_xcd ? (v / nt_n) * kXcd + xcd : v / nt_n;
@@ -441,7 +441,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                                              acc[ai][bi], 0, 0, 0);
   };
 
-  if (PACKED && primed) {
+  if (primed) {
     pf_g = kStages;
     // the stages were issued ahead of the previous epilogue's stores: wait for everything
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -519,35 +519,32 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // nothing may land in LDS any more
   __syncthreads();
 
-  // bias, activation, bf16, into a row-major tile in LDS: row = token, column = output channel.
-  // The weights are the first MFMA operand, so a lane holds one token (column) and, per group
-  // of four accumulator registers, four consecutive output channels: 8-byte LDS writes.  Rows
-  // are 512 bytes with the 16-byte pieces of row m stored at piece ^ (m & 7): the 32 lanes of a
-  // half-wave (32 rows, same channels) then spread over all banks, and a row is still read back
-  // as one contiguous 512 bytes.
-  char *tile = (char *)ring;
+  // Epilogue: bias, activation, bf16, straight from the accumulators to global memory; nothing
+  // goes through LDS, so the next tile's first stages are issued first and land while the
+  // arithmetic runs.  The weights are the first MFMA operand, so a lane holds one token (column)
+  // and, per group of four accumulator registers, four consecutive output channels 8g + 4h .. + 3:
+  // lanes l and l + 32 trade halves (one v_permlane32_swap per register pair: the first operand's
+  // lanes 32-63 against the second operand's lanes 0-31), after which lane l has channels 0-7 and
+  // lane l + 32 channels 8-15 of a run of 16, 16 bytes per lane.
   const float alpha = alpha_p ? *alpha_p : 1.0f;
   int anchor = 0;   // opaque zero: keeps the address arithmetic below inside this tile's epilogue
   asm volatile("" : "+v"(anchor));   // (hoisted out of the tile loop it would stay live through the main loop)
+  if (v + v_step < my_tiles) {
+    const int v2 = v + v_step;
+    f_tn = v2 % nt_n;
+    f_tm = by_xcd ? (v2 / nt_n) * kXcd + xcd : v2 / nt_n;
+    pf_g = 0;
+#pragma unroll
+    for (int i = 0; i < kStages; ++i) fetch();
+    primed = true;
+  } else {
+    primed = false;
+  }
   if constexpr (PACKED) {
     // The output is the next linear layer's activation operand and is written in that kernel's
-    // fragment order straight from the accumulators: out[(row / 32) * KSn + k-step][lane], where
-    // a k-step is 16 of this layer's output channels and lane = row % 32 + 32 * (second 8 of
-    // the 16).  A lane holds, per group of four registers, channels 8g + 4h .. + 3 of its token:
-    // lanes l and l + 32 trade halves (one swap per register pair), after which lane l has
-    // channels 0-7 and lane l + 32 channels 8-15 of the k-step, and a wave stores 1 KB in a row.
-    // Nothing goes through LDS, so the next tile's first stages are issued before the arithmetic.
-    if (v + v_step < my_tiles) {
-      const int v2 = v + v_step;
-      f_tn = v2 % nt_n;
-      f_tm = by_xcd ? (v2 / nt_n) * kXcd + xcd : v2 / nt_n;
-      pf_g = 0;
-#pragma unroll
-      for (int i = 0; i < kStages; ++i) fetch();
-      primed = true;
-    } else {
-      primed = false;
-    }
+    // fragment order: out[(row / 32) * KSn + k-step][lane], where a k-step is 16 of this layer's
+    // output channels and lane = row % 32 + 32 * (second 8 of the 16), which is exactly what the
+    // lanes hold after the swap: a wave stores 1 KB in a row.
     if constexpr (FP8) {
       // E4M3 codes for an FP8 layer with K = Nout (units of 32 rows x 32 channels, lane h * 32 + r
       // holds the 16 codes of channels 32u + 16h .. + 15 of row r): every value is rounded to
@@ -616,47 +613,43 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       }
     continue;
   }
-  const int tok = wd * 64 + (lane & 31) + anchor;
+  // row-major rows of `split` channels: per store instruction a wave writes 32 bytes of each of
+  // 32 rows; the four stores that complete a 128-byte line follow each other
+  const int blk = (tn * kTile) / split, col0 = (tn * kTile) % split;   // a tile never straddles two blocks
+  uint16_t *ob = out + (size_t)blk * M * split + col0 + wn * 128 + 8 * h + anchor;
 #pragma unroll
   for (int b = 0; b < 4; ++b)
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int ch0 = wn * 128 + 32 * b + 8 * g + 4 * h;
-      const f32x4 bv = *(const f32x4 *)(bias_lds + ch0);
+    for (int gp = 0; gp < 2; ++gp) {
+      const int ch0 = wn * 128 + 32 * b + 16 * gp + 4 * h;
+      const f32x4 bv0 = *(const f32x4 *)(bias_lds + ch0), bv1 = *(const f32x4 *)(bias_lds + ch0 + 8);
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
-        const int mrow = tok + 32 * a;
-        float v[4];
+        float v0[4], v1[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          v[i] = FP8 ? acc[a][b][4 * g + i] * alpha + bv[i] : acc[a][b][4 * g + i] + bv[i];
-          if (gelu) v[i] = gelu_erf(v[i]);
+          v0[i] = FP8 ? acc[a][b][8 * gp + i] * alpha + bv0[i] : acc[a][b][8 * gp + i] + bv0[i];
+          v1[i] = FP8 ? acc[a][b][8 * gp + 4 + i] * alpha + bv1[i] : acc[a][b][8 * gp + 4 + i] + bv1[i];
+          if (gelu) {
+            v0[i] = gelu_erf(v0[i]);
+            v1[i] = gelu_erf(v1[i]);
+          }
         }
-        *(u32x2 *)(tile + (size_t)mrow * (kTile * 2) + (((ch0 >> 3) ^ (mrow & 7)) << 4) + ((ch0 & 7) << 1)) =
-            u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        const auto s0 = __builtin_amdgcn_permlane32_swap(pack_bf16(v0[0], v0[1]), pack_bf16(v1[0], v1[1]), false, false);
+        const auto s1 = __builtin_amdgcn_permlane32_swap(pack_bf16(v0[2], v0[3]), pack_bf16(v1[2], v1[3]), false, false);
+        u32x4 t = u32x4{s0[0], s1[0], s0[1], s1[1]};
+        const int64_t m = (int64_t)tm * kTile + wd * 64 + 32 * a + (lane & 31);
+        if (addend) {   // out = addend + (this layer's output, already rounded to bf16): one more rounding
+          const u32x4 y = m < M ? *(const u32x4 *)(addend + (ob - out) + (size_t)m * split + 32 * b + 16 * gp)
+                                : u32x4{0u, 0u, 0u, 0u};
+          t.x = pack_bf16(bf16_lo(t.x) + bf16_lo(y.x), bf16_hi(t.x) + bf16_hi(y.x));
+          t.y = pack_bf16(bf16_lo(t.y) + bf16_lo(y.y), bf16_hi(t.y) + bf16_hi(y.y));
+          t.z = pack_bf16(bf16_lo(t.z) + bf16_lo(y.z), bf16_hi(t.z) + bf16_hi(y.z));
+          t.w = pack_bf16(bf16_lo(t.w) + bf16_lo(y.w), bf16_hi(t.w) + bf16_hi(y.w));
+        }
+        if (m < M) *(u32x4 *)(ob + (size_t)m * split + 32 * b + 16 * gp) = t;
       }
     }
-  __syncthreads();
-  // 16-byte pieces along the rows: 32 per row, 8192 per tile, 16 per thread
-  const int blk = (tn * kTile) / split, col0 = (tn * kTile) % split;   // a tile never straddles two blocks
-  uint16_t *ob = out + (size_t)blk * M * split + col0;
-#pragma unroll 4
-  for (int i = 0; i < 16; ++i) {
-    const int c = i * 512 + tid + anchor, mrow = c >> 5, piece = c & 31;
-    const int64_t m = (int64_t)tm * kTile + mrow;
-    if (m < M) {
-      u32x4 t = *(const u32x4 *)(tile + (size_t)mrow * (kTile * 2) + ((piece ^ (mrow & 7)) << 4));
-      if (addend) {   // out = addend + (this layer's output, already rounded to bf16): one more rounding
-        const u32x4 y = *(const u32x4 *)(addend + (ob - out) + (size_t)m * split + piece * 8);
-        t.x = pack_bf16(bf16_lo(t.x) + bf16_lo(y.x), bf16_hi(t.x) + bf16_hi(y.x));
-        t.y = pack_bf16(bf16_lo(t.y) + bf16_lo(y.y), bf16_hi(t.y) + bf16_hi(y.y));
-        t.z = pack_bf16(bf16_lo(t.z) + bf16_lo(y.z), bf16_hi(t.z) + bf16_hi(y.z));
-        t.w = pack_bf16(bf16_lo(t.w) + bf16_lo(y.w), bf16_hi(t.w) + bf16_hi(y.w));
-      }
-      *(u32x4 *)(ob + (size_t)m * split + piece * 8) = t;
-    }
-  }
-  __syncthreads();   // the transposed tile has been read: the ring may be refilled
   }   // tiles
 }
 
@@ -726,8 +719,6 @@ static int launch_linear(const uint16_t *A, int64_t M, int K, const uint16_t *W,
   if (o.pack_out && (o.addend || split != Nout || (o.fp8 && (!o.out_inv || !o.out_amax)))) return LV_ERR_PARAM;
   if (K % 64 != 0 || Nout % kTile != 0 || split % kTile != 0 || Nout % split != 0) return LV_ERR_SHAPE;
   int rc;
-  // the ring; the epilogue's output tile (256 rows of 512 bytes) has the same size
-  static_assert((size_t)kTile * kTile * 2 <= (size_t)kStages * kStageU4 * 16, "output tile must fit the ring");
   const size_t lds = (size_t)kStages * kStageU4 * 16 + 2 * kTile * sizeof(float);   // + two tiles' bias values
   static std::atomic<uint64_t> lds_done[4];
   if ((rc = allow_dynamic_lds((const void *)k_gemm_bt<false, false>, lds, lds_done[0]))) return rc;
