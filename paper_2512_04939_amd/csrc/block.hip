@@ -379,19 +379,45 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int total = KS >> 1;
   // persistent: one workgroup per CU walks the tiles (a workgroup owns a whole CU's LDS, so a
   // launch per tile would pay a dispatch between any two tiles of a CU)
-  // Workgroup w runs on XCD w % 8.  An XCD takes the row tiles tm = x, x + 8, ... and walks
-  // them with all their column tiles, so an activation tile is fetched into one L2 only and
-  // the 32 workgroups of an XCD share a few row tiles and the weights at any time.
+  // Workgroup w runs on XCD w % 8.  An XCD takes the row tiles tm = x, x + 8, ..., so an
+  // activation tile is fetched into one L2 only.  Its workgroups form a block of Rb row tiles x G
+  // column tiles (8 x 4 with 32 workgroups) that takes one group of G column tiles through all
+  // the XCD's row tiles before it moves to the next group: the G weight tiles of a group (2 MB
+  // at K = 1024) stay in that L2 meanwhile, and an activation tile is shared by G workgroups.
   const int nt_m = n_tiles / nt_n;
   const int xcd = blockIdx.x & (kXcd - 1), per_xcd = (int)gridDim.x >> 3;
-  const bool by_xcd = (gridDim.x & (kXcd - 1)) == 0;
+  const int G = nt_n < 4 ? nt_n : 4, Rb = per_xcd / G;
+  const bool by_xcd = (gridDim.x & (kXcd - 1)) == 0 && Rb >= 1;
   const int my_rows = by_xcd ? (nt_m - xcd + kXcd - 1) / kXcd : 0;   // row tiles of this XCD
-  const int my_tiles = by_xcd ? my_rows * nt_n : n_tiles;
-  const int v_step = by_xcd ? per_xcd : (int)gridDim.x;
+  const int n_rb = by_xcd ? (my_rows + Rb - 1) / Rb : 0, n_cg = (nt_n + G - 1) / G;
+  const int jr = (int)(blockIdx.x >> 3) / G, jc = (int)(blockIdx.x >> 3) % G;
+  const int n_steps = by_xcd ? n_rb * n_cg : (n_tiles + (int)gridDim.x - 1) / (int)gridDim.x;
+  // the first step >= k at which this workgroup has a tile (n_steps if none), and that tile
+  auto next_step = [&](int k, int &tm_, int &tn_) {
+    for (; k < n_steps; ++k) {
+      if (by_xcd) {
+        const int cg = k / n_rb, rb = k - cg * n_rb, lr = rb * Rb + jr, col = cg * G + jc;
+        if (jr < Rb && lr < my_rows && col < nt_n) {
+          tm_ = lr * kXcd + xcd;
+          tn_ = col;
+          break;
+        }
+      } else {
+        const int v = (int)blockIdx.x + k * (int)gridDim.x;
+        if (v < n_tiles) {
+          tm_ = v / nt_n;
+          tn_ = v % nt_n;
+          break;
+        }
+      }
+    }
+    return k;
+  };
   bool primed = false;   // the previous tile's epilogue has issued this tile's first stages
   int parity = 0;
-  for (int v = by_xcd ? (int)(blockIdx.x >> 3) : (int)blockIdx.x; v < my_tiles; v += v_step, parity ^= 1) {
-  const int tn = v % nt_n, tm = by_xcd ? (v / nt_n) * kXcd + xcd : v / nt_n;
+  int tm = 0, tn = 0, tm2 = 0, tn2 = 0, k2 = 0;
+  for (int k = next_step(0, tm, tn); k < n_steps; k = k2, tm = tm2, tn = tn2, parity ^= 1) {
+  k2 = next_step(k + 1, tm2, tn2);
   // this tile's 256 bias values wait in LDS behind the ring (read in the epilogue, many barriers
   // later); two buffers in turn, so a wave still in the previous tile's epilogue reads its own
   float *bias_lds = (float *)(ring + (size_t)kStages * kStageU4) + parity * kTile;
@@ -529,10 +555,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const float alpha = alpha_p ? *alpha_p : 1.0f;
   int anchor = 0;   // opaque zero: keeps the address arithmetic below inside this tile's epilogue
   asm volatile("" : "+v"(anchor));   // (hoisted out of the tile loop it would stay live through the main loop)
-  if (v + v_step < my_tiles) {
-    const int v2 = v + v_step;
-    f_tn = v2 % nt_n;
-    f_tm = by_xcd ? (v2 / nt_n) * kXcd + xcd : v2 / nt_n;
+  if (k2 < n_steps) {
+    f_tn = tn2;
+    f_tm = tm2;
     pf_g = 0;
 #pragma unroll
     for (int i = 0; i < kStages; ++i) fetch();
