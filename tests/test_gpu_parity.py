@@ -840,11 +840,12 @@ def _dev_block_weights(B, w):
 
 
 @pytest.mark.parametrize("n,dim,heads,qk_norm", [(300, 256, 4, 1), (777, 256, 4, 0), (520, 1024, 16, 1),
-                                                 (5000, 1024, 16, 1)])
+                                                 (600, 768, 12, 1), (5000, 1024, 16, 1)])
 def test_global_block(B, n, dim, heads, qk_norm):
     """LN -> qkv projection -> attention -> output projection -> LN -> GELU MLP against the
     oracle; n is ragged against the 256-row tiles, dim 1024 runs 4-16 output tiles per row.
-    With 5000 rows the first MLP layer has 320 tiles, more than one per compute unit, so
+    Dim 768 gives 9, 3 and 12 column tiles (a last column group that is not full) and channel
+    pieces that do not fill the second half of a wave.  With 5000 rows the first MLP layer has 320 tiles, more than one per compute unit, so
     workgroups walk from one tile to the next (the fetches of the next tile are issued ahead of
     the epilogue); with qk_norm 0 the attention output takes the row-major way into the output
     projection, with qk_norm 1 the attention kernel writes that layer's operand itself."""
@@ -895,7 +896,8 @@ def test_global_block_fp8_linear_current_scaling(B, n, dim, heads):
     assert max_rel_err(got, exact) <= 1e-1
 
 
-@pytest.mark.parametrize("n,dim,heads,amps", [(300, 256, 4, (1.5, 0.4, 3.0, 1.0)), (4200, 1024, 16, (1.5, 0.4))])
+@pytest.mark.parametrize("n,dim,heads,amps", [(300, 256, 4, (1.5, 0.4, 3.0, 1.0)), (600, 768, 12, (1.5, 0.4)),
+                                              (4200, 1024, 16, (1.5, 0.4))])
 def test_global_block_fp8_linear_delayed_scaling(B, n, dim, heads, amps):
     """Delayed scaling over several calls with inputs of different range: the scale of a call
     comes from the amaxes the earlier calls recorded (1 in the first call, where most codes
